@@ -1,0 +1,222 @@
+/*
+ * redux_oracle.c -- plain, slow, single-threaded CPU oracle for the arithmetic
+ * reduction R(X) = sum_{i=1..n} x_i (paper Section III, the definition of the
+ * arithmetic reduction).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It exists so that the GPU library can be
+ * checked against something that is obviously correct.  It shares no code,
+ * header, table or helper with the GPU library, and the GPU library never
+ * calls it.  Only the test-suite, the smoke check and the "cpu_baseline" leg
+ * of the benchmark may load it.
+ *
+ * The method of the paper (Section IV-A: two matrix-multiply-accumulate
+ * operations against an all-ones operand, applied hierarchically) only
+ * re-associates the additions of the definition and multiplies by one, so in
+ * exact arithmetic it reaches the plain sum.  The oracle is therefore the
+ * definition written out, in arithmetic wide enough that its own rounding is
+ * far below the tolerance that the GPU result is held to:
+ *
+ *   binary16 input  -> every value is decoded exactly to binary64, then
+ *       summed in binary64 four independent ways:
+ *         serial   : one accumulator, left to right (the "simple loop with a
+ *                    single accumulator" of Section III);
+ *         pairwise : recursive halving with a 128-element serial base case;
+ *         neumaier : Kahan-Babuska compensated serial sum (compensated
+ *                    summation is the remedy named in Section II);
+ *         exact    : every finite binary16 is an integer multiple of 2^-24
+ *                    with |multiple| < 2^41, so the sum of multiples is
+ *                    accumulated exactly in a 128-bit integer (n < 2^86) and
+ *                    converted once.
+ *   int8 input      -> int64 serial sum (exact for n < 2^56).
+ *
+ * Every routine also returns sum |x_i|, which the tolerance for cancelling
+ * sums is stated against.
+ *
+ * Non-finite inputs follow IEEE-754 addition: NaN, or +Inf together with
+ * -Inf, gives NaN; otherwise an infinity dominates.  The exact routine
+ * reports their presence through *nonfinite and leaves them out of the
+ * integer sum.
+ *
+ * Build: gcc -O2 -std=c11 -shared -fPIC -o libredux_oracle.so redux_oracle.c -lm
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_NULL (-1)
+
+/* ---- binary16 decode ---------------------------------------------------- */
+
+/* IEEE-754 binary16: 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits. */
+double redux_oracle_f16_decode(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int f = h & 0x3ff;
+    double v;
+    if (e == 0) {
+        v = ldexp((double)f, -24);            /* zero and subnormals: f * 2^-24 */
+    } else if (e == 31) {
+        v = (f == 0) ? INFINITY : NAN;
+    } else {
+        v = ldexp((double)(1024 + f), e - 25); /* (1 + f/1024) * 2^(e-15) */
+    }
+    return sign ? -v : v;
+}
+
+/* All 65536 decoded values; filled from redux_oracle_f16_decode on first use. */
+static double g_decode[65536];
+static int g_decode_ready = 0;
+
+static const double *decode_table(void)
+{
+    if (!g_decode_ready) {
+        for (uint32_t h = 0; h < 65536u; ++h)
+            g_decode[h] = redux_oracle_f16_decode((uint16_t)h);
+        g_decode_ready = 1;
+    }
+    return g_decode;
+}
+
+/* ---- binary16 sums ------------------------------------------------------ */
+
+/* Section III: one accumulator, elements taken in index order. */
+int redux_oracle_sum_f16_serial(const uint16_t *x, size_t n, double *sum, double *sum_abs)
+{
+    if ((n && !x) || !sum || !sum_abs) return ORACLE_ERR_NULL;
+    const double *t = decode_table();
+    double s = 0.0, a = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        double v = t[x[i]];
+        s += v;
+        a += fabs(v);
+    }
+    *sum = s;
+    *sum_abs = a;
+    return ORACLE_OK;
+}
+
+static void pairwise(const double *t, const uint16_t *x, size_t n, double *s, double *a)
+{
+    if (n <= 128) {
+        double ss = 0.0, aa = 0.0;
+        for (size_t i = 0; i < n; ++i) {
+            double v = t[x[i]];
+            ss += v;
+            aa += fabs(v);
+        }
+        *s = ss;
+        *a = aa;
+        return;
+    }
+    size_t half = n / 2;
+    double s0, a0, s1, a1;
+    pairwise(t, x, half, &s0, &a0);
+    pairwise(t, x + half, n - half, &s1, &a1);
+    *s = s0 + s1;
+    *a = a0 + a1;
+}
+
+/* Primary oracle: binary64 pairwise summation. */
+int redux_oracle_sum_f16(const uint16_t *x, size_t n, double *sum, double *sum_abs)
+{
+    if ((n && !x) || !sum || !sum_abs) return ORACLE_ERR_NULL;
+    pairwise(decode_table(), x, n, sum, sum_abs);
+    return ORACLE_OK;
+}
+
+/* Cross-check: Neumaier's variant of Kahan's compensated summation. */
+int redux_oracle_sum_f16_neumaier(const uint16_t *x, size_t n, double *sum, double *sum_abs)
+{
+    if ((n && !x) || !sum || !sum_abs) return ORACLE_ERR_NULL;
+    const double *t = decode_table();
+    double s = 0.0, c = 0.0;            /* never build this file with -ffast-math */
+    double a = 0.0;
+    int nonfinite = 0;
+    for (size_t i = 0; i < n; ++i) {
+        double v = t[x[i]];
+        if (!isfinite(v)) nonfinite = 1;
+        double tt = s + v;
+        if (fabs(s) >= fabs(v)) c += (s - tt) + v;
+        else                    c += (v - tt) + s;
+        s = tt;
+        a += fabs(v);
+    }
+    /* The compensation term is meaningless (Inf - Inf) once a non-finite value came in. */
+    *sum = nonfinite ? s : s + c;
+    *sum_abs = a;
+    return ORACLE_OK;
+}
+
+/*
+ * Cross-check: exact fixed-point sum in units of 2^-24.
+ * The integer total is returned as hi:lo (two's complement, 128 bits) and
+ * rounded once to binary64 in *sum.  *nonfinite is 1 if an Inf or NaN was
+ * seen (such elements are skipped in the integer sums).
+ */
+int redux_oracle_sum_f16_exact(const uint16_t *x, size_t n, double *sum, double *sum_abs,
+                               int64_t *hi, uint64_t *lo, int *nonfinite)
+{
+    if ((n && !x) || !sum || !sum_abs || !hi || !lo || !nonfinite) return ORACLE_ERR_NULL;
+    __int128 s = 0, a = 0;
+    int nf = 0;
+    for (size_t i = 0; i < n; ++i) {
+        uint16_t h = x[i];
+        int e = (h >> 10) & 0x1f;
+        int64_t f = h & 0x3ff;
+        int64_t units;
+        if (e == 31) { nf = 1; continue; }
+        if (e == 0) units = f;                          /* f * 2^-24 */
+        else        units = (1024 + f) << (e - 1);      /* (1024+f) * 2^(e-25) = ((1024+f) << (e-1)) * 2^-24 */
+        a += units;
+        s += (h & 0x8000) ? -units : units;
+    }
+    *hi = (int64_t)(s >> 64);
+    *lo = (uint64_t)s;
+    /* __int128 -> double conversion rounds to nearest; scaling by 2^-24 is exact. */
+    *sum = ldexp((double)s, -24);
+    *sum_abs = ldexp((double)a, -24);
+    *nonfinite = nf;
+    return ORACLE_OK;
+}
+
+/* ---- int8 sum ----------------------------------------------------------- */
+
+int redux_oracle_sum_i8(const int8_t *x, size_t n, int64_t *sum, int64_t *sum_abs)
+{
+    if ((n && !x) || !sum || !sum_abs) return ORACLE_ERR_NULL;
+    int64_t s = 0, a = 0;
+    for (size_t i = 0; i < n; ++i) {
+        int64_t v = x[i];
+        s += v;
+        a += v < 0 ? -v : v;
+    }
+    *sum = s;
+    *sum_abs = a;
+    return ORACLE_OK;
+}
+
+/* ---- segmented forms: the same sums, one per contiguous segment ---------- */
+
+int redux_oracle_sum_segmented_f16(const uint16_t *x, size_t nseg, size_t seglen,
+                                   double *sum, double *sum_abs)
+{
+    if ((nseg && seglen && !x) || (nseg && (!sum || !sum_abs))) return ORACLE_ERR_NULL;
+    for (size_t s = 0; s < nseg; ++s) {
+        int rc = redux_oracle_sum_f16(x + s * seglen, seglen, &sum[s], &sum_abs[s]);
+        if (rc) return rc;
+    }
+    return ORACLE_OK;
+}
+
+int redux_oracle_sum_segmented_i8(const int8_t *x, size_t nseg, size_t seglen,
+                                  int64_t *sum, int64_t *sum_abs)
+{
+    if ((nseg && seglen && !x) || (nseg && (!sum || !sum_abs))) return ORACLE_ERR_NULL;
+    for (size_t s = 0; s < nseg; ++s) {
+        int rc = redux_oracle_sum_i8(x + s * seglen, seglen, &sum[s], &sum_abs[s]);
+        if (rc) return rc;
+    }
+    return ORACLE_OK;
+}

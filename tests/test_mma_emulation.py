@@ -1,0 +1,100 @@
+"""Pins for the numpy replay of the paper's algorithm (Section IV-A) and its cost model (Section IV-B)."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import mma_reduction as mr
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "cost_model.txt")
+
+
+@pytest.mark.parametrize("m", [2, 4, 16])
+def test_first_mma_gives_row_sums_in_every_column(m):
+    rng = np.random.default_rng(m)
+    g = rng.integers(-50, 50, size=m * m).astype(np.float64)
+    D, Dp = mr.group_reduce(g, m)
+    rows = g.reshape(m, m).sum(axis=1)
+    for j in range(m):
+        assert np.array_equal(D[:, j], rows)          # first worked equation: each column = the m row sums
+    assert np.all(Dp == g.sum())                      # second worked equation: every entry = the group total
+    assert Dp.shape == (m, m)
+
+
+def test_fill_order_last_slot_is_last_element():
+    m = 4
+    g = np.zeros(m * m)
+    g[-1] = 7.0                                       # "A[m,m] is the m^2-th element of the group"
+    D, _ = mr.group_reduce(g, m)
+    assert np.array_equal(D[m - 1], np.full(m, 7.0)) and np.all(D[: m - 1] == 0)
+
+
+@pytest.mark.parametrize("rows,depth", [(16, 32), (16, 64), (32, 16), (4, 4)])
+def test_rectangular_tile(rows, depth):
+    rng = np.random.default_rng(rows * depth)
+    g = rng.integers(-128, 128, size=rows * depth).astype(np.float64)
+    D, Dp = mr.group_reduce(g, rows, depth, cols=16)
+    assert D.shape == (rows, 16)
+    assert np.array_equal(D[:, 0], g.reshape(rows, depth).sum(axis=1))
+    assert np.all(D == D[:, :1]) and np.all(Dp == g.sum())
+
+
+@pytest.mark.parametrize("m", [2, 4, 16])
+def test_zero_padding_of_a_short_group(m):
+    rng = np.random.default_rng(99 + m)
+    for k in range(0, m * m + 1):
+        g = rng.integers(1, 9, size=k).astype(np.float64)
+        _, Dp = mr.group_reduce(g, m)
+        assert np.all(Dp == g.sum())
+
+
+@pytest.mark.parametrize("m", [2, 4, 16])
+@pytest.mark.parametrize("n", [1, 2, 3, 15, 16, 17, 255, 256, 257, 4095, 4096, 4097, 70000])
+def test_hierarchy_reaches_the_plain_sum(m, n):
+    rng = np.random.default_rng(n * 31 + m)
+    x = rng.standard_normal(n).astype(np.float16)
+    got, levels, sizes = mr.reduce_tc(x, m)
+    # every partial sum here is a multiple of 2^-24 below 2^29, so binary64 regrouping is exact
+    assert Fraction(got) == Fraction(oracle.sum_f16_exact(x)[2], 1 << 24)
+    assert levels == mr.expected_levels(n, m * m)
+    for a, b in zip(sizes, sizes[1:]):
+        assert b == -(-a // (m * m))                  # each level divides the problem by m^2
+
+
+def test_hierarchy_on_cdna_tile_and_empty_input():
+    x = np.arange(1, 5001).astype(np.float16)[:2048]
+    got, levels, sizes = mr.reduce_tc(x, 16, 32)
+    assert got == 2048 * 2049 / 2 and levels == 2 and sizes == [2048, 4]
+    assert mr.reduce_tc(np.zeros(0, np.float16), 16) == (0.0, 0, [])
+
+
+def test_expected_levels_against_paper_recurrence():
+    # T_tc(n) = 5 + T_tc(n/m^2), T_tc(m^2) = 5  =>  levels = log_{m^2} n when n is a power of m^2
+    for m in (2, 4, 16):
+        for k in range(1, 6):
+            n = (m * m) ** k
+            assert mr.expected_levels(n, m * m) == k
+            assert mr.expected_levels(n + 1, m * m) == k + 1
+            assert abs(mr.model_steps_tc(n, m) - 5 * k) < 1e-9
+    assert mr.expected_levels(1 << 30, 256) == 4
+
+
+def test_cost_model_values_printed_in_the_paper():
+    rows = [l.split() for l in open(GOLDEN) if l.strip() and not l.startswith("#")]
+    for kind, arg, val in rows:
+        val = float(val)
+        if kind == "speedup":
+            m = int(arg.split("=")[1])
+            assert abs(mr.model_speedup(m) - val) < 1e-12
+            assert mr.model_speedup(m) > 1
+            for n in (1 << 10, 1 << 20, 1 << 30):
+                assert abs(mr.model_steps_classic(n) / mr.model_steps_tc(n, m) - val) < 1e-9
+        elif kind == "steps_tc_at_group_size":
+            m = int(arg.split("=")[1])
+            assert abs(mr.model_steps_tc(m * m, m) - val) < 1e-12
+        elif kind == "steps_classic_per_halving":
+            assert mr.model_steps_classic(2) == val
+        else:
+            raise AssertionError(kind)
