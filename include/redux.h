@@ -1,0 +1,141 @@
+/*
+ * redux.h -- C ABI of libredux: arithmetic reduction of n numbers to one sum on
+ * an AMD MI355X (gfx950), with the additions encoded as chains of
+ * matrix-multiply-accumulate (MMA) operations against an all-ones operand.
+ *
+ * Method: the tensor-core reduction of Section IV-A of "Analyzing GPU Tensor
+ * Core Potential for Fast Reductions" (Carrasco, Vega, Navarro; arXiv
+ * 1903.03640).  The problem solved is the arithmetic reduction of Section III,
+ *      R(X) = sum_{i=1..n} x_i .
+ *
+ * Conventions that hold for every entry point
+ *   - Plain C types only.  No exceptions cross this boundary; every function
+ *     that can fail returns a redux_status (0 = success, negative = error).
+ *   - "device pointer" = memory the current HIP device can read (hipMalloc,
+ *     or PyTorch device tensors).  "host pointer" = ordinary process memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued asynchronously on it; the library never synchronises
+ *     the device.  Results are valid once the stream has reached that point.
+ *   - Inputs are never modified (the paper reduces in place inside X; this
+ *     library does not).  Outputs are written only by kernels.
+ *   - All argument checks happen before the first HIP call, so the error
+ *     returns for bad arguments can be exercised on a machine without a GPU.
+ *   - The library owns one small workspace (block partials + a ticket
+ *     counter, < 128 KiB) per (device, stream); it is created by the first
+ *     call on that stream (one hipMalloc, so not during stream capture) and
+ *     released by redux_shutdown().  Two calls on the same stream are ordered
+ *     by the stream; calls on different streams use different workspaces.
+ *   - Determinism: for a given input, device, variant and launch parameters
+ *     the result is bit-identical from call to call (partials are combined in
+ *     a fixed order; no floating-point atomics).
+ */
+#ifndef REDUX_H
+#define REDUX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element type of the input array. */
+typedef enum {
+    REDUX_F16 = 0, /* IEEE binary16 in, binary32 MMA accumulation, one binary32 result */
+    REDUX_I8  = 1  /* int8 in, int32 MMA accumulation flushed to int64, one int64 result */
+} redux_dtype;
+
+typedef enum {
+    REDUX_OK        =  0,
+    REDUX_ERR_NULL  = -1, /* x is NULL with a non-empty input, or out is NULL */
+    REDUX_ERR_DTYPE = -2, /* dtype is not a redux_dtype */
+    REDUX_ERR_SIZE  = -3, /* nseg*seglen (or the byte count) overflows size_t / exceeds 2^62 */
+    REDUX_ERR_ALIGN = -4, /* x not aligned to its element size, or out not aligned to its result size */
+    REDUX_ERR_HIP   = -5, /* a HIP call failed; see redux_last_hip_error() */
+    REDUX_ERR_NOMEM = -6, /* the workspace could not be allocated */
+    REDUX_ERR_ALIAS = -7, /* out lies inside the input range */
+    REDUX_ERR_PARAM = -8  /* unknown name or out-of-range value in redux_set_param / redux_set_variant */
+} redux_status;
+
+/* Which kernel family computes the sum. */
+typedef enum {
+    REDUX_VARIANT_AUTO    = 0, /* the library's default choice (the measured winner per dtype/shape) */
+    REDUX_VARIANT_MFMA    = 1, /* MMA encoding: data tile x all-ones, accumulator chained through C   */
+    REDUX_VARIANT_CLASSIC = 2  /* per-lane serial accumulation + wavefront tree (Section III)         */
+} redux_variant;
+
+/*
+ * redux_sum -- R(X) = sum of n numbers (Section III, definition of the arithmetic
+ * reduction; computed by the MMA scheme of Section IV-A, or by the classic tree
+ * scheme of Section III when the classic variant is selected).
+ *
+ *   x      device pointer, read only, n contiguous elements of `dtype`; must be
+ *          aligned to the element size only (2 for F16, 1 for I8).  May be NULL iff n == 0.
+ *   n      number of elements; 0 is allowed and yields the empty sum 0.
+ *   dtype  a redux_dtype.
+ *   out    device pointer owned by the caller: one float (F16, 4-byte aligned) or one
+ *          int64_t (I8, 8-byte aligned).  Must not lie inside [x, x + n*elemsize).
+ *   stream hipStream_t or NULL.
+ *
+ * F16: elements past the end of the last MMA tile count as zeros; binary32 partial
+ * sums are combined across wavefronts and blocks in binary64 and rounded once to
+ * binary32.  IEEE semantics for Inf/NaN; subnormal inputs are not flushed.
+ * I8: the result is exact for any n that fits in device memory.
+ */
+int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
+
+/*
+ * redux_sum_segmented -- nseg independent reductions: out[s] = sum_{k<seglen} x[s*seglen + k]
+ * (the same R(X), applied to each array of a batch; the first MMA of Section IV-A
+ * already yields independent row sums).
+ *
+ *   x       device pointer, row-major [nseg][seglen], read only; may be NULL iff nseg*seglen == 0.
+ *   out     device pointer to nseg results (float for F16, int64_t for I8).
+ *   nseg == 0 is a no-op; seglen == 0 writes nseg zeros.
+ */
+int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, void *out, void *stream);
+
+/*
+ * redux_mma_group_probe -- the two MMA steps of Section IV-A on ONE group, with both
+ * result matrices written out (for checking the encoding, not for speed).
+ *
+ *   x      device pointer to `count` elements, count <= 512 (F16: a 16 x 32 operand A,
+ *          filled row by row) or <= 1024 (I8: 16 x 64); missing elements are zeros.
+ *   D      device pointer to 256 results, row-major 16 x 16: D = A x 1 + 0
+ *          (float for F16, int32_t for I8).  Every column holds the 16 row sums of A.
+ *   Dprime device pointer to 256 results, row-major 16 x 16: D' = 1 x D + 0
+ *          (float for F16, double for I8 -- the int32 matrix is widened exactly and the
+ *          second MMA runs in binary64).  Every entry is the sum of the group.
+ */
+int redux_mma_group_probe(const void *x, size_t count, int dtype, void *D, void *Dprime, void *stream);
+
+/* Select the kernel family for subsequent calls (process-wide). Also read once from the
+ * environment variable REDUX_VARIANT = auto | mfma | classic. */
+int redux_set_variant(int variant);
+int redux_get_variant(void);
+
+/*
+ * Launch parameters (process-wide; for tuning and tests).  Names:
+ *   "blocks_per_cu"     1..16   256-thread blocks per compute unit for the flat sum (default 8)
+ *   "seg_blocks_per_cu" 1..16   the same for the segmented sum (default 8)
+ *   "max_grid"          1..16384 upper limit on the number of blocks (default 16384)
+ *   "unroll"            0,1,2,4,8   16-byte loads in flight per lane; 0 = chosen from the size (default 0)
+ *   "nontemporal"       0/1     use non-temporal (streaming) loads (default 1)
+ *   "pipeline"          0/1     issue the next iteration's loads before consuming the current ones (default 0)
+ *   "max_chain"         1..65536 loop iterations between folds of the MMA accumulators into the wide
+ *                               per-wavefront total (bounds binary32 chain length; keeps int32
+ *                               accumulators below 2^31 for any input)
+ * Returns REDUX_ERR_PARAM for an unknown name or a value out of range.
+ */
+int redux_set_param(const char *name, long value);
+long redux_get_param(const char *name); /* LONG_MIN for an unknown name */
+
+const char *redux_strerror(int status);
+int redux_last_hip_error(void); /* raw hipError_t behind the last REDUX_ERR_HIP/NOMEM on this thread */
+void redux_shutdown(void);      /* frees every workspace; the library can be used again afterwards   */
+const char *redux_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REDUX_H */

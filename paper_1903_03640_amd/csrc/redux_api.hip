@@ -1,0 +1,379 @@
+// redux_api.hip -- the C ABI of libredux (see include/redux.h): argument checks, variant and
+// launch-shape selection, workspace ownership, kernel launches.  No compute happens on the host.
+#include "../../include/redux.h"
+#include "redux_kernels.h"
+
+#include <climits>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <utility>
+
+using namespace redux;
+
+namespace {
+
+// ---- process-wide settings --------------------------------------------------------------------
+struct Settings {
+    int variant = REDUX_VARIANT_AUTO;
+    long blocks_per_cu = 8;
+    long seg_blocks_per_cu = 8;
+    long unroll = 0;          // 0 = from the problem size
+    long nontemporal = 1;
+    long pipeline = 0;
+    long max_chain = 256;
+    long max_grid = kMaxGrid;
+};
+Settings g_set;
+std::once_flag g_env_once;
+std::mutex g_mu;
+
+thread_local int t_last_hip = 0;
+
+void read_env()
+{
+    const char *v = std::getenv("REDUX_VARIANT");
+    if (!v) return;
+    if (!std::strcmp(v, "mfma")) g_set.variant = REDUX_VARIANT_MFMA;
+    else if (!std::strcmp(v, "classic")) g_set.variant = REDUX_VARIANT_CLASSIC;
+    else g_set.variant = REDUX_VARIANT_AUTO;
+}
+
+int hip_fail(hipError_t e, int status = REDUX_ERR_HIP)
+{
+    t_last_hip = (int)e;
+    return status;
+}
+
+// ---- per (device, stream) workspace -----------------------------------------------------------
+struct Workspace {
+    u64 *partials = nullptr;    // kMaxGrid slots
+    unsigned *ticket = nullptr; // behind the partials, on its own 256-byte line
+};
+constexpr size_t kTicketOffset = (size_t)kMaxGrid * sizeof(u64);
+constexpr size_t kWorkspaceBytes = kTicketOffset + 256;
+
+std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
+std::map<int, int> g_cus;
+
+int device_cus(int dev, int *cus)
+{
+    auto it = g_cus.find(dev);
+    if (it == g_cus.end()) {
+        int n = 0;
+        hipError_t e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return hip_fail(e);
+        if (n <= 0) n = 1;
+        it = g_cus.emplace(dev, n).first;
+    }
+    *cus = it->second;
+    return REDUX_OK;
+}
+
+int get_workspace(int dev, hipStream_t st, Workspace *out)
+{
+    auto key = std::make_pair(dev, st);
+    auto it = g_ws.find(key);
+    if (it == g_ws.end()) {
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, kWorkspaceBytes);
+        if (e != hipSuccess) return hip_fail(e, REDUX_ERR_NOMEM);
+        Workspace w;
+        w.partials = (u64 *)p;
+        w.ticket = (unsigned *)((char *)p + kTicketOffset);
+        // the ticket must read zero before the first launch; a fill kernel on the caller's
+        // stream keeps the ordering without a device-wide synchronisation
+        hipLaunchKernelGGL(fill_zero_words_kernel, dim3(1), dim3(64), 0, st, w.ticket, 64u);
+        e = hipGetLastError();
+        if (e != hipSuccess) { (void)hipFree(p); return hip_fail(e); }
+        it = g_ws.emplace(key, w).first;
+    }
+    *out = it->second;
+    return REDUX_OK;
+}
+
+// ---- kernel dispatch ----------------------------------------------------------------------------
+template <class F, int U>
+void launch_flat_u(bool nt, bool pipe, unsigned grid, hipStream_t st, const FlatArgs &a)
+{
+    if (nt) {
+        if (pipe) hipLaunchKernelGGL((sum_flat_kernel<F, U, true, true>), dim3(grid), dim3(kBlock), 0, st, a);
+        else      hipLaunchKernelGGL((sum_flat_kernel<F, U, true, false>), dim3(grid), dim3(kBlock), 0, st, a);
+    } else {
+        if (pipe) hipLaunchKernelGGL((sum_flat_kernel<F, U, false, true>), dim3(grid), dim3(kBlock), 0, st, a);
+        else      hipLaunchKernelGGL((sum_flat_kernel<F, U, false, false>), dim3(grid), dim3(kBlock), 0, st, a);
+    }
+}
+
+template <class F>
+void launch_flat(int unroll, bool nt, bool pipe, unsigned grid, hipStream_t st, const FlatArgs &a)
+{
+    switch (unroll) {
+    case 8: launch_flat_u<F, 8>(nt, pipe, grid, st, a); break;
+    case 4: launch_flat_u<F, 4>(nt, pipe, grid, st, a); break;
+    case 2: launch_flat_u<F, 2>(nt, pipe, grid, st, a); break;
+    default: launch_flat_u<F, 1>(nt, pipe, grid, st, a); break;
+    }
+}
+
+template <class F, int U>
+void launch_seg_u(bool nt, unsigned grid, hipStream_t st, const SegArgs &a)
+{
+    if (nt) hipLaunchKernelGGL((sum_segmented_kernel<F, U, true>), dim3(grid), dim3(kBlock), 0, st, a);
+    else    hipLaunchKernelGGL((sum_segmented_kernel<F, U, false>), dim3(grid), dim3(kBlock), 0, st, a);
+}
+
+template <class F>
+void launch_seg(int unroll, bool nt, unsigned grid, hipStream_t st, const SegArgs &a)
+{
+    switch (unroll) {
+    case 8: launch_seg_u<F, 8>(nt, grid, st, a); break;
+    case 4: launch_seg_u<F, 4>(nt, grid, st, a); break;
+    case 2: launch_seg_u<F, 2>(nt, grid, st, a); break;
+    default: launch_seg_u<F, 1>(nt, grid, st, a); break;
+    }
+}
+
+// ---- argument checks shared by the entry points ---------------------------------------------------
+int check_common(const void *x, size_t count, int dtype, const void *out, size_t nout, size_t *elem_size)
+{
+    if (dtype != REDUX_F16 && dtype != REDUX_I8) return REDUX_ERR_DTYPE;
+    const size_t es = dtype == REDUX_F16 ? 2 : 1;
+    const size_t os = dtype == REDUX_F16 ? 4 : 8;
+    if (count > ((size_t)1 << 62)) return REDUX_ERR_SIZE;
+    if (!out && nout) return REDUX_ERR_NULL;
+    if (!x && count) return REDUX_ERR_NULL;
+    if ((uintptr_t)x % es) return REDUX_ERR_ALIGN;
+    if ((uintptr_t)out % os) return REDUX_ERR_ALIGN;
+    if (count && nout) {
+        uintptr_t xb = (uintptr_t)x, xe = xb + count * es;
+        uintptr_t ob = (uintptr_t)out, oe = ob + nout * os;
+        if (ob < xe && xb < oe) return REDUX_ERR_ALIAS;
+    }
+    *elem_size = es;
+    return REDUX_OK;
+}
+
+int effective_variant(int dtype)
+{
+    (void)dtype;
+    int v = g_set.variant;
+    return v == REDUX_VARIANT_AUTO ? REDUX_VARIANT_MFMA : v;
+}
+
+long *param_slot(const char *name, long *lo, long *hi)
+{
+    if (!name) return nullptr;
+    if (!std::strcmp(name, "blocks_per_cu")) { *lo = 1; *hi = 16; return &g_set.blocks_per_cu; }
+    if (!std::strcmp(name, "seg_blocks_per_cu")) { *lo = 1; *hi = 16; return &g_set.seg_blocks_per_cu; }
+    if (!std::strcmp(name, "unroll")) { *lo = 0; *hi = 8; return &g_set.unroll; }
+    if (!std::strcmp(name, "nontemporal")) { *lo = 0; *hi = 1; return &g_set.nontemporal; }
+    if (!std::strcmp(name, "pipeline")) { *lo = 0; *hi = 1; return &g_set.pipeline; }
+    if (!std::strcmp(name, "max_chain")) { *lo = 1; *hi = 65536; return &g_set.max_chain; }
+    if (!std::strcmp(name, "max_grid")) { *lo = 1; *hi = kMaxGrid; return &g_set.max_grid; }
+    return nullptr;
+}
+
+} // namespace
+
+// =====================================================================================================
+extern "C" {
+
+int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
+{
+    std::call_once(g_env_once, read_env);
+    size_t es = 0;
+    int rc = check_common(x, n, dtype, out, 1, &es);
+    if (rc != REDUX_OK) return rc;
+
+    hipStream_t st = (hipStream_t)stream;
+    std::lock_guard<std::mutex> lock(g_mu);
+
+    if (n == 0) {  // the empty sum
+        if (dtype == REDUX_F16) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(1), dim3(64), 0, st, (float *)out, (u64)1);
+        else                    hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(1), dim3(64), 0, st, (i64 *)out, (u64)1);
+        hipError_t e = hipGetLastError();
+        return e == hipSuccess ? REDUX_OK : hip_fail(e);
+    }
+
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
+    Workspace ws;
+    if ((rc = get_workspace(dev, st, &ws)) != REDUX_OK) return rc;
+
+    FlatArgs a;
+    a.run = (es == 2) ? make_run<2>(x, n) : make_run<1>(x, n);
+    a.partials = ws.partials;
+    a.ticket = ws.ticket;
+    a.out = out;
+    a.max_chain = (unsigned)g_set.max_chain;
+
+    // launch shape: as many resident blocks as asked for; the deepest unroll that still
+    // leaves every block at least two iterations
+    u64 gmax = (u64)cus * (u64)g_set.blocks_per_cu;
+    if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+    int unroll = (int)g_set.unroll;
+    if (unroll == 0) {
+        unroll = 8;
+        while (unroll > 1 && a.run.nvec / ((u64)kBlock * unroll) < 2 * gmax) unroll >>= 1;
+    } else if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) {
+        unroll = 1;
+    }
+    u64 nslab = a.run.nvec / ((u64)kBlock * unroll);
+    unsigned grid = (unsigned)(nslab < 1 ? 1 : (nslab < gmax ? nslab : gmax));
+
+    const bool nt = g_set.nontemporal != 0, pipe = g_set.pipeline != 0;
+    const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
+    if (dtype == REDUX_F16) {
+        if (mfma) launch_flat<F16Mfma>(unroll, nt, pipe, grid, st, a);
+        else      launch_flat<F16Classic>(unroll, nt, pipe, grid, st, a);
+    } else {
+        if (mfma) launch_flat<I8Mfma>(unroll, nt, pipe, grid, st, a);
+        else      launch_flat<I8Classic>(unroll, nt, pipe, grid, st, a);
+    }
+    e = hipGetLastError();
+    return e == hipSuccess ? REDUX_OK : hip_fail(e);
+}
+
+int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, void *out, void *stream)
+{
+    std::call_once(g_env_once, read_env);
+    if (dtype != REDUX_F16 && dtype != REDUX_I8) return REDUX_ERR_DTYPE;
+    if (seglen && nseg > ((size_t)1 << 62) / seglen) return REDUX_ERR_SIZE;
+    if (nseg > ((size_t)1 << 59)) return REDUX_ERR_SIZE;
+    size_t es = 0;
+    int rc = check_common(x, nseg * seglen, dtype, out, nseg, &es);
+    if (rc != REDUX_OK) return rc;
+    if (nseg == 0) return REDUX_OK;
+
+    hipStream_t st = (hipStream_t)stream;
+    std::lock_guard<std::mutex> lock(g_mu);
+
+    if (seglen == 0) {
+        unsigned grid = (unsigned)((nseg + 255) / 256);
+        if (dtype == REDUX_F16) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(grid), dim3(256), 0, st, (float *)out, (u64)nseg);
+        else                    hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(grid), dim3(256), 0, st, (i64 *)out, (u64)nseg);
+        hipError_t e = hipGetLastError();
+        return e == hipSuccess ? REDUX_OK : hip_fail(e);
+    }
+
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
+
+    SegArgs a;
+    a.x = (const unsigned char *)x;
+    a.nseg = nseg;
+    a.seglen = seglen;
+    a.out = out;
+    a.max_chain = (unsigned)g_set.max_chain;
+
+    const u64 vec_per_seg = (u64)seglen * es / 16;
+    int unroll = (int)g_set.unroll;
+    if (unroll == 0) unroll = vec_per_seg >= 512 ? 8 : vec_per_seg >= 256 ? 4 : vec_per_seg >= 128 ? 2 : 1;
+    else if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) unroll = 1;
+
+    u64 blocks_needed = (nseg + kWaves - 1) / kWaves;
+    u64 gmax = (u64)cus * (u64)g_set.seg_blocks_per_cu;
+    if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+    unsigned grid = (unsigned)(blocks_needed < gmax ? blocks_needed : gmax);
+
+    const bool nt = g_set.nontemporal != 0;
+    const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
+    if (dtype == REDUX_F16) {
+        if (mfma) launch_seg<F16Mfma>(unroll, nt, grid, st, a);
+        else      launch_seg<F16Classic>(unroll, nt, grid, st, a);
+    } else {
+        if (mfma) launch_seg<I8Mfma>(unroll, nt, grid, st, a);
+        else      launch_seg<I8Classic>(unroll, nt, grid, st, a);
+    }
+    e = hipGetLastError();
+    return e == hipSuccess ? REDUX_OK : hip_fail(e);
+}
+
+int redux_mma_group_probe(const void *x, size_t count, int dtype, void *D, void *Dprime, void *stream)
+{
+    if (dtype != REDUX_F16 && dtype != REDUX_I8) return REDUX_ERR_DTYPE;
+    if (count > (dtype == REDUX_F16 ? 512u : 1024u)) return REDUX_ERR_SIZE;
+    if ((!x && count) || !D || !Dprime) return REDUX_ERR_NULL;
+    if ((uintptr_t)x % (dtype == REDUX_F16 ? 2 : 1) || (uintptr_t)D % 4 || (uintptr_t)Dprime % (dtype == REDUX_F16 ? 4 : 8))
+        return REDUX_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == REDUX_F16)
+        hipLaunchKernelGGL(group_probe_f16_kernel, dim3(1), dim3(64), 0, st, (const unsigned short *)x, (unsigned)count,
+                           (float *)D, (float *)Dprime);
+    else
+        hipLaunchKernelGGL(group_probe_i8_kernel, dim3(1), dim3(64), 0, st, (const signed char *)x, (unsigned)count,
+                           (int *)D, (double *)Dprime);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? REDUX_OK : hip_fail(e);
+}
+
+int redux_set_variant(int variant)
+{
+    std::call_once(g_env_once, read_env);
+    if (variant < REDUX_VARIANT_AUTO || variant > REDUX_VARIANT_CLASSIC) return REDUX_ERR_PARAM;
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_set.variant = variant;
+    return REDUX_OK;
+}
+
+int redux_get_variant(void)
+{
+    std::call_once(g_env_once, read_env);
+    std::lock_guard<std::mutex> lock(g_mu);
+    return g_set.variant;
+}
+
+int redux_set_param(const char *name, long value)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    long lo = 0, hi = 0;
+    long *slot = param_slot(name, &lo, &hi);
+    if (!slot || value < lo || value > hi) return REDUX_ERR_PARAM;
+    if (slot == &g_set.unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return REDUX_ERR_PARAM;
+    *slot = value;
+    return REDUX_OK;
+}
+
+long redux_get_param(const char *name)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    long lo = 0, hi = 0;
+    long *slot = param_slot(name, &lo, &hi);
+    return slot ? *slot : LONG_MIN;
+}
+
+const char *redux_strerror(int status)
+{
+    switch (status) {
+    case REDUX_OK: return "success";
+    case REDUX_ERR_NULL: return "null pointer for a non-empty input or for the output";
+    case REDUX_ERR_DTYPE: return "unknown dtype";
+    case REDUX_ERR_SIZE: return "size overflows or exceeds the supported range";
+    case REDUX_ERR_ALIGN: return "pointer not aligned to its element size";
+    case REDUX_ERR_HIP: return "a HIP call failed (see redux_last_hip_error)";
+    case REDUX_ERR_NOMEM: return "workspace allocation failed";
+    case REDUX_ERR_ALIAS: return "output lies inside the input range";
+    case REDUX_ERR_PARAM: return "unknown parameter name or value out of range";
+    default: return "unknown status";
+    }
+}
+
+int redux_last_hip_error(void) { return t_last_hip; }
+
+void redux_shutdown(void)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (auto &kv : g_ws) (void)hipFree(kv.second.partials);
+    g_ws.clear();
+    g_cus.clear();
+}
+
+const char *redux_version(void) { return "libredux 0.1 (gfx950)"; }
+
+} // extern "C"

@@ -1,0 +1,573 @@
+// redux_kernels.h -- gfx950 (CDNA4) device code of libredux.
+//
+// The reduction of Section IV-A of the paper, re-mapped to the CDNA4 matrix unit:
+//
+//   * a wavefront's coalesced 16-byte-per-lane load (1 KiB) IS the A operand of one
+//     MFMA: 16 rows x 32 binary16 (v_mfma_f32_16x16x32_f16) or 16 rows x 64 int8
+//     (v_mfma_i32_16x16x64_i8).  B is the all-ones constant.  This is the paper's
+//     first MMA, D = A x 1 + C, except that C is not zero but the running D of the
+//     previous tile ("chain"), so no per-group partial ever leaves the registers.
+//     Which element lands in which (row, k) slot does not matter: B is all ones, so
+//     every bijection gives the same set of additions.
+//   * the paper's second MMA, D' = 1 x D, folds the 16 row sums: the accumulator
+//     registers of D are fed back as the B operand of v_mfma_f32_16x16x4_f32 (binary64:
+//     v_mfma_f64_16x16x4_f64) with an all-ones A.  Lane l, register r of a 16x16
+//     accumulator holds D[4*(l/16)+r][l%16]; lane l of a 4x16 B operand holds
+//     B[l/16][l%16]; so register r used as B contributes rows r, 4+r, 8+r, 12+r and four
+//     chained MFMAs (r = 0..3) sum all 16 rows with no data movement between lanes.
+//   * the next level of the paper's hierarchy (partials of all groups -> one value) is one
+//     binary64 two-MMA group reduction over the per-block partials, run by the block that
+//     arrives last (single pass over HBM instead of one kernel per level).
+//
+// The "classic" family is the tree reduction of Section III with Brent's coarsening: each lane
+// accumulates serially, then a DPP / ds_swizzle butterfly combines the 64 lanes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace redux {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned long long u64;
+typedef long long i64;
+
+constexpr int kBlock = 256;          // threads per block: 4 wavefronts of 64
+constexpr int kWaves = kBlock / 64;
+constexpr int kMaxGrid = 16384;      // capacity of the partials array
+
+// ---------------------------------------------------------------------------------------------
+// loads
+// ---------------------------------------------------------------------------------------------
+template <bool NT>
+__device__ __forceinline__ u32x4 load16(const u32x4 *p)
+{
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+// ---------------------------------------------------------------------------------------------
+// cross-lane helpers for the classic family (wave64)
+// ---------------------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+
+constexpr int kQuadXor1 = 0xB1;       // quad_perm [1,0,3,2]
+constexpr int kQuadXor2 = 0x4E;       // quad_perm [2,3,0,1]
+constexpr int kRowHalfMirror = 0x141; // lane i <-> 7-i within each 8
+constexpr int kRowMirror = 0x140;     // lane i <-> 15-i within each 16
+constexpr int kSwizzleXor16 = 0x401F; // ds_swizzle bit mode: and 0x1f, or 0, xor 0x10
+
+__device__ __forceinline__ float wave_sum_f32(float v)
+{
+    // butterfly inside each row of 16 lanes (DPP), then across rows (ds_swizzle, readlane).
+    // Every step adds a lane's value and its partner's, so all lanes of a group hold the
+    // same value afterwards and the result does not depend on which lane reads it.
+    v += __builtin_bit_cast(float, dpp_i32<kQuadXor1>(__builtin_bit_cast(int, v)));
+    v += __builtin_bit_cast(float, dpp_i32<kQuadXor2>(__builtin_bit_cast(int, v)));
+    v += __builtin_bit_cast(float, dpp_i32<kRowHalfMirror>(__builtin_bit_cast(int, v)));
+    v += __builtin_bit_cast(float, dpp_i32<kRowMirror>(__builtin_bit_cast(int, v)));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), kSwizzleXor16));
+    float lo = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+    float hi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+    return lo + hi;
+}
+
+template <int CTRL>
+__device__ __forceinline__ i64 dpp_i64(i64 v)
+{
+    int lo = dpp_i32<CTRL>((int)(u64)v);
+    int hi = dpp_i32<CTRL>((int)((u64)v >> 32));
+    return (i64)(((u64)(unsigned)hi << 32) | (unsigned)lo);
+}
+
+__device__ __forceinline__ i64 wave_sum_i64(i64 v)
+{
+    v += dpp_i64<kQuadXor1>(v);
+    v += dpp_i64<kQuadXor2>(v);
+    v += dpp_i64<kRowHalfMirror>(v);
+    v += dpp_i64<kRowMirror>(v);
+    {
+        int lo = __builtin_amdgcn_ds_swizzle((int)(u64)v, kSwizzleXor16);
+        int hi = __builtin_amdgcn_ds_swizzle((int)((u64)v >> 32), kSwizzleXor16);
+        v += (i64)(((u64)(unsigned)hi << 32) | (unsigned)lo);
+    }
+    i64 a = (i64)(((u64)(unsigned)__builtin_amdgcn_readlane((int)((u64)v >> 32), 0) << 32) |
+                  (unsigned)__builtin_amdgcn_readlane((int)(u64)v, 0));
+    i64 b = (i64)(((u64)(unsigned)__builtin_amdgcn_readlane((int)((u64)v >> 32), 32) << 32) |
+                  (unsigned)__builtin_amdgcn_readlane((int)(u64)v, 32));
+    return a + b;
+}
+
+__device__ __forceinline__ float uniform_f32(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v)));
+}
+
+__device__ __forceinline__ double uniform_f64(double v)
+{
+    u64 b = __builtin_bit_cast(u64, v);
+    unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)b);
+    unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32));
+    return __builtin_bit_cast(double, ((u64)hi << 32) | lo);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel families.  Each one defines
+//   Acc            per-lane accumulator state of the hot loop
+//   Total          wide type that wave, block and grid totals are carried in
+//   Out            type written to the caller's buffer
+//   consume        take one 16-byte vector per lane (one 1-KiB tile per wavefront); u picks the accumulator
+//   fold           reduce Acc to one wave-uniform Total and clear Acc
+//   edge           build a vector holding a single element in slot 0 (zero padding elsewhere)
+// ---------------------------------------------------------------------------------------------
+
+struct F16Mfma {
+    typedef double Total;
+    typedef float Out;
+    static constexpr int kElemSize = 2;
+    static constexpr int kNumAcc = 4;
+    static constexpr bool kMfmaFinish = true;
+    struct Acc { f32x4 d[kNumAcc]; };
+
+    static __device__ __forceinline__ void clear(Acc &c)
+    {
+#pragma unroll
+        for (int i = 0; i < kNumAcc; ++i) c.d[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // first MMA of Section IV-A with the accumulator chained through C:  D <- A x 1 + D
+    static __device__ __forceinline__ void consume(Acc &c, int U, u32x4 v)
+    {
+        const f16x8 ones = {1, 1, 1, 1, 1, 1, 1, 1};
+        c.d[U % kNumAcc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, v), ones,
+                                                                  c.d[U % kNumAcc], 0, 0, 0);
+    }
+    // second MMA: D' <- 1 x D, chained over the four register slices of every accumulator
+    static __device__ __forceinline__ Total fold(Acc &c)
+    {
+        f32x4 dp = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < kNumAcc; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                dp = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, c.d[i][r], dp, 0, 0, 0);
+        clear(c);
+        return (double)uniform_f32(dp[0]);
+    }
+    static __device__ __forceinline__ u32x4 edge(const void *p)
+    {
+        return u32x4{(unsigned)*(const unsigned short *)p, 0u, 0u, 0u};
+    }
+    static __device__ __forceinline__ Out to_out(Total t) { return (float)t; }
+};
+
+struct F16Classic {
+    typedef double Total;
+    typedef float Out;
+    static constexpr int kElemSize = 2;
+    static constexpr bool kMfmaFinish = false;
+    struct Acc { float s[4]; };
+
+    static __device__ __forceinline__ void clear(Acc &c) { c.s[0] = c.s[1] = c.s[2] = c.s[3] = 0.f; }
+    static __device__ __forceinline__ void consume(Acc &c, int U, u32x4 v)
+    {
+        f16x8 h = __builtin_bit_cast(f16x8, v);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) c.s[k & 3] += (float)h[k];
+    }
+    static __device__ __forceinline__ Total fold(Acc &c)
+    {
+        float s = (c.s[0] + c.s[1]) + (c.s[2] + c.s[3]);
+        clear(c);
+        return (double)wave_sum_f32(s);
+    }
+    static __device__ __forceinline__ u32x4 edge(const void *p)
+    {
+        return u32x4{(unsigned)*(const unsigned short *)p, 0u, 0u, 0u};
+    }
+    static __device__ __forceinline__ Out to_out(Total t) { return (float)t; }
+};
+
+struct I8Mfma {
+    typedef i64 Total;
+    typedef i64 Out;
+    static constexpr int kElemSize = 1;
+    static constexpr int kNumAcc = 4;
+    static constexpr bool kMfmaFinish = false;
+    struct Acc { i32x4 d[kNumAcc]; };
+
+    static __device__ __forceinline__ void clear(Acc &c)
+    {
+#pragma unroll
+        for (int i = 0; i < kNumAcc; ++i) c.d[i] = i32x4{0, 0, 0, 0};
+    }
+    static __device__ __forceinline__ void consume(Acc &c, int U, u32x4 v)
+    {
+        const i32x4 ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+        c.d[U % kNumAcc] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, v), ones,
+                                                                 c.d[U % kNumAcc], 0, 0, 0);
+    }
+    // There is no MFMA with int32 inputs.  Every accumulator entry is an int32 and a column of
+    // sixteen of them sums to less than 2^35, so the second MMA runs exactly in binary64.
+    static __device__ __forceinline__ Total fold(Acc &c)
+    {
+        f64x4 dp = {0., 0., 0., 0.};
+#pragma unroll
+        for (int i = 0; i < kNumAcc; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                dp = __builtin_amdgcn_mfma_f64_16x16x4f64(1.0, (double)c.d[i][r], dp, 0, 0, 0);
+        clear(c);
+        return (i64)uniform_f64(dp[0]);
+    }
+    static __device__ __forceinline__ u32x4 edge(const void *p)
+    {
+        return u32x4{(unsigned)*(const unsigned char *)p, 0u, 0u, 0u};
+    }
+    static __device__ __forceinline__ Out to_out(Total t) { return t; }
+};
+
+struct I8Classic {
+    typedef i64 Total;
+    typedef i64 Out;
+    static constexpr int kElemSize = 1;
+    static constexpr bool kMfmaFinish = false;
+    struct Acc { int s[4]; };
+
+    static __device__ __forceinline__ void clear(Acc &c) { c.s[0] = c.s[1] = c.s[2] = c.s[3] = 0; }
+    static __device__ __forceinline__ void consume(Acc &c, int U, u32x4 v)
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) c.s[k] = __builtin_amdgcn_sdot4((int)v[k], 0x01010101, c.s[k], false);
+    }
+    static __device__ __forceinline__ Total fold(Acc &c)
+    {
+        i64 s = ((i64)c.s[0] + (i64)c.s[1]) + ((i64)c.s[2] + (i64)c.s[3]);
+        clear(c);
+        return wave_sum_i64(s);
+    }
+    static __device__ __forceinline__ u32x4 edge(const void *p)
+    {
+        return u32x4{(unsigned)*(const unsigned char *)p, 0u, 0u, 0u};
+    }
+    static __device__ __forceinline__ Out to_out(Total t) { return t; }
+};
+
+// ---------------------------------------------------------------------------------------------
+// geometry of one contiguous run of elements: unaligned head, 16-byte vectors, tail
+// ---------------------------------------------------------------------------------------------
+struct Run {
+    const unsigned char *head; // first element
+    const u32x4 *body;         // first 16-byte aligned vector
+    const unsigned char *tail; // first element after the last whole vector
+    u64 nvec;
+    int nhead, ntail;          // element counts, each < 16 / elemsize
+};
+
+template <int ES>
+__host__ __device__ __forceinline__ Run make_run(const void *x, u64 n)
+{
+    constexpr u64 kPerVec = 16 / ES;
+    Run r;
+    r.head = (const unsigned char *)x;
+    u64 mis = (u64)(uintptr_t)x & 15u;
+    u64 nh = mis ? (16 - mis) / ES : 0;
+    if (nh > n) nh = n;
+    r.nhead = (int)nh;
+    r.body = (const u32x4 *)(r.head + nh * ES);
+    r.nvec = (n - nh) / kPerVec;
+    r.ntail = (int)(n - nh - r.nvec * kPerVec);
+    r.tail = r.head + (nh + r.nvec * kPerVec) * ES;
+    return r;
+}
+
+// head and tail elements, one per lane, each in slot 0 of an otherwise zero vector: a zero-padded tile
+template <class F>
+__device__ __forceinline__ u32x4 edge_vector(const Run &r, int lane)
+{
+    constexpr int kPerVec = 16 / F::kElemSize;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (lane < r.nhead) v = F::edge(r.head + lane * F::kElemSize);
+    else if (lane >= kPerVec && lane - kPerVec < r.ntail) v = F::edge(r.tail + (lane - kPerVec) * F::kElemSize);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// publishing block partials and electing the block that finishes
+// ---------------------------------------------------------------------------------------------
+template <class T>
+__device__ __forceinline__ void store_partial(u64 *slot, T v)
+{
+    __hip_atomic_store(slot, __builtin_bit_cast(u64, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <class T>
+__device__ __forceinline__ T load_partial(const u64 *slot)
+{
+    return __builtin_bit_cast(T, __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// Sum of the grid's partials in a fixed order, by all threads of the calling block.
+// Returns the total in thread 0.
+template <class F>
+__device__ __forceinline__ typename F::Total sum_partials(const u64 *partials, unsigned count,
+                                                          typename F::Total *lds /* kBlock entries */)
+{
+    typedef typename F::Total Total;
+    const unsigned tid = threadIdx.x;
+    if (F::kMfmaFinish) {
+        // The next level of the paper's hierarchy, in binary64, by one wavefront:
+        // first MMA  D <- A x 1 + D with A = 64 partials (16 x 4), chained over all partials;
+        // second MMA D' <- 1 x D.
+        Total total = 0;
+        if (tid < 64) {
+            f64x4 d = {0., 0., 0., 0.};
+            for (unsigned i0 = 0; i0 < count; i0 += 64) {
+                double a = (i0 + tid < count) ? load_partial<double>(partials + i0 + tid) : 0.0;
+                d = __builtin_amdgcn_mfma_f64_16x16x4f64(a, 1.0, d, 0, 0, 0);
+            }
+            f64x4 dp = {0., 0., 0., 0.};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dp = __builtin_amdgcn_mfma_f64_16x16x4f64(1.0, d[r], dp, 0, 0, 0);
+            total = (Total)dp[0];
+        }
+        return total;
+    } else {
+        Total t = 0;
+        for (unsigned i = tid; i < count; i += kBlock) t += load_partial<Total>(partials + i);
+        lds[tid] = t;
+        __syncthreads();
+        for (unsigned off = kBlock / 2; off > 0; off >>= 1) {
+            if (tid < off) lds[tid] += lds[tid + off];
+            __syncthreads();
+        }
+        return lds[0];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// flat sum: one pass over HBM, one partial per block, last block finishes
+// ---------------------------------------------------------------------------------------------
+struct FlatArgs {
+    Run run;
+    u64 *partials;      // kMaxGrid slots
+    unsigned *ticket;   // zero before the launch; the finishing block resets it
+    void *out;
+    unsigned max_chain; // loop iterations between folds
+};
+
+template <class F, int U, bool NT, bool PIPE>
+__global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
+{
+    typedef typename F::Total Total;
+    const unsigned tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u64 G = gridDim.x;
+    constexpr u64 kSlab = (u64)kBlock * U;         // vectors per block iteration
+    const u64 nslab = a.run.nvec / kSlab;
+
+    typename F::Acc acc;
+    F::clear(acc);
+    Total wave_total = 0;
+    unsigned chain = 0;
+
+    u64 s = blockIdx.x;
+    if (PIPE) {
+        if (s < nslab) {
+            u32x4 cur[U];
+            const u32x4 *p = a.run.body + s * kSlab + tid;
+#pragma unroll
+            for (int u = 0; u < U; ++u) cur[u] = load16<NT>(p + u * kBlock);
+            for (s += G; s < nslab; s += G) {
+                u32x4 nxt[U];
+                p = a.run.body + s * kSlab + tid;
+#pragma unroll
+                for (int u = 0; u < U; ++u) nxt[u] = load16<NT>(p + u * kBlock);
+#pragma unroll
+                for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
+#pragma unroll
+                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+                if (++chain >= a.max_chain) { wave_total += F::fold(acc); chain = 0; }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
+        }
+    } else {
+        for (; s < nslab; s += G) {
+            u32x4 cur[U];
+            const u32x4 *p = a.run.body + s * kSlab + tid;
+#pragma unroll
+            for (int u = 0; u < U; ++u) cur[u] = load16<NT>(p + u * kBlock);
+            __builtin_amdgcn_sched_barrier(0);     // issue every load of the slab before the first MMA waits
+#pragma unroll
+            for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
+            if (++chain >= a.max_chain) { wave_total += F::fold(acc); chain = 0; }
+        }
+    }
+
+    // vectors past the last whole slab: one block, lanes past the end contribute zeros
+    if (blockIdx.x == (unsigned)(nslab % G)) {
+        const u64 base = nslab * kSlab;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            u64 idx = base + (u64)u * kBlock + tid;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (idx < a.run.nvec) v = load16<NT>(a.run.body + idx);
+            F::consume(acc, u, v);
+        }
+    }
+    // elements before the first and after the last aligned vector: one zero-padded tile
+    if (blockIdx.x == 0 && wave == 0 && (a.run.nhead | a.run.ntail))
+        F::consume(acc, 0, edge_vector<F>(a.run, (int)lane));
+
+    wave_total += F::fold(acc);
+
+    __shared__ Total lds[kBlock];
+    __shared__ unsigned is_last;
+    if (lane == 0) lds[wave] = wave_total;
+    __syncthreads();
+    if (tid == 0) {
+        Total block_total = ((lds[0] + lds[1]) + (lds[2] + lds[3]));
+        store_partial(a.partials + blockIdx.x, block_total);
+        // release: the partial is visible device-wide before the ticket moves;
+        // acquire: the block that sees the last ticket sees every partial.
+        unsigned t = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (t == gridDim.x - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (is_last) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        Total total = sum_partials<F>(a.partials, gridDim.x, lds);
+        if (tid == 0) {
+            *(typename F::Out *)a.out = F::to_out(total);
+            __hip_atomic_store(a.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// segmented sum: one wavefront per segment, no cross-block step
+// ---------------------------------------------------------------------------------------------
+struct SegArgs {
+    const unsigned char *x;
+    u64 nseg, seglen;   // elements
+    void *out;
+    unsigned max_chain;
+};
+
+template <class F, int U, bool NT>
+__global__ void __launch_bounds__(kBlock) sum_segmented_kernel(SegArgs a)
+{
+    typedef typename F::Total Total;
+    const unsigned lane = threadIdx.x & 63u;
+    const u64 wave_global = (u64)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const u64 nwaves = (u64)gridDim.x * kWaves;
+    constexpr u64 kChunk = 64ull * U;              // vectors per wave iteration
+
+    for (u64 seg = wave_global; seg < a.nseg; seg += nwaves) {
+        const Run run = make_run<F::kElemSize>(a.x + seg * a.seglen * F::kElemSize, a.seglen);
+        typename F::Acc acc;
+        F::clear(acc);
+        Total total = 0;
+        unsigned chain = 0;
+        u64 v0 = 0;
+        for (; v0 + kChunk <= run.nvec; v0 += kChunk) {
+            u32x4 cur[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) cur[u] = load16<NT>(run.body + v0 + (u64)u * 64 + lane);
+#pragma unroll
+            for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
+            if (++chain >= a.max_chain) { total += F::fold(acc); chain = 0; }
+        }
+        if (v0 < run.nvec) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                u64 idx = v0 + (u64)u * 64 + lane;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (idx < run.nvec) v = load16<NT>(run.body + idx);
+                F::consume(acc, u, v);
+            }
+        }
+        if (run.nhead | run.ntail) F::consume(acc, 0, edge_vector<F>(run, (int)lane));
+        total += F::fold(acc);
+        if (lane == 0) ((typename F::Out *)a.out)[seg] = F::to_out(total);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------------------
+template <class T>
+__global__ void fill_zero_kernel(T *out, u64 count)
+{
+    u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) out[i] = (T)0;
+}
+
+__global__ void fill_zero_words_kernel(unsigned *p, unsigned count)
+{
+    unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0u;
+}
+
+// One group through both MMAs of Section IV-A, results written out in matrix order.
+// A is filled row by row: element e of the group sits at A[e / depth][e % depth].
+// Lane l of the A operand holds A[l % 16][(l / 16) * w .. + w) with w = depth / 4 consecutive k.
+__global__ void __launch_bounds__(64) group_probe_f16_kernel(const unsigned short *x, unsigned count,
+                                                             float *D, float *Dp)
+{
+    const unsigned lane = threadIdx.x;
+    const unsigned row = lane & 15u, kgrp = lane >> 4;
+    f16x8 a;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        unsigned e = row * 32u + kgrp * 8u + k;
+        unsigned short bits = e < count ? x[e] : (unsigned short)0;
+        a[k] = __builtin_bit_cast(_Float16, bits);
+    }
+    const f16x8 ones = {1, 1, 1, 1, 1, 1, 1, 1};
+    f32x4 d = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ones, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+    f32x4 dp = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        D[(4 * kgrp + r) * 16 + row] = d[r];       // accumulator register r of lane l is D[4*(l/16)+r][l%16]
+        dp = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, d[r], dp, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) Dp[(4 * kgrp + r) * 16 + row] = dp[r];
+}
+
+__global__ void __launch_bounds__(64) group_probe_i8_kernel(const signed char *x, unsigned count,
+                                                            int *D, double *Dp)
+{
+    const unsigned lane = threadIdx.x;
+    const unsigned row = lane & 15u, kgrp = lane >> 4;
+    i32x4 a;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        unsigned word = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            unsigned e = row * 64u + kgrp * 16u + w * 4 + b;
+            unsigned byte = e < count ? (unsigned)(unsigned char)x[e] : 0u;
+            word |= byte << (8 * b);
+        }
+        a[w] = (int)word;
+    }
+    const i32x4 ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    i32x4 d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, ones, i32x4{0, 0, 0, 0}, 0, 0, 0);
+    f64x4 dp = {0., 0., 0., 0.};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        D[(4 * kgrp + r) * 16 + row] = d[r];
+        dp = __builtin_amdgcn_mfma_f64_16x16x4f64(1.0, (double)d[r], dp, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) Dp[(4 * kgrp + r) * 16 + row] = dp[r];
+}
+
+} // namespace redux

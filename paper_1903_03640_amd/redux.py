@@ -1,0 +1,180 @@
+"""ctypes binding of libredux (see include/redux.h).  Argument marshalling only.
+
+Every arithmetic step runs in the HIP kernels of ``libredux.so``; PyTorch is used
+for device memory and the current stream, nothing else.  There is no CPU
+fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libredux.so")
+
+F16, I8 = 0, 1
+VARIANTS = {"auto": 0, "mfma": 1, "classic": 2}
+
+# every symbol include/redux.h declares
+SYMBOLS = (
+    "redux_sum", "redux_sum_segmented", "redux_mma_group_probe",
+    "redux_set_variant", "redux_get_variant", "redux_set_param", "redux_get_param",
+    "redux_strerror", "redux_last_hip_error", "redux_shutdown", "redux_version",
+)
+
+_lib = None
+
+
+class ReduxError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib.redux_strerror(status).decode() if _lib is not None else "?"
+        hip = _lib.redux_last_hip_error() if _lib is not None and status in (-5, -6) else 0
+        super().__init__("%s failed: %s (status %d%s)" % (where, msg, status, ", hipError %d" % hip if hip else ""))
+
+
+def load():
+    """Load libredux.so (built by __graft_entry__.build()); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libredux.so is not built: run `python __graft_entry__.py` (there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        lib.redux_sum.restype = ci
+        lib.redux_sum.argtypes = [vp, sz, ci, vp, vp]
+        lib.redux_sum_segmented.restype = ci
+        lib.redux_sum_segmented.argtypes = [vp, sz, sz, ci, vp, vp]
+        lib.redux_mma_group_probe.restype = ci
+        lib.redux_mma_group_probe.argtypes = [vp, sz, ci, vp, vp, vp]
+        lib.redux_set_variant.restype = ci
+        lib.redux_set_variant.argtypes = [ci]
+        lib.redux_get_variant.restype = ci
+        lib.redux_get_variant.argtypes = []
+        lib.redux_set_param.restype = ci
+        lib.redux_set_param.argtypes = [ctypes.c_char_p, ctypes.c_long]
+        lib.redux_get_param.restype = ctypes.c_long
+        lib.redux_get_param.argtypes = [ctypes.c_char_p]
+        lib.redux_strerror.restype = ctypes.c_char_p
+        lib.redux_strerror.argtypes = [ci]
+        lib.redux_last_hip_error.restype = ci
+        lib.redux_last_hip_error.argtypes = []
+        lib.redux_shutdown.restype = None
+        lib.redux_shutdown.argtypes = []
+        lib.redux_version.restype = ctypes.c_char_p
+        lib.redux_version.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise ReduxError(status, where)
+
+
+def version() -> str:
+    return load().redux_version().decode()
+
+
+def strerror(status: int) -> str:
+    return load().redux_strerror(status).decode()
+
+
+def set_variant(variant) -> None:
+    v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
+    _check(load().redux_set_variant(v), "redux_set_variant")
+
+
+def get_variant() -> int:
+    return load().redux_get_variant()
+
+
+def set_param(name: str, value: int) -> None:
+    _check(load().redux_set_param(name.encode(), int(value)), "redux_set_param(%s)" % name)
+
+
+def get_param(name: str) -> int:
+    return int(load().redux_get_param(name.encode()))
+
+
+def shutdown() -> None:
+    load().redux_shutdown()
+
+
+# ---- raw calls: pointers and sizes, exactly the C signatures --------------------------------------
+
+def sum_raw(x_ptr: int, n: int, dtype: int, out_ptr: int, stream: int = 0) -> int:
+    return load().redux_sum(x_ptr, n, dtype, out_ptr, stream)
+
+
+def sum_segmented_raw(x_ptr: int, nseg: int, seglen: int, dtype: int, out_ptr: int, stream: int = 0) -> int:
+    return load().redux_sum_segmented(x_ptr, nseg, seglen, dtype, out_ptr, stream)
+
+
+def mma_group_probe_raw(x_ptr: int, count: int, dtype: int, d_ptr: int, dp_ptr: int, stream: int = 0) -> int:
+    return load().redux_mma_group_probe(x_ptr, count, dtype, d_ptr, dp_ptr, stream)
+
+
+# ---- torch conveniences: allocate the output, pass the current stream --------------------------------
+
+def _dtype_of(x) -> int:
+    import torch
+    if x.dtype == torch.float16:
+        return F16
+    if x.dtype == torch.int8:
+        return I8
+    raise TypeError("redux supports float16 and int8 tensors, got %s" % x.dtype)
+
+
+def _prep(x):
+    import torch
+    if not x.is_cuda:
+        raise ValueError("redux needs a device tensor (there is no CPU path)")
+    if not x.is_contiguous():
+        raise ValueError("redux needs a contiguous tensor")
+    return torch.cuda.current_stream(x.device).cuda_stream
+
+
+def sum(x, out=None):
+    """Sum of all elements of a float16 (-> float32) or int8 (-> int64) device tensor; returns a 1-element tensor."""
+    import torch
+    stream = _prep(x)
+    dt = _dtype_of(x)
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32 if dt == F16 else torch.int64, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(sum_raw(x.data_ptr() if x.numel() else 0, x.numel(), dt, out.data_ptr(), stream), "redux_sum")
+    return out
+
+
+def sum_segmented(x, nseg: Optional[int] = None, seglen: Optional[int] = None, out=None):
+    """Per-segment sums of a row-major [nseg][seglen] device tensor; returns nseg results."""
+    import torch
+    stream = _prep(x)
+    dt = _dtype_of(x)
+    if nseg is None or seglen is None:
+        if x.dim() != 2:
+            raise ValueError("give nseg and seglen, or a 2-D tensor")
+        nseg, seglen = x.shape
+    if nseg * seglen != x.numel():
+        raise ValueError("nseg*seglen != numel")
+    if out is None:
+        out = torch.empty(nseg, dtype=torch.float32 if dt == F16 else torch.int64, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(sum_segmented_raw(x.data_ptr() if x.numel() else 0, nseg, seglen, dt,
+                                 out.data_ptr() if nseg else 0, stream), "redux_sum_segmented")
+    return out
+
+
+def mma_group_probe(x):
+    """Both MMA result matrices (D, D') of one group, as 16x16 tensors."""
+    import torch
+    stream = _prep(x)
+    dt = _dtype_of(x)
+    D = torch.empty(16, 16, dtype=torch.float32 if dt == F16 else torch.int32, device=x.device)
+    Dp = torch.empty(16, 16, dtype=torch.float32 if dt == F16 else torch.float64, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(mma_group_probe_raw(x.data_ptr() if x.numel() else 0, x.numel(), dt, D.data_ptr(), Dp.data_ptr(), stream),
+               "redux_mma_group_probe")
+    return D, Dp

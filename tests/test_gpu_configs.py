@@ -1,0 +1,76 @@
+"""The five benchmark configurations at full size, in the launch configuration bench.py times
+(library defaults), against the CPU oracle run over the whole array (about a second each)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1903_03640_amd import redux, workloads
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+_cache = {}
+
+
+def config_data(name):
+    """(host array, device tensor, oracle result) for one configuration; kept for both variants."""
+    if name not in _cache:
+        _cache.clear()                                   # one configuration resident at a time
+        cfg = workloads.CONFIGS[name]
+        host = workloads.make(cfg)
+        if cfg.segmented:
+            want = oracle.sum_segmented_f16(host, cfg.nseg, cfg.seglen)
+        elif cfg.dtype == "f16":
+            want = oracle.sum_f16(host)
+            exact = oracle.sum_f16_exact(host)
+            assert abs(want[0] - exact[0]) <= 1e-12 * exact[1]     # the oracle's own cross-check at full size
+        else:
+            want = oracle.sum_i8(host)
+        _cache[name] = (cfg, host, torch.from_numpy(host).to("cuda:0"), want)
+    return _cache[name]
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _setup():
+    assert torch.cuda.is_available()
+    redux.load()
+    torch.cuda.set_device(0)
+    yield
+    _cache.clear()
+    redux.set_variant("auto")
+
+
+@pytest.mark.parametrize("variant", ["auto", "mfma", "classic"])
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_f16_configs(name, variant):
+    cfg, host, x, (want, want_abs) = config_data(name)
+    redux.set_variant(variant)
+    got = redux.sum(x)
+    torch.cuda.synchronize()
+    got = float(got.item())
+    print("%s %s: gpu %.6f oracle %.6f sum|x| %.6g err/sum|x| %.3g" % (name, variant, got, want, want_abs, abs(got - want) / want_abs))
+    assert abs(got - want) <= TOL * want_abs
+    if name in ("C1", "C3"):                             # non-negative data: the relative form of the bar
+        assert abs(got - want) <= TOL * abs(want)
+
+
+@pytest.mark.parametrize("variant", ["auto", "mfma", "classic"])
+def test_i8_config(variant):
+    cfg, host, x, (want, _) = config_data("C4")
+    redux.set_variant(variant)
+    got = redux.sum(x)
+    torch.cuda.synchronize()
+    assert int(got.item()) == want
+
+
+@pytest.mark.parametrize("variant", ["auto", "mfma", "classic"])
+def test_segmented_config(variant):
+    cfg, host, x, (want, want_abs) = config_data("C5")
+    redux.set_variant(variant)
+    got = redux.sum_segmented(x, cfg.nseg, cfg.seglen)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().astype(np.float64)
+    assert got.shape == (cfg.nseg,)
+    assert np.all(np.abs(got - want) <= TOL * want_abs)
+    print("C5 %s: worst err/sum|x| %.3g" % (variant, np.max(np.abs(got - want) / want_abs)))

@@ -1,0 +1,320 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded inputs.
+
+Bars (written here, as the task states them):
+  * int8 sums: bit-exact (int64).
+  * binary16 sums with binary32 accumulation: |gpu - oracle| <= 1e-4 * |oracle|, or, where the
+    sum cancels, <= 1e-4 * sum|x_i|.  For non-negative data the two coincide; the tests apply
+    the second form, which is never looser than the first on such data.
+Sizes here are ones the oracle finishes in well under a second; the full-size benchmark
+configurations are in test_gpu_configs.py.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import mma_reduction as mr
+from paper_1903_03640_amd import redux, workloads
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+VARIANTS = ("mfma", "classic")
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    redux.load()
+    torch.cuda.set_device(0)
+    yield torch.device("cuda:0")
+    redux.set_variant("auto")
+
+
+@pytest.fixture(autouse=True)
+def default_params():
+    yield
+    for name, val in (("unroll", 0), ("nontemporal", 1), ("pipeline", 0), ("max_chain", 256),
+                      ("max_grid", 16384), ("blocks_per_cu", 8), ("seg_blocks_per_cu", 8)):
+        redux.set_param(name, val)
+    redux.set_variant("auto")
+
+
+def to_dev(a, dev, offset_elems=0):
+    """Copy a host array to the device; with an offset the data starts that many elements past
+    a 256-byte aligned allocation, so the base pointer is deliberately misaligned."""
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if offset_elems == 0:
+        return t.to(dev)
+    buf = torch.empty(t.numel() + offset_elems, dtype=t.dtype, device=dev)
+    view = buf[offset_elems:]
+    view.copy_(t)
+    return view
+
+
+def gpu_sum(x, variant):
+    redux.set_variant(variant)
+    out = redux.sum(x)
+    torch.cuda.synchronize()
+    return out.item()
+
+
+def check_f16(got, x_host):
+    want, want_abs = oracle.sum_f16(x_host)
+    if math.isnan(want):
+        assert math.isnan(got)
+    elif math.isinf(want):
+        assert got == want
+    else:
+        assert abs(got - want) <= TOL * want_abs, (got, want, want_abs)
+        if want_abs == 0:
+            assert got == 0.0
+
+
+# ---- the two MMA steps on one group (first and second worked equations of Section IV-A) -------------
+
+@pytest.mark.parametrize("count", [0, 1, 31, 32, 33, 256, 511, 512])
+def test_group_probe_f16(dev, count):
+    rng = np.random.default_rng(count)
+    g = rng.integers(-8, 9, size=count).astype(np.float16)          # small integers: binary32 sums are exact
+    D, Dp = redux.mma_group_probe(to_dev(g, dev) if count else torch.empty(0, dtype=torch.float16, device=dev))
+    torch.cuda.synchronize()
+    D, Dp = D.cpu().numpy().astype(np.float64), Dp.cpu().numpy().astype(np.float64)
+    eD, eDp = mr.group_reduce(g, 16, 32, cols=16)
+    assert np.array_equal(D, eD)               # row-major fill; every column = the 16 row sums
+    assert np.array_equal(Dp, eDp)             # every entry = the group total
+    assert np.all(D == D[:, :1]) and np.all(Dp == Dp[0, 0])
+
+
+def test_group_probe_f16_random_values(dev):
+    g = workloads.normal_f16(7, 512)
+    D, Dp = redux.mma_group_probe(to_dev(g, dev))
+    torch.cuda.synchronize()
+    eD, eDp = mr.group_reduce(g, 16, 32, cols=16)
+    absrow = np.abs(g.astype(np.float64)).reshape(16, 32).sum(axis=1)
+    assert np.all(np.abs(D.cpu().numpy() - eD) <= 1e-6 * absrow[:, None])
+    assert np.all(np.abs(Dp.cpu().numpy() - eDp) <= 1e-6 * absrow.sum())
+
+
+@pytest.mark.parametrize("count", [0, 1, 63, 64, 65, 1023, 1024])
+def test_group_probe_i8(dev, count):
+    g = workloads.uniform_i8(count + 1, count)
+    D, Dp = redux.mma_group_probe(to_dev(g, dev) if count else torch.empty(0, dtype=torch.int8, device=dev))
+    torch.cuda.synchronize()
+    eD, eDp = mr.group_reduce(g, 16, 64, cols=16)
+    assert np.array_equal(D.cpu().numpy().astype(np.float64), eD)
+    assert np.array_equal(Dp.cpu().numpy(), eDp)
+
+
+# ---- flat sums: sizes around every boundary of the tiling ----------------------------------------------
+
+EDGE_N = [0, 1, 2, 7, 8, 9, 15, 16, 17, 63, 64, 65, 511, 512, 513, 1023, 1024, 1025, 2047, 2048, 2049,
+          4095, 4096, 4097, 65535, 65536, 65537, (1 << 20) - 1, 1 << 20, (1 << 20) + 1,
+          256 * 8 * 8 * 5 + 3, 3 * (1 << 20) + 777]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("n", EDGE_N)
+def test_flat_f16_edge_sizes(dev, variant, n):
+    x = workloads.normal_f16(100 + n % 97, n)
+    got = gpu_sum(to_dev(x, dev) if n else torch.empty(0, dtype=torch.float16, device=dev), variant)
+    check_f16(got, x)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("n", EDGE_N)
+def test_flat_i8_edge_sizes(dev, variant, n):
+    x = workloads.uniform_i8(200 + n % 89, n)
+    got = gpu_sum(to_dev(x, dev) if n else torch.empty(0, dtype=torch.int8, device=dev), variant)
+    assert got == oracle.sum_i8(x)[0]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_flat_misaligned_base(dev, variant):
+    for off in range(1, 8):
+        for n in (1, 5, 8, 13, 517, 70001):
+            x = workloads.uniform_f16(off, n, symmetric=True)
+            check_f16(gpu_sum(to_dev(x, dev, off), variant), x)
+    for off in range(1, 16):
+        for n in (1, 14, 16, 31, 1031, 70001):
+            x = workloads.uniform_i8(off, n)
+            assert gpu_sum(to_dev(x, dev, off), variant) == oracle.sum_i8(x)[0]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
+@pytest.mark.parametrize("pipeline", [0, 1])
+@pytest.mark.parametrize("nontemporal", [0, 1])
+def test_flat_every_launch_shape(dev, variant, unroll, pipeline, nontemporal):
+    redux.set_param("unroll", unroll)
+    redux.set_param("pipeline", pipeline)
+    redux.set_param("nontemporal", nontemporal)
+    n = 5 * (1 << 20) + 12345
+    x = workloads.uniform_f16(9, n)
+    check_f16(gpu_sum(to_dev(x, dev), variant), x)
+    xi = workloads.uniform_i8(9, n)
+    assert gpu_sum(to_dev(xi, dev), variant) == oracle.sum_i8(xi)[0]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("max_chain,max_grid", [(1, 16384), (3, 16384), (256, 1), (2, 3), (65536, 7)])
+def test_flat_chain_folds_and_small_grids(dev, variant, max_chain, max_grid):
+    redux.set_param("max_chain", max_chain)
+    redux.set_param("max_grid", max_grid)
+    n = (1 << 22) + 4321
+    x = workloads.normal_f16(5, n)
+    check_f16(gpu_sum(to_dev(x, dev), variant), x)
+    xi = workloads.uniform_i8(5, n)
+    assert gpu_sum(to_dev(xi, dev), variant) == oracle.sum_i8(xi)[0]
+
+
+# ---- closed forms, through the GPU ---------------------------------------------------------------------
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_flat_closed_forms(dev, variant):
+    for n in (1, 1000, 1 << 20, (1 << 24) - 3):
+        assert gpu_sum(torch.ones(n, dtype=torch.float16, device=dev), variant) == float(n)
+        assert gpu_sum(torch.ones(n, dtype=torch.int8, device=dev), variant) == n
+        assert gpu_sum(torch.full((n,), -128, dtype=torch.int8, device=dev), variant) == -128 * n
+        assert gpu_sum(torch.full((n,), 127, dtype=torch.int8, device=dev), variant) == 127 * n
+    n = (1 << 22) + 777
+    i = np.arange(n, dtype=np.int64)
+    ramp = ((i % 2048) + 1).astype(np.float16)
+    q, r = divmod(n, 2048)
+    expect = q * (2048 * 2049 // 2) + r * (r + 1) // 2
+    got = gpu_sum(to_dev(ramp, dev), variant)
+    assert abs(got - expect) <= TOL * expect
+    iramp = ((i % 256) - 128).astype(np.int8)
+    q, r = divmod(n, 256)
+    assert gpu_sum(to_dev(iramp, dev), variant) == -128 * q + sum(k - 128 for k in range(r))
+    alt = np.full(n, 0.333251953125, dtype=np.float16)
+    alt[1::2] *= -1
+    got = gpu_sum(to_dev(alt, dev), variant)
+    assert abs(got - 0.333251953125) <= TOL * 0.333251953125 * n
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_flat_subnormals_extremes_and_nonfinite(dev, variant):
+    n = (1 << 20) + 5
+    sub = np.full(n, 2.0 ** -24, dtype=np.float16)                 # smallest subnormal: must not be flushed
+    got = gpu_sum(to_dev(sub, dev), variant)
+    assert abs(got - n * 2.0 ** -24) <= TOL * n * 2.0 ** -24
+    big = np.full(n, 65504.0, dtype=np.float16)
+    got = gpu_sum(to_dev(big, dev), variant)
+    assert abs(got - 65504.0 * n) <= TOL * 65504.0 * n
+    big[::2] = -65504.0
+    check_f16(gpu_sum(to_dev(big, dev), variant), big)
+    base = workloads.uniform_f16(1, 100000)
+    for pos in (0, 7, 99999, 51234):
+        for vals, want in (((np.inf,), math.inf), ((-np.inf,), -math.inf), ((np.nan,), math.nan),
+                           ((np.inf, -np.inf), math.nan), ((np.inf, np.inf), math.inf)):
+            x = base.copy()
+            for k, v in enumerate(vals):
+                x[(pos + 4097 * k) % x.size] = v
+            got = gpu_sum(to_dev(x, dev), variant)
+            assert (math.isnan(got) if math.isnan(want) else got == want), (pos, vals, got)
+
+
+def test_variants_agree_and_runs_are_bit_identical(dev):
+    n = (1 << 23) + 99
+    x = to_dev(workloads.normal_f16(21, n), dev)
+    xi = to_dev(workloads.uniform_i8(21, n), dev)
+    res = {}
+    for variant in VARIANTS:
+        redux.set_variant(variant)
+        outs = torch.empty(300, dtype=torch.float32, device=dev)
+        outi = torch.empty(300, dtype=torch.int64, device=dev)
+        for k in range(300):
+            redux.sum(x, out=outs[k:k + 1])
+            redux.sum(xi, out=outi[k:k + 1])
+        torch.cuda.synchronize()
+        outs, outi = outs.cpu().numpy(), outi.cpu().numpy()
+        assert np.all(outs.view(np.uint32) == outs.view(np.uint32)[0])   # same bits every launch
+        assert np.all(outi == outi[0])
+        res[variant] = (float(outs[0]), int(outi[0]))
+    want_abs = oracle.sum_f16(x.cpu().numpy())[1]
+    assert abs(res["mfma"][0] - res["classic"][0]) <= 2 * TOL * want_abs
+    assert res["mfma"][1] == res["classic"][1]
+
+
+def test_two_streams_do_not_share_a_workspace(dev):
+    n = (1 << 22) + 1
+    xa = to_dev(workloads.uniform_f16(31, n), dev)
+    xb = to_dev(workloads.uniform_f16(32, n), dev)
+    wa, wb = oracle.sum_f16(xa.cpu().numpy()), oracle.sum_f16(xb.cpu().numpy())
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    oa = torch.empty(50, dtype=torch.float32, device=dev)
+    ob = torch.empty(50, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    for k in range(50):
+        with torch.cuda.stream(sa):
+            redux.sum(xa, out=oa[k:k + 1])
+        with torch.cuda.stream(sb):
+            redux.sum(xb, out=ob[k:k + 1])
+    torch.cuda.synchronize()
+    assert np.all(np.abs(oa.cpu().numpy().astype(np.float64) - wa[0]) <= TOL * wa[1])
+    assert np.all(np.abs(ob.cpu().numpy().astype(np.float64) - wb[0]) <= TOL * wb[1])
+
+
+# ---- segmented sums ------------------------------------------------------------------------------------
+
+SEG_SHAPES = [(1, 1), (3, 7), (5, 8), (64, 9), (17, 31), (1000, 33), (257, 512), (100, 513), (64, 4096),
+              (33, 4099), (7, 65536 + 5), (2, (1 << 20) + 3), (4097, 64), (1, 12345)]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("nseg,seglen", SEG_SHAPES)
+def test_segmented_f16(dev, variant, nseg, seglen):
+    x = workloads.uniform_f16(nseg + seglen, nseg * seglen, symmetric=True)
+    redux.set_variant(variant)
+    got = redux.sum_segmented(to_dev(x, dev), nseg, seglen)
+    torch.cuda.synchronize()
+    want, want_abs = oracle.sum_segmented_f16(x, nseg, seglen)
+    assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("nseg,seglen", SEG_SHAPES)
+def test_segmented_i8(dev, variant, nseg, seglen):
+    x = workloads.uniform_i8(nseg + seglen, nseg * seglen)
+    redux.set_variant(variant)
+    got = redux.sum_segmented(to_dev(x, dev, 3), nseg, seglen)      # misaligned base as well
+    torch.cuda.synchronize()
+    want, _ = oracle.sum_segmented_i8(x, nseg, seglen)
+    assert np.array_equal(got.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_segmented_degenerate(dev, variant):
+    redux.set_variant(variant)
+    out = torch.full((5,), 7.0, dtype=torch.float32, device=dev)
+    redux.sum_segmented(torch.empty(0, dtype=torch.float16, device=dev), 5, 0, out=out)     # empty segments -> zeros
+    outi = torch.full((5,), 7, dtype=torch.int64, device=dev)
+    redux.sum_segmented(torch.empty(0, dtype=torch.int8, device=dev), 5, 0, out=outi)
+    torch.cuda.synchronize()
+    assert np.all(out.cpu().numpy() == 0) and np.all(outi.cpu().numpy() == 0)
+    assert redux.sum_segmented(torch.empty(0, dtype=torch.float16, device=dev), 0, 9).numel() == 0
+    # segmented result adds up to the flat sum over the same buffer (ints: exactly)
+    x = to_dev(workloads.uniform_i8(77, 300 * 1000), dev)
+    seg = redux.sum_segmented(x, 300, 1000)
+    flat = redux.sum(x)
+    torch.cuda.synchronize()
+    assert int(seg.sum().item()) == flat.item()
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_segmented_params(dev, variant):
+    x = workloads.normal_f16(3, 513 * 4100)
+    want, want_abs = oracle.sum_segmented_f16(x, 513, 4100)
+    xd = to_dev(x, dev)
+    redux.set_variant(variant)
+    for unroll in (1, 2, 4, 8):
+        for max_chain, max_grid in ((1, 16384), (256, 2)):
+            redux.set_param("unroll", unroll)
+            redux.set_param("max_chain", max_chain)
+            redux.set_param("max_grid", max_grid)
+            got = redux.sum_segmented(xd, 513, 4100)
+            torch.cuda.synchronize()
+            assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
