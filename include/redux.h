@@ -109,6 +109,14 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
  */
 int redux_mma_group_probe(const void *x, size_t count, int dtype, void *D, void *Dprime, void *stream);
 
+/*
+ * redux_calibration_copy -- plain device-to-device copy of nbytes (a multiple of 16; both pointers
+ * 16-byte aligned) by a 16-byte-per-lane kernel.  Not part of the reduction: it is the kernel of
+ * exactly known traffic (nbytes read, nbytes written) against which hardware byte counters are
+ * calibrated when the reduction's HBM traffic is measured.
+ */
+int redux_calibration_copy(void *dst, const void *src, size_t nbytes, void *stream);
+
 /* Select the kernel family for subsequent calls (process-wide). Also read once from the
  * environment variable REDUX_VARIANT = auto | mfma | classic. */
 int redux_set_variant(int variant);
@@ -116,12 +124,19 @@ int redux_get_variant(void);
 
 /*
  * Launch parameters (process-wide; for tuning and tests).  Names:
- *   "blocks_per_cu"     1..16   256-thread blocks per compute unit for the flat sum (default 8)
- *   "seg_blocks_per_cu" 1..16   the same for the segmented sum (default 8)
+ *   "blocks_per_cu"     1..16   256-thread blocks per compute unit for the flat sum (default 1)
+ *   "seg_blocks_per_cu" 0..16   the same for the segmented sum; 0 = from the segment length (default 0)
  *   "max_grid"          1..16384 upper limit on the number of blocks (default 16384)
  *   "unroll"            0,1,2,4,8   16-byte loads in flight per lane; 0 = chosen from the size (default 0)
  *   "nontemporal"       0/1     use non-temporal (streaming) loads (default 1)
  *   "pipeline"          0/1     issue the next iteration's loads before consuming the current ones (default 0)
+ *   "layout"            0..2    which part of the array a block reads: 0 = blocks interleaved over the
+ *                               whole array, 1 = one contiguous share per block, 2 = one contiguous
+ *                               eighth per accelerator die, interleaved among that die's blocks (default 2)
+ *   "finish"            -1..2   how block partials become the result: 0/1 = the block that arrives last
+ *                               sums them in the same kernel (0: acquire+release on every block's ticket,
+ *                               1: release only, acquire in the last block), 2 = a second one-block kernel
+ *                               on the same stream, -1 = chosen from the grid size (default -1)
  *   "max_chain"         1..65536 loop iterations between folds of the MMA accumulators into the wide
  *                               per-wavefront total (bounds binary32 chain length; keeps int32
  *                               accumulators below 2^31 for any input)

@@ -17,13 +17,15 @@ namespace {
 // ---- process-wide settings --------------------------------------------------------------------
 struct Settings {
     int variant = REDUX_VARIANT_AUTO;
-    long blocks_per_cu = 8;
-    long seg_blocks_per_cu = 8;
+    long blocks_per_cu = 1;
+    long seg_blocks_per_cu = 0;   // 0 = from the segment length
     long unroll = 0;          // 0 = from the problem size
     long nontemporal = 1;
     long pipeline = 0;
     long max_chain = 256;
     long max_grid = kMaxGrid;
+    long layout = 2;
+    long finish = -1;             // -1 = from the grid size
 };
 Settings g_set;
 std::once_flag g_env_once;
@@ -166,12 +168,14 @@ long *param_slot(const char *name, long *lo, long *hi)
 {
     if (!name) return nullptr;
     if (!std::strcmp(name, "blocks_per_cu")) { *lo = 1; *hi = 16; return &g_set.blocks_per_cu; }
-    if (!std::strcmp(name, "seg_blocks_per_cu")) { *lo = 1; *hi = 16; return &g_set.seg_blocks_per_cu; }
+    if (!std::strcmp(name, "seg_blocks_per_cu")) { *lo = 0; *hi = 16; return &g_set.seg_blocks_per_cu; }
     if (!std::strcmp(name, "unroll")) { *lo = 0; *hi = 8; return &g_set.unroll; }
     if (!std::strcmp(name, "nontemporal")) { *lo = 0; *hi = 1; return &g_set.nontemporal; }
     if (!std::strcmp(name, "pipeline")) { *lo = 0; *hi = 1; return &g_set.pipeline; }
     if (!std::strcmp(name, "max_chain")) { *lo = 1; *hi = 65536; return &g_set.max_chain; }
     if (!std::strcmp(name, "max_grid")) { *lo = 1; *hi = kMaxGrid; return &g_set.max_grid; }
+    if (!std::strcmp(name, "layout")) { *lo = 0; *hi = 2; return &g_set.layout; }
+    if (!std::strcmp(name, "finish")) { *lo = -1; *hi = 2; return &g_set.finish; }
     return nullptr;
 }
 
@@ -210,20 +214,26 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
     a.ticket = ws.ticket;
     a.out = out;
     a.max_chain = (unsigned)g_set.max_chain;
+    a.layout = (int)g_set.layout;
+    a.finish = (int)g_set.finish;
 
-    // launch shape: as many resident blocks as asked for; the deepest unroll that still
-    // leaves every block at least two iterations
+    // Launch shape.  Measured on MI355X: read bandwidth peaks with about 8 MiB in flight
+    // (one 256-thread block per compute unit, eight 16-byte loads per lane) and drops by
+    // several percent when more blocks are resident.  Small inputs keep the deep unroll as long
+    // as that leaves 64 blocks, so that they finish in one kernel (see `finish` below).
     u64 gmax = (u64)cus * (u64)g_set.blocks_per_cu;
     if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
     int unroll = (int)g_set.unroll;
     if (unroll == 0) {
+        const u64 want = gmax < 64 ? gmax : 64;
         unroll = 8;
-        while (unroll > 1 && a.run.nvec / ((u64)kBlock * unroll) < 2 * gmax) unroll >>= 1;
-    } else if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) {
-        unroll = 1;
+        while (unroll > 1 && a.run.nvec / ((u64)kBlock * unroll) < want) unroll >>= 1;
     }
     u64 nslab = a.run.nvec / ((u64)kBlock * unroll);
     unsigned grid = (unsigned)(nslab < 1 ? 1 : (nslab < gmax ? nslab : gmax));
+    // A second tiny kernel sums the partials faster than a device-wide release per block
+    // once there are many blocks; a handful of blocks finish in the same kernel.
+    if (a.finish < 0) a.finish = grid >= 128 ? 2 : 1;
 
     const bool nt = g_set.nontemporal != 0, pipe = g_set.pipeline != 0;
     const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
@@ -235,7 +245,18 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
         else      launch_flat<I8Classic>(unroll, nt, pipe, grid, st, a);
     }
     e = hipGetLastError();
-    return e == hipSuccess ? REDUX_OK : hip_fail(e);
+    if (e != hipSuccess) return hip_fail(e);
+    if (a.finish == 2) {
+        if (dtype == REDUX_F16) {
+            if (mfma) hipLaunchKernelGGL(finish_kernel<F16Mfma>, dim3(1), dim3(kBlock), 0, st, a.partials, grid, out);
+            else      hipLaunchKernelGGL(finish_kernel<F16Classic>, dim3(1), dim3(kBlock), 0, st, a.partials, grid, out);
+        } else {
+            hipLaunchKernelGGL(finish_kernel<I8Classic>, dim3(1), dim3(kBlock), 0, st, a.partials, grid, out);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return REDUX_OK;
 }
 
 int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, void *out, void *stream)
@@ -272,23 +293,24 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     a.out = out;
     a.max_chain = (unsigned)g_set.max_chain;
 
+    // one wavefront per segment; loads in flight per lane x resident blocks per compute unit = 8
     const u64 vec_per_seg = (u64)seglen * es / 16;
     int unroll = (int)g_set.unroll;
-    if (unroll == 0) unroll = vec_per_seg >= 512 ? 8 : vec_per_seg >= 256 ? 4 : vec_per_seg >= 128 ? 2 : 1;
-    else if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) unroll = 1;
+    if (unroll == 0) unroll = vec_per_seg >= 256 ? 4 : vec_per_seg >= 128 ? 2 : 1;
+    long bpc = g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 8 / unroll;
 
     u64 blocks_needed = (nseg + kWaves - 1) / kWaves;
-    u64 gmax = (u64)cus * (u64)g_set.seg_blocks_per_cu;
+    u64 gmax = (u64)cus * (u64)bpc;
     if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
     unsigned grid = (unsigned)(blocks_needed < gmax ? blocks_needed : gmax);
 
     const bool nt = g_set.nontemporal != 0;
     const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
     if (dtype == REDUX_F16) {
-        if (mfma) launch_seg<F16Mfma>(unroll, nt, grid, st, a);
+        if (mfma) launch_seg<F16MfmaSeg>(unroll, nt, grid, st, a);
         else      launch_seg<F16Classic>(unroll, nt, grid, st, a);
     } else {
-        if (mfma) launch_seg<I8Mfma>(unroll, nt, grid, st, a);
+        if (mfma) launch_seg<I8MfmaSeg>(unroll, nt, grid, st, a);
         else      launch_seg<I8Classic>(unroll, nt, grid, st, a);
     }
     e = hipGetLastError();
@@ -310,6 +332,23 @@ int redux_mma_group_probe(const void *x, size_t count, int dtype, void *D, void 
         hipLaunchKernelGGL(group_probe_i8_kernel, dim3(1), dim3(64), 0, st, (const signed char *)x, (unsigned)count,
                            (int *)D, (double *)Dprime);
     hipError_t e = hipGetLastError();
+    return e == hipSuccess ? REDUX_OK : hip_fail(e);
+}
+
+int redux_calibration_copy(void *dst, const void *src, size_t nbytes, void *stream)
+{
+    if ((!dst || !src) && nbytes) return REDUX_ERR_NULL;
+    if ((uintptr_t)dst % 16 || (uintptr_t)src % 16 || nbytes % 16) return REDUX_ERR_ALIGN;
+    if (nbytes == 0) return REDUX_OK;
+    std::lock_guard<std::mutex> lock(g_mu);
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    int rc = device_cus(dev, &cus);
+    if (rc != REDUX_OK) return rc;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)cus * 4), dim3(kBlock), 0, (hipStream_t)stream,
+                       (u32x4 *)dst, (const u32x4 *)src, (u64)(nbytes / 16));
+    e = hipGetLastError();
     return e == hipSuccess ? REDUX_OK : hip_fail(e);
 }
 
@@ -335,7 +374,7 @@ int redux_set_param(const char *name, long value)
     long lo = 0, hi = 0;
     long *slot = param_slot(name, &lo, &hi);
     if (!slot || value < lo || value > hi) return REDUX_ERR_PARAM;
-    if (slot == &g_set.unroll && value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return REDUX_ERR_PARAM;
+    if (slot == &g_set.unroll && (value & (value - 1)) != 0) return REDUX_ERR_PARAM;   // 0 or a power of two
     *slot = value;
     return REDUX_OK;
 }

@@ -128,11 +128,12 @@ __device__ __forceinline__ double uniform_f64(double v)
 //   edge           build a vector holding a single element in slot 0 (zero padding elsewhere)
 // ---------------------------------------------------------------------------------------------
 
-struct F16Mfma {
+template <int NACC>
+struct F16MfmaT {
     typedef double Total;
     typedef float Out;
     static constexpr int kElemSize = 2;
-    static constexpr int kNumAcc = 4;
+    static constexpr int kNumAcc = NACC;   // independent accumulator chains per wavefront
     static constexpr bool kMfmaFinish = true;
     struct Acc { f32x4 d[kNumAcc]; };
 
@@ -167,6 +168,9 @@ struct F16Mfma {
     static __device__ __forceinline__ Out to_out(Total t) { return (float)t; }
 };
 
+typedef F16MfmaT<4> F16Mfma;      // flat sum: four chains, folded once per wavefront
+typedef F16MfmaT<1> F16MfmaSeg;   // segmented sum: one chain, so the per-segment fold is four MFMAs
+
 struct F16Classic {
     typedef double Total;
     typedef float Out;
@@ -194,11 +198,12 @@ struct F16Classic {
     static __device__ __forceinline__ Out to_out(Total t) { return (float)t; }
 };
 
-struct I8Mfma {
+template <int NACC>
+struct I8MfmaT {
     typedef i64 Total;
     typedef i64 Out;
     static constexpr int kElemSize = 1;
-    static constexpr int kNumAcc = 4;
+    static constexpr int kNumAcc = NACC;
     static constexpr bool kMfmaFinish = false;
     struct Acc { i32x4 d[kNumAcc]; };
 
@@ -232,6 +237,9 @@ struct I8Mfma {
     }
     static __device__ __forceinline__ Out to_out(Total t) { return t; }
 };
+
+typedef I8MfmaT<4> I8Mfma;
+typedef I8MfmaT<1> I8MfmaSeg;
 
 struct I8Classic {
     typedef i64 Total;
@@ -359,7 +367,36 @@ struct FlatArgs {
     unsigned *ticket;   // zero before the launch; the finishing block resets it
     void *out;
     unsigned max_chain; // loop iterations between folds
+    int layout;         // which slabs a block takes (see slab_schedule)
+    int finish;         // 0/1: the last block to arrive sums the partials; 2: a second kernel does
 };
+
+constexpr int kXcds = 8;  // workgroup b is dispatched to accelerator die b % 8
+
+// Which slabs (block-sized runs of U x 4 KiB) a block reads: slab k of the block is start + k*stride.
+//   layout 0  interleaved: at any time the grid reads one contiguous moving window
+//   layout 1  blocked: every block streams its own contiguous share of the array
+//   layout 2  die-blocked: every accelerator die owns a contiguous eighth, interleaved among its blocks
+__device__ __forceinline__ void slab_schedule(int layout, u64 nslab, u64 G, u64 b, u64 *start, u64 *stride, u64 *count)
+{
+    if (layout == 1) {
+        const u64 q = nslab / G, r = nslab % G;
+        *start = b * q + (b < r ? b : r);
+        *stride = 1;
+        *count = q + (b < r ? 1 : 0);
+    } else if (layout == 2 && G >= (u64)kXcds) {
+        const u64 x = b % kXcds, l = b / kXcds;
+        const u64 gx = (G - x + kXcds - 1) / kXcds;              // blocks on this die
+        const u64 lo = nslab * x / kXcds, hi = nslab * (x + 1) / kXcds;
+        *start = lo + l;
+        *stride = gx;
+        *count = (hi - lo > l) ? (hi - lo - l + gx - 1) / gx : 0;
+    } else {
+        *start = b;
+        *stride = G;
+        *count = (nslab > b) ? (nslab - b + G - 1) / G : 0;
+    }
+}
 
 template <class F, int U, bool NT, bool PIPE>
 __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
@@ -375,18 +412,23 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
     Total wave_total = 0;
     unsigned chain = 0;
 
-    u64 s = blockIdx.x;
+    u64 s0, stride, count;
+    slab_schedule(a.layout, nslab, G, blockIdx.x, &s0, &stride, &count);
+    // load u of a block covers 4 KiB contiguous: every wavefront reads whole 1-KiB tiles
+    const u32x4 *p = a.run.body + s0 * kSlab + tid;
+    const u64 step = stride * kSlab;
+
     if (PIPE) {
-        if (s < nslab) {
+        if (count) {
             u32x4 cur[U];
-            const u32x4 *p = a.run.body + s * kSlab + tid;
 #pragma unroll
             for (int u = 0; u < U; ++u) cur[u] = load16<NT>(p + u * kBlock);
-            for (s += G; s < nslab; s += G) {
+            for (u64 k = 1; k < count; ++k) {
+                p += step;
                 u32x4 nxt[U];
-                p = a.run.body + s * kSlab + tid;
 #pragma unroll
                 for (int u = 0; u < U; ++u) nxt[u] = load16<NT>(p + u * kBlock);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
 #pragma unroll
@@ -397,9 +439,8 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
             for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
         }
     } else {
-        for (; s < nslab; s += G) {
+        for (u64 k = 0; k < count; ++k, p += step) {
             u32x4 cur[U];
-            const u32x4 *p = a.run.body + s * kSlab + tid;
 #pragma unroll
             for (int u = 0; u < U; ++u) cur[u] = load16<NT>(p + u * kBlock);
             __builtin_amdgcn_sched_barrier(0);     // issue every load of the slab before the first MMA waits
@@ -430,12 +471,20 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
     __shared__ unsigned is_last;
     if (lane == 0) lds[wave] = wave_total;
     __syncthreads();
+    if (a.finish == 2) {
+        // partials are summed by finish_kernel, launched behind this kernel on the same stream
+        if (tid == 0) a.partials[blockIdx.x] = __builtin_bit_cast(u64, (lds[0] + lds[1]) + (lds[2] + lds[3]));
+        return;
+    }
     if (tid == 0) {
         Total block_total = ((lds[0] + lds[1]) + (lds[2] + lds[3]));
         store_partial(a.partials + blockIdx.x, block_total);
-        // release: the partial is visible device-wide before the ticket moves;
-        // acquire: the block that sees the last ticket sees every partial.
-        unsigned t = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        // release: the partial is visible device-wide before the ticket moves.  The block that draws the
+        // last ticket has read, through the chain of read-modify-writes, from every other block's
+        // release; its acquire fence below then makes all partials visible to it.
+        unsigned t = (a.finish == 0)
+            ? __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT)
+            : __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         is_last = (t == gridDim.x - 1) ? 1u : 0u;
     }
     __syncthreads();
@@ -447,6 +496,16 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
             __hip_atomic_store(a.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+}
+
+// Second kernel of the two-kernel finish: one block sums the partials in the same fixed order.
+template <class F>
+__global__ void __launch_bounds__(kBlock) finish_kernel(const u64 *partials, unsigned count, void *out)
+{
+    typedef typename F::Total Total;
+    __shared__ Total lds[kBlock];
+    Total total = sum_partials<F>(partials, count, lds);
+    if (threadIdx.x == 0) *(typename F::Out *)out = F::to_out(total);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -479,6 +538,7 @@ __global__ void __launch_bounds__(kBlock) sum_segmented_kernel(SegArgs a)
             u32x4 cur[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) cur[u] = load16<NT>(run.body + v0 + (u64)u * 64 + lane);
+            __builtin_amdgcn_sched_barrier(0);     // all loads of the chunk in flight before the first MMA waits
 #pragma unroll
             for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
             if (++chain >= a.max_chain) { total += F::fold(acc); chain = 0; }
@@ -512,6 +572,13 @@ __global__ void fill_zero_words_kernel(unsigned *p, unsigned count)
 {
     unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) p[i] = 0u;
+}
+
+// Plain 16-byte-per-lane copy of `nvec` vectors: a kernel of exactly known traffic, used to
+// calibrate hardware byte counters.
+__global__ void __launch_bounds__(kBlock) copy_kernel(u32x4 *dst, const u32x4 *src, u64 nvec)
+{
+    for (u64 i = (u64)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += (u64)gridDim.x * kBlock) dst[i] = src[i];
 }
 
 // One group through both MMAs of Section IV-A, results written out in matrix order.

@@ -18,7 +18,7 @@ VARIANTS = {"auto": 0, "mfma": 1, "classic": 2}
 
 # every symbol include/redux.h declares
 SYMBOLS = (
-    "redux_sum", "redux_sum_segmented", "redux_mma_group_probe",
+    "redux_sum", "redux_sum_segmented", "redux_mma_group_probe", "redux_calibration_copy",
     "redux_set_variant", "redux_get_variant", "redux_set_param", "redux_get_param",
     "redux_strerror", "redux_last_hip_error", "redux_shutdown", "redux_version",
 )
@@ -48,6 +48,8 @@ def load():
         lib.redux_sum_segmented.argtypes = [vp, sz, sz, ci, vp, vp]
         lib.redux_mma_group_probe.restype = ci
         lib.redux_mma_group_probe.argtypes = [vp, sz, ci, vp, vp, vp]
+        lib.redux_calibration_copy.restype = ci
+        lib.redux_calibration_copy.argtypes = [vp, vp, sz, vp]
         lib.redux_set_variant.restype = ci
         lib.redux_set_variant.argtypes = [ci]
         lib.redux_get_variant.restype = ci
@@ -114,6 +116,10 @@ def sum_segmented_raw(x_ptr: int, nseg: int, seglen: int, dtype: int, out_ptr: i
 
 def mma_group_probe_raw(x_ptr: int, count: int, dtype: int, d_ptr: int, dp_ptr: int, stream: int = 0) -> int:
     return load().redux_mma_group_probe(x_ptr, count, dtype, d_ptr, dp_ptr, stream)
+
+
+def calibration_copy_raw(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> int:
+    return load().redux_calibration_copy(dst_ptr, src_ptr, nbytes, stream)
 
 
 # ---- torch conveniences: allocate the output, pass the current stream --------------------------------

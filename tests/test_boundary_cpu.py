@@ -64,7 +64,7 @@ def test_settings():
     redux.set_param("unroll", 4)
     assert redux.get_param("unroll") == 4
     redux.set_param("unroll", keep)
-    for bad in (("unroll", 3), ("blocks_per_cu", 0), ("nontemporal", 2), ("no_such_param", 1), ("max_chain", 1 << 20)):
+    for bad in (("unroll", 3), ("unroll", 16), ("blocks_per_cu", 0), ("nontemporal", 2), ("no_such_param", 1), ("max_chain", 1 << 20)):
         with pytest.raises(redux.ReduxError):
             redux.set_param(*bad)
     assert redux.get_param("no_such_param") < -(1 << 40)

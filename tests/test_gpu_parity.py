@@ -33,11 +33,19 @@ def dev():
     redux.set_variant("auto")
 
 
+DEFAULTS = {}
+
+
 @pytest.fixture(autouse=True)
 def default_params():
+    if not DEFAULTS:
+        for name in ("blocks_per_cu", "seg_blocks_per_cu", "layout", "finish"):
+            DEFAULTS[name] = redux.get_param(name)
     yield
     for name, val in (("unroll", 0), ("nontemporal", 1), ("pipeline", 0), ("max_chain", 256),
-                      ("max_grid", 16384), ("blocks_per_cu", 8), ("seg_blocks_per_cu", 8)):
+                      ("max_grid", 16384), ("blocks_per_cu", DEFAULTS["blocks_per_cu"]),
+                      ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
+                      ("finish", DEFAULTS["finish"])):
         redux.set_param(name, val)
     redux.set_variant("auto")
 
@@ -170,6 +178,22 @@ def test_flat_chain_folds_and_small_grids(dev, variant, max_chain, max_grid):
     assert gpu_sum(to_dev(xi, dev), variant) == oracle.sum_i8(xi)[0]
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("layout", [0, 1, 2])
+@pytest.mark.parametrize("finish", [0, 1, 2])
+def test_flat_layouts_and_finishes(dev, variant, layout, finish):
+    redux.set_param("layout", layout)
+    redux.set_param("finish", finish)
+    for n, max_grid, unroll in ((100, 16384, 0), ((1 << 21) + 4099, 16384, 0), ((1 << 22) + 5, 13, 2),
+                                ((1 << 22) + 5, 8, 1), ((1 << 23) + 11, 1000, 4), (3 * (1 << 22), 7, 8)):
+        redux.set_param("max_grid", max_grid)
+        redux.set_param("unroll", unroll)
+        x = workloads.normal_f16(n % 1000, n)
+        check_f16(gpu_sum(to_dev(x, dev), variant), x)
+        xi = workloads.uniform_i8(n % 1000, n)
+        assert gpu_sum(to_dev(xi, dev), variant) == oracle.sum_i8(xi)[0]
+
+
 # ---- closed forms, through the GPU ---------------------------------------------------------------------
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -258,6 +282,15 @@ def test_two_streams_do_not_share_a_workspace(dev):
     assert np.all(np.abs(ob.cpu().numpy().astype(np.float64) - wb[0]) <= TOL * wb[1])
 
 
+def test_calibration_copy(dev):
+    src = torch.from_numpy(workloads.uniform_i8(1, (1 << 22) + 16 * 5)).to(dev)
+    dst = torch.zeros_like(src)
+    assert redux.calibration_copy_raw(dst.data_ptr(), src.data_ptr(), src.numel(), 0) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    assert redux.calibration_copy_raw(dst.data_ptr(), src.data_ptr(), 8, 0) == -4
+
+
 # ---- segmented sums ------------------------------------------------------------------------------------
 
 SEG_SHAPES = [(1, 1), (3, 7), (5, 8), (64, 9), (17, 31), (1000, 33), (257, 512), (100, 513), (64, 4096),
@@ -313,6 +346,7 @@ def test_segmented_params(dev, variant):
     for unroll in (1, 2, 4, 8):
         for max_chain, max_grid in ((1, 16384), (256, 2)):
             redux.set_param("unroll", unroll)
+            redux.set_param("seg_blocks_per_cu", unroll)
             redux.set_param("max_chain", max_chain)
             redux.set_param("max_grid", max_grid)
             got = redux.sum_segmented(xd, 513, 4100)
