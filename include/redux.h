@@ -129,7 +129,6 @@ int redux_get_variant(void);
  *   "max_grid"          1..16384 upper limit on the number of blocks (default 16384)
  *   "unroll"            0,1,2,4,8   16-byte loads in flight per lane; 0 = chosen from the size (default 0)
  *   "nontemporal"       0/1     use non-temporal (streaming) loads (default 1)
- *   "pipeline"          0/1     issue the next iteration's loads before consuming the current ones (default 0)
  *   "layout"            0..2    which part of the array a block reads: 0 = blocks interleaved over the
  *                               whole array, 1 = one contiguous share per block, 2 = one contiguous
  *                               eighth per accelerator die, interleaved among that die's blocks (default 2)

@@ -21,7 +21,6 @@ struct Settings {
     long seg_blocks_per_cu = 0;   // 0 = from the segment length
     long unroll = 0;          // 0 = from the problem size
     long nontemporal = 1;
-    long pipeline = 0;
     long max_chain = 256;
     long max_grid = kMaxGrid;
     long layout = 2;
@@ -97,25 +96,20 @@ int get_workspace(int dev, hipStream_t st, Workspace *out)
 
 // ---- kernel dispatch ----------------------------------------------------------------------------
 template <class F, int U>
-void launch_flat_u(bool nt, bool pipe, unsigned grid, hipStream_t st, const FlatArgs &a)
+void launch_flat_u(bool nt, unsigned grid, hipStream_t st, const FlatArgs &a)
 {
-    if (nt) {
-        if (pipe) hipLaunchKernelGGL((sum_flat_kernel<F, U, true, true>), dim3(grid), dim3(kBlock), 0, st, a);
-        else      hipLaunchKernelGGL((sum_flat_kernel<F, U, true, false>), dim3(grid), dim3(kBlock), 0, st, a);
-    } else {
-        if (pipe) hipLaunchKernelGGL((sum_flat_kernel<F, U, false, true>), dim3(grid), dim3(kBlock), 0, st, a);
-        else      hipLaunchKernelGGL((sum_flat_kernel<F, U, false, false>), dim3(grid), dim3(kBlock), 0, st, a);
-    }
+    if (nt) hipLaunchKernelGGL((sum_flat_kernel<F, U, true>), dim3(grid), dim3(kBlock), 0, st, a);
+    else    hipLaunchKernelGGL((sum_flat_kernel<F, U, false>), dim3(grid), dim3(kBlock), 0, st, a);
 }
 
 template <class F>
-void launch_flat(int unroll, bool nt, bool pipe, unsigned grid, hipStream_t st, const FlatArgs &a)
+void launch_flat(int unroll, bool nt, unsigned grid, hipStream_t st, const FlatArgs &a)
 {
     switch (unroll) {
-    case 8: launch_flat_u<F, 8>(nt, pipe, grid, st, a); break;
-    case 4: launch_flat_u<F, 4>(nt, pipe, grid, st, a); break;
-    case 2: launch_flat_u<F, 2>(nt, pipe, grid, st, a); break;
-    default: launch_flat_u<F, 1>(nt, pipe, grid, st, a); break;
+    case 8: launch_flat_u<F, 8>(nt, grid, st, a); break;
+    case 4: launch_flat_u<F, 4>(nt, grid, st, a); break;
+    case 2: launch_flat_u<F, 2>(nt, grid, st, a); break;
+    default: launch_flat_u<F, 1>(nt, grid, st, a); break;
     }
 }
 
@@ -171,7 +165,6 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "seg_blocks_per_cu")) { *lo = 0; *hi = 16; return &g_set.seg_blocks_per_cu; }
     if (!std::strcmp(name, "unroll")) { *lo = 0; *hi = 8; return &g_set.unroll; }
     if (!std::strcmp(name, "nontemporal")) { *lo = 0; *hi = 1; return &g_set.nontemporal; }
-    if (!std::strcmp(name, "pipeline")) { *lo = 0; *hi = 1; return &g_set.pipeline; }
     if (!std::strcmp(name, "max_chain")) { *lo = 1; *hi = 65536; return &g_set.max_chain; }
     if (!std::strcmp(name, "max_grid")) { *lo = 1; *hi = kMaxGrid; return &g_set.max_grid; }
     if (!std::strcmp(name, "layout")) { *lo = 0; *hi = 2; return &g_set.layout; }
@@ -235,14 +228,14 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
     // once there are many blocks; a handful of blocks finish in the same kernel.
     if (a.finish < 0) a.finish = grid >= 128 ? 2 : 1;
 
-    const bool nt = g_set.nontemporal != 0, pipe = g_set.pipeline != 0;
+    const bool nt = g_set.nontemporal != 0;
     const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
     if (dtype == REDUX_F16) {
-        if (mfma) launch_flat<F16Mfma>(unroll, nt, pipe, grid, st, a);
-        else      launch_flat<F16Classic>(unroll, nt, pipe, grid, st, a);
+        if (mfma) launch_flat<F16Mfma>(unroll, nt, grid, st, a);
+        else      launch_flat<F16Classic>(unroll, nt, grid, st, a);
     } else {
-        if (mfma) launch_flat<I8Mfma>(unroll, nt, pipe, grid, st, a);
-        else      launch_flat<I8Classic>(unroll, nt, pipe, grid, st, a);
+        if (mfma) launch_flat<I8Mfma>(unroll, nt, grid, st, a);
+        else      launch_flat<I8Classic>(unroll, nt, grid, st, a);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);

@@ -398,7 +398,7 @@ __device__ __forceinline__ void slab_schedule(int layout, u64 nslab, u64 G, u64 
     }
 }
 
-template <class F, int U, bool NT, bool PIPE>
+template <class F, int U, bool NT>
 __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
 {
     typedef typename F::Total Total;
@@ -418,36 +418,14 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
     const u32x4 *p = a.run.body + s0 * kSlab + tid;
     const u64 step = stride * kSlab;
 
-    if (PIPE) {
-        if (count) {
-            u32x4 cur[U];
+    for (u64 k = 0; k < count; ++k, p += step) {
+        u32x4 cur[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) cur[u] = load16<NT>(p + u * kBlock);
-            for (u64 k = 1; k < count; ++k) {
-                p += step;
-                u32x4 nxt[U];
+        for (int u = 0; u < U; ++u) cur[u] = load16<NT>(p + u * kBlock);
+        __builtin_amdgcn_sched_barrier(0);     // issue every load of the slab before the first MMA waits
 #pragma unroll
-                for (int u = 0; u < U; ++u) nxt[u] = load16<NT>(p + u * kBlock);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
-#pragma unroll
-                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
-                if (++chain >= a.max_chain) { wave_total += F::fold(acc); chain = 0; }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
-        }
-    } else {
-        for (u64 k = 0; k < count; ++k, p += step) {
-            u32x4 cur[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) cur[u] = load16<NT>(p + u * kBlock);
-            __builtin_amdgcn_sched_barrier(0);     // issue every load of the slab before the first MMA waits
-#pragma unroll
-            for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
-            if (++chain >= a.max_chain) { wave_total += F::fold(acc); chain = 0; }
-        }
+        for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
+        if (++chain >= a.max_chain) { wave_total += F::fold(acc); chain = 0; }
     }
 
     // vectors past the last whole slab: one block, lanes past the end contribute zeros

@@ -42,7 +42,7 @@ def default_params():
         for name in ("blocks_per_cu", "seg_blocks_per_cu", "layout", "finish"):
             DEFAULTS[name] = redux.get_param(name)
     yield
-    for name, val in (("unroll", 0), ("nontemporal", 1), ("pipeline", 0), ("max_chain", 256),
+    for name, val in (("unroll", 0), ("nontemporal", 1), ("max_chain", 256),
                       ("max_grid", 16384), ("blocks_per_cu", DEFAULTS["blocks_per_cu"]),
                       ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
                       ("finish", DEFAULTS["finish"])):
@@ -153,11 +153,9 @@ def test_flat_misaligned_base(dev, variant):
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("unroll", [1, 2, 4, 8])
-@pytest.mark.parametrize("pipeline", [0, 1])
 @pytest.mark.parametrize("nontemporal", [0, 1])
-def test_flat_every_launch_shape(dev, variant, unroll, pipeline, nontemporal):
+def test_flat_every_launch_shape(dev, variant, unroll, nontemporal):
     redux.set_param("unroll", unroll)
-    redux.set_param("pipeline", pipeline)
     redux.set_param("nontemporal", nontemporal)
     n = 5 * (1 << 20) + 12345
     x = workloads.uniform_f16(9, n)
