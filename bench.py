@@ -46,7 +46,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--variant", default="auto", choices=["auto", "mfma", "classic"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "mfma", "classic", "multipass"],
+                    help="kernel family of redux_sum; 'multipass' times redux_sum_multipass (the level-by-level form) instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the reduction, run --steps plain copies of MIB MiB (known traffic) "
@@ -91,7 +92,8 @@ def main() -> int:
     x = torch.from_numpy(host).to(dev)
     torch.cuda.synchronize()
 
-    redux.set_variant(args.variant)
+    multipass = args.variant == "multipass"
+    redux.set_variant("auto" if multipass else args.variant)
     for kv in args.set:
         name, val = kv.split("=")
         redux.set_param(name, int(val))
@@ -101,7 +103,7 @@ def main() -> int:
         step = lambda: redux.sum_segmented(x, cfg.nseg, cfg.seglen, out=out)
     else:
         out = torch.empty(1, dtype=torch.float32 if cfg.dtype == "f16" else torch.int64, device=dev)
-        step = lambda: redux.sum(x, out=out)
+        step = (lambda: redux.sum_multipass(x, out=out)) if multipass else (lambda: redux.sum(x, out=out))
 
     for _ in range(args.warmup):
         step()
@@ -126,7 +128,7 @@ def main() -> int:
     launch_us = dev_ms * 1e3 / args.steps
     achieved = nbytes / (launch_us * 1e-6) / 1e9
 
-    variant_run = {0: "mfma", 1: "mfma", 2: "classic"}[redux.get_variant()]   # auto resolves to mfma
+    variant_run = "multipass" if multipass else {0: "mfma", 1: "mfma", 2: "classic"}[redux.get_variant()]   # auto resolves to mfma
     traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, variant_run))
 
     line = {

@@ -92,8 +92,33 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
  *   x       device pointer, row-major [nseg][seglen], read only; may be NULL iff nseg*seglen == 0.
  *   out     device pointer to nseg results (float for F16, int64_t for I8).
  *   nseg == 0 is a no-op; seglen == 0 writes nseg zeros.
+ *
+ * Three shapes of kernel, chosen from (nseg, seglen): short 16-byte-aligned segments (up to 1 KiB)
+ * go sixteen to a wavefront, one per row of the A operand, and need only the first MMA; otherwise one
+ * wavefront takes one segment (first MMA chained over its tiles, second MMA to fold the rows); a few
+ * long segments are cut into pieces whose totals (in the workspace) a second kernel adds per segment.
  */
 int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, void *out, void *stream);
+
+/*
+ * redux_sum_multipass -- the same sum computed exactly as Sections IV-A and IV-B lay the algorithm out,
+ * level by level: the input is cut into contiguous groups of m*m = 256 numbers (the first int8 level:
+ * 512, the narrowest int8 tile being 16 x 32); every group goes through both MMAs with C = 0
+ * (D = A x 1, D' = 1 x D) and the thread in charge writes D'[1,1] into an array of partial sums in
+ * global memory; each level is one kernel launch and the partial sums are the next level's input,
+ * until one value is left (recurrence R_tc; ceil(log_256 n) levels for binary16).  A last group that
+ * is not full is zero padded.  Binary16: partial sums are binary32 at every level.  Int8: int32 inside
+ * the first MMA, int64 partial sums, later levels in binary64 (exact below 2^53).
+ *
+ *   x, n, dtype, out, stream   as for redux_sum.
+ *   levels   host pointer or NULL; receives the number of levels (= kernel launches); 0 for n == 0.
+ *
+ * The arrays of partial sums (n/256 and n/65536 entries) are library-owned per (device, stream) and grow
+ * on demand (hipMalloc; a larger request frees the old buffer first, which waits for the device).
+ * This entry point exists to measure the algorithm as published against redux_sum, which chains the
+ * accumulator through C and makes one pass; it is not the fast path.
+ */
+int redux_sum_multipass(const void *x, size_t n, int dtype, void *out, int *levels, void *stream);
 
 /*
  * redux_mma_group_probe -- the two MMA steps of Section IV-A on ONE group, with both
@@ -129,6 +154,14 @@ int redux_get_variant(void);
  *   "max_grid"          1..16384 upper limit on the number of blocks (default 16384)
  *   "unroll"            0,1,2,4,8   16-byte loads in flight per lane; 0 = chosen from the size (default 0)
  *   "nontemporal"       0/1     use non-temporal (streaming) loads (default 1)
+ *   "rows_max_vec"      0..64   segmented sum: segments of at most this many 16-byte vectors (and 16-byte
+ *                               aligned) take the sixteen-segments-per-wavefront kernel; 0 = never (default 64)
+ *   "seg_parts"         0,1,2,4,...,4096  segmented sum: pieces a long segment is cut into; 0 = from the
+ *                               shape (default 0); ignored if nseg * pieces exceeds the workspace (16384)
+ *   "lit_unroll"        0,1,2,4,8,16  redux_sum_multipass: groups per wavefront iteration; 0 = 16 for
+ *                               binary16, 4 for int8 (default 0)
+ *   "lit_blocks_per_cu" 0..16   redux_sum_multipass: 256-thread blocks per compute unit; 0 = 4 for binary16,
+ *                               8 for int8 (default 0)
  *   "layout"            0..2    which part of the array a block reads: 0 = blocks interleaved over the
  *                               whole array, 1 = one contiguous share per block, 2 = one contiguous
  *                               eighth per accelerator die, interleaved among that die's blocks (default 2)

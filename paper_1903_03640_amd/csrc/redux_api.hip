@@ -2,6 +2,7 @@
 // launch-shape selection, workspace ownership, kernel launches.  No compute happens on the host.
 #include "../../include/redux.h"
 #include "redux_kernels.h"
+#include "redux_literal.h"
 
 #include <climits>
 #include <cstdlib>
@@ -24,6 +25,10 @@ struct Settings {
     long max_chain = 256;
     long max_grid = kMaxGrid;
     long layout = 2;
+    long rows_max_vec = 64;       // short-segment kernel up to this many 16-byte vectors per segment (0 = off)
+    long seg_parts = 0;           // 0 = pieces per long segment chosen from the shape
+    long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
+    long lit_blocks_per_cu = 0;
     long finish = -1;             // -1 = from the grid size
 };
 Settings g_set;
@@ -92,6 +97,52 @@ int get_workspace(int dev, hipStream_t st, Workspace *out)
     }
     *out = it->second;
     return REDUX_OK;
+}
+
+// ---- per (device, stream) buffers for the arrays of partial sums of the level-by-level form ----------
+struct LevelBuffers {
+    void *buf[2] = {nullptr, nullptr};
+    size_t bytes[2] = {0, 0};
+};
+std::map<std::pair<int, hipStream_t>, LevelBuffers> g_levels;
+
+int get_level_buffers(int dev, hipStream_t st, size_t bytes0, size_t bytes1, LevelBuffers *out)
+{
+    LevelBuffers &lb = g_levels[std::make_pair(dev, st)];
+    const size_t want[2] = {bytes0, bytes1};
+    for (int i = 0; i < 2; ++i) {
+        if (lb.bytes[i] >= want[i]) continue;
+        if (lb.buf[i]) (void)hipFree(lb.buf[i]);          // waits for work that may still use it
+        lb.buf[i] = nullptr;
+        lb.bytes[i] = 0;
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, want[i]);
+        if (e != hipSuccess) return hip_fail(e, REDUX_ERR_NOMEM);
+        lb.buf[i] = p;
+        lb.bytes[i] = want[i];
+    }
+    *out = lb;
+    return REDUX_OK;
+}
+
+template <int U>
+void launch_literal_level(int dtype, bool first, bool fast, const void *in, u64 n, void *outp, unsigned grid, hipStream_t st)
+{
+    if (dtype == REDUX_F16) {
+        if (first) {
+            if (fast) hipLaunchKernelGGL((literal_level_f16_kernel<U, true>), dim3(grid), dim3(kBlock), 0, st, (const unsigned short *)in, n, (float *)outp);
+            else      hipLaunchKernelGGL((literal_level_f16_kernel<U, false>), dim3(grid), dim3(kBlock), 0, st, (const unsigned short *)in, n, (float *)outp);
+        } else {
+            hipLaunchKernelGGL((literal_level_f32_kernel<U>), dim3(grid), dim3(kBlock), 0, st, (const float *)in, n, (float *)outp);
+        }
+    } else {
+        if (first) {
+            if (fast) hipLaunchKernelGGL((literal_level_i8_kernel<U, true>), dim3(grid), dim3(kBlock), 0, st, (const signed char *)in, n, (i64 *)outp);
+            else      hipLaunchKernelGGL((literal_level_i8_kernel<U, false>), dim3(grid), dim3(kBlock), 0, st, (const signed char *)in, n, (i64 *)outp);
+        } else {
+            hipLaunchKernelGGL((literal_level_i64_kernel<U>), dim3(grid), dim3(kBlock), 0, st, (const i64 *)in, n, (i64 *)outp);
+        }
+    }
 }
 
 // ---- kernel dispatch ----------------------------------------------------------------------------
@@ -167,6 +218,10 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "nontemporal")) { *lo = 0; *hi = 1; return &g_set.nontemporal; }
     if (!std::strcmp(name, "max_chain")) { *lo = 1; *hi = 65536; return &g_set.max_chain; }
     if (!std::strcmp(name, "max_grid")) { *lo = 1; *hi = kMaxGrid; return &g_set.max_grid; }
+    if (!std::strcmp(name, "rows_max_vec")) { *lo = 0; *hi = 64; return &g_set.rows_max_vec; }
+    if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
+    if (!std::strcmp(name, "lit_unroll")) { *lo = 0; *hi = 16; return &g_set.lit_unroll; }
+    if (!std::strcmp(name, "lit_blocks_per_cu")) { *lo = 0; *hi = 16; return &g_set.lit_blocks_per_cu; }
     if (!std::strcmp(name, "layout")) { *lo = 0; *hi = 2; return &g_set.layout; }
     if (!std::strcmp(name, "finish")) { *lo = -1; *hi = 2; return &g_set.finish; }
     return nullptr;
@@ -279,26 +334,74 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     if (e != hipSuccess) return hip_fail(e);
     if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
 
+    const bool nt = g_set.nontemporal != 0;
+    const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
+    const u64 seg_bytes = (u64)seglen * es;
+
+    // ---- short segments: sixteen per wavefront, one per row of the A operand -------------------------
+    if (g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 && (uintptr_t)x % 16 == 0 &&
+        seg_bytes / 16 <= (u64)g_set.rows_max_vec) {
+        RowArgs r;
+        r.x = (const u32x4 *)x;
+        r.nseg = nseg;
+        r.nvec = (unsigned)(seg_bytes / 16);
+        r.out = out;
+        const unsigned steps = (r.nvec + 3) / 4;
+        const int tc = steps <= 1 ? 1 : steps <= 2 ? 2 : steps <= 4 ? 4 : 8;
+        const u64 nsuper = ((nseg + 15) / 16 + (8 / tc) - 1) / (8 / tc);
+        u64 blocks = (nsuper + kWaves - 1) / kWaves;
+        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 2);   // measured best
+        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        const unsigned grid = (unsigned)(blocks < gmax ? blocks : gmax);
+#define REDUX_ROWS(R, TC) do { if (nt) hipLaunchKernelGGL((sum_rows_kernel<R, TC, true>), dim3(grid), dim3(kBlock), 0, st, r); \
+                               else    hipLaunchKernelGGL((sum_rows_kernel<R, TC, false>), dim3(grid), dim3(kBlock), 0, st, r); } while (0)
+#define REDUX_ROWS_TC(R) do { if (tc == 1) REDUX_ROWS(R, 1); else if (tc == 2) REDUX_ROWS(R, 2); \
+                              else if (tc == 4) REDUX_ROWS(R, 4); else REDUX_ROWS(R, 8); } while (0)
+        if (dtype == REDUX_F16) { if (mfma) REDUX_ROWS_TC(F16MfmaRows); else REDUX_ROWS_TC(F16ClassicRows); }
+        else                    { if (mfma) REDUX_ROWS_TC(I8MfmaRows);  else REDUX_ROWS_TC(I8ClassicRows); }
+#undef REDUX_ROWS_TC
+#undef REDUX_ROWS
+        e = hipGetLastError();
+        return e == hipSuccess ? REDUX_OK : hip_fail(e);
+    }
+
+    // ---- general form: one wavefront per segment, or per piece of a long segment -------------------------
     SegArgs a;
     a.x = (const unsigned char *)x;
     a.nseg = nseg;
     a.seglen = seglen;
     a.out = out;
     a.max_chain = (unsigned)g_set.max_chain;
+    a.parts = 1;
+    a.part_len = seglen;
+    a.partials = nullptr;
 
-    // one wavefront per segment; loads in flight per lane x resident blocks per compute unit = 8
-    const u64 vec_per_seg = (u64)seglen * es / 16;
+    // A few long segments would leave most of the chip idle: cut each into a power-of-two number of
+    // pieces (whole 512-element tiles, at least 8 tiles each) until there are about 8 wavefronts per
+    // compute unit, as far as the workspace allows.
+    const u64 want_waves = (u64)cus * 8;
+    u64 parts = 1;
+    if (g_set.seg_parts > 0) parts = (u64)g_set.seg_parts;
+    else while (nseg * parts < want_waves && nseg * parts * 2 <= (u64)kMaxGrid && seglen / (parts * 2) >= 8 * 512) parts *= 2;
+    if (parts > 1 && nseg <= (u64)kMaxGrid / parts) {
+        Workspace ws;
+        if ((rc = get_workspace(dev, st, &ws)) != REDUX_OK) return rc;
+        a.parts = parts;
+        a.part_len = ((seglen + parts - 1) / parts + 511) / 512 * 512;
+        a.partials = ws.partials;
+    }
+
+    // loads in flight per lane x resident blocks per compute unit = 8
+    const u64 vec_per_piece = (u64)a.part_len * es / 16;
     int unroll = (int)g_set.unroll;
-    if (unroll == 0) unroll = vec_per_seg >= 256 ? 4 : vec_per_seg >= 128 ? 2 : 1;
+    if (unroll == 0) unroll = vec_per_piece >= 256 ? 4 : vec_per_piece >= 128 ? 2 : 1;
     long bpc = g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 8 / unroll;
 
-    u64 blocks_needed = (nseg + kWaves - 1) / kWaves;
+    u64 blocks_needed = (nseg * a.parts + kWaves - 1) / kWaves;
     u64 gmax = (u64)cus * (u64)bpc;
     if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
     unsigned grid = (unsigned)(blocks_needed < gmax ? blocks_needed : gmax);
 
-    const bool nt = g_set.nontemporal != 0;
-    const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
     if (dtype == REDUX_F16) {
         if (mfma) launch_seg<F16MfmaSeg>(unroll, nt, grid, st, a);
         else      launch_seg<F16Classic>(unroll, nt, grid, st, a);
@@ -307,7 +410,82 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
         else      launch_seg<I8Classic>(unroll, nt, grid, st, a);
     }
     e = hipGetLastError();
-    return e == hipSuccess ? REDUX_OK : hip_fail(e);
+    if (e != hipSuccess) return hip_fail(e);
+    if (a.parts > 1) {
+        const unsigned p = (unsigned)a.parts, g = (unsigned)nseg;
+        if (dtype == REDUX_F16) {
+            if (mfma) hipLaunchKernelGGL(finish_segments_kernel<F16Mfma>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
+            else      hipLaunchKernelGGL(finish_segments_kernel<F16Classic>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
+        } else {
+            hipLaunchKernelGGL(finish_segments_kernel<I8Classic>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return REDUX_OK;
+}
+
+int redux_sum_multipass(const void *x, size_t n, int dtype, void *out, int *levels, void *stream)
+{
+    std::call_once(g_env_once, read_env);
+    size_t es = 0;
+    int rc = check_common(x, n, dtype, out, 1, &es);
+    if (rc != REDUX_OK) return rc;
+    if (levels) *levels = 0;
+
+    hipStream_t st = (hipStream_t)stream;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (n == 0) {
+        if (dtype == REDUX_F16) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(1), dim3(64), 0, st, (float *)out, (u64)1);
+        else                    hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(1), dim3(64), 0, st, (i64 *)out, (u64)1);
+        hipError_t e = hipGetLastError();
+        return e == hipSuccess ? REDUX_OK : hip_fail(e);
+    }
+
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
+
+    const u64 first_group = dtype == REDUX_F16 ? kLitGroup : kLitGroupI8;
+    const size_t ps = dtype == REDUX_F16 ? sizeof(float) : sizeof(i64);     // size of a partial sum
+    const u64 n1 = ((u64)n + first_group - 1) / first_group;                 // partial sums after level 1
+    const u64 n2 = (n1 + kLitGroup - 1) / kLitGroup;                         // ... after level 2
+    LevelBuffers lb;
+    if (n1 > 1 && (rc = get_level_buffers(dev, st, (size_t)n1 * ps + 16, (size_t)n2 * ps + 16, &lb)) != REDUX_OK) return rc;
+
+    // measured best on MI355X (the kernels are bound by the matrix unit, not by HBM)
+    const int U = g_set.lit_unroll ? (int)g_set.lit_unroll : (dtype == REDUX_F16 ? 16 : 4);
+    const u64 bpc = g_set.lit_blocks_per_cu ? (u64)g_set.lit_blocks_per_cu : (dtype == REDUX_F16 ? 4 : 8);
+    const void *in = x;
+    u64 count = n;
+    int level = 0;
+    while (true) {
+        const u64 group = level == 0 ? first_group : (u64)kLitGroup;
+        const u64 ngroups = (count + group - 1) / group;
+        void *outp = ngroups == 1 ? out : lb.buf[level & 1];
+        const u64 nbatch = (ngroups + U - 1) / U;
+        u64 blocks = (nbatch + kWaves - 1) / kWaves;
+        u64 gmax = (u64)cus * bpc;
+        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        const unsigned grid = (unsigned)(blocks < gmax ? blocks : gmax);
+        const bool fast = ((uintptr_t)in % 8) == 0;
+        switch (U) {
+        case 16: launch_literal_level<16>(dtype, level == 0, fast, in, count, outp, grid, st); break;
+        case 8: launch_literal_level<8>(dtype, level == 0, fast, in, count, outp, grid, st); break;
+        case 4: launch_literal_level<4>(dtype, level == 0, fast, in, count, outp, grid, st); break;
+        case 2: launch_literal_level<2>(dtype, level == 0, fast, in, count, outp, grid, st); break;
+        default: launch_literal_level<1>(dtype, level == 0, fast, in, count, outp, grid, st); break;
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+        ++level;
+        if (ngroups == 1) break;
+        in = outp;
+        count = ngroups;
+    }
+    if (levels) *levels = level;
+    return REDUX_OK;
 }
 
 int redux_mma_group_probe(const void *x, size_t count, int dtype, void *D, void *Dprime, void *stream)
@@ -367,7 +545,8 @@ int redux_set_param(const char *name, long value)
     long lo = 0, hi = 0;
     long *slot = param_slot(name, &lo, &hi);
     if (!slot || value < lo || value > hi) return REDUX_ERR_PARAM;
-    if (slot == &g_set.unroll && (value & (value - 1)) != 0) return REDUX_ERR_PARAM;   // 0 or a power of two
+    if ((slot == &g_set.unroll || slot == &g_set.seg_parts || slot == &g_set.lit_unroll) && (value & (value - 1)) != 0)
+        return REDUX_ERR_PARAM;   // 0 or a power of two
     *slot = value;
     return REDUX_OK;
 }
@@ -403,6 +582,10 @@ void redux_shutdown(void)
     std::lock_guard<std::mutex> lock(g_mu);
     for (auto &kv : g_ws) (void)hipFree(kv.second.partials);
     g_ws.clear();
+    for (auto &kv : g_levels)
+        for (int i = 0; i < 2; ++i)
+            if (kv.second.buf[i]) (void)hipFree(kv.second.buf[i]);
+    g_levels.clear();
     g_cus.clear();
 }
 

@@ -487,13 +487,17 @@ __global__ void __launch_bounds__(kBlock) finish_kernel(const u64 *partials, uns
 }
 
 // ---------------------------------------------------------------------------------------------
-// segmented sum: one wavefront per segment, no cross-block step
+// segmented sum, general form: one wavefront per segment (or per part of a long segment)
 // ---------------------------------------------------------------------------------------------
 struct SegArgs {
     const unsigned char *x;
     u64 nseg, seglen;   // elements
     void *out;
     unsigned max_chain;
+    // Long segments are cut into `parts` pieces of part_len elements so that a few segments still
+    // fill the chip; piece totals go to `partials` and finish_segments_kernel adds them up.
+    u64 parts, part_len;
+    u64 *partials;
 };
 
 template <class F, int U, bool NT>
@@ -504,9 +508,13 @@ __global__ void __launch_bounds__(kBlock) sum_segmented_kernel(SegArgs a)
     const u64 wave_global = (u64)blockIdx.x * kWaves + (threadIdx.x >> 6);
     const u64 nwaves = (u64)gridDim.x * kWaves;
     constexpr u64 kChunk = 64ull * U;              // vectors per wave iteration
+    const u64 npieces = a.nseg * a.parts;
 
-    for (u64 seg = wave_global; seg < a.nseg; seg += nwaves) {
-        const Run run = make_run<F::kElemSize>(a.x + seg * a.seglen * F::kElemSize, a.seglen);
+    for (u64 piece = wave_global; piece < npieces; piece += nwaves) {
+        const u64 seg = piece / a.parts, part = piece % a.parts;
+        const u64 first = part * a.part_len;
+        const u64 len = first < a.seglen ? (a.seglen - first < a.part_len ? a.seglen - first : a.part_len) : 0;
+        const Run run = make_run<F::kElemSize>(a.x + (seg * a.seglen + first) * F::kElemSize, len);
         typename F::Acc acc;
         F::clear(acc);
         Total total = 0;
@@ -532,7 +540,175 @@ __global__ void __launch_bounds__(kBlock) sum_segmented_kernel(SegArgs a)
         }
         if (run.nhead | run.ntail) F::consume(acc, 0, edge_vector<F>(run, (int)lane));
         total += F::fold(acc);
-        if (lane == 0) ((typename F::Out *)a.out)[seg] = F::to_out(total);
+        if (lane == 0) {
+            if (a.parts == 1) ((typename F::Out *)a.out)[seg] = F::to_out(total);
+            else a.partials[piece] = __builtin_bit_cast(u64, total);
+        }
+    }
+}
+
+// One block per segment adds that segment's piece totals in a fixed order.
+template <class F>
+__global__ void __launch_bounds__(kBlock) finish_segments_kernel(const u64 *partials, unsigned parts, void *out)
+{
+    typedef typename F::Total Total;
+    __shared__ Total lds[kBlock];
+    Total total = sum_partials<F>(partials + (u64)blockIdx.x * parts, parts, lds);
+    if (threadIdx.x == 0) ((typename F::Out *)out)[blockIdx.x] = F::to_out(total);
+}
+
+// ---------------------------------------------------------------------------------------------
+// segmented sum, short segments: sixteen segments per wavefront, one per row of the A operand.
+//
+// The first MMA of Section IV-A already yields one independent sum per row of A (every column of
+// D holds the m row sums), so short segments need no second MMA at all: row i of A takes the
+// elements of segment s0 + i, 32 (binary16) or 64 (int8) per MFMA, and after the chain column 0 of
+// the accumulator is the sixteen results.  Requires 16-byte aligned segments (host-checked).
+//
+// A lane holds A[lane % 16][(lane / 16) * w .. + w): row = lane & 15, quarter = lane >> 4.  The
+// classic family uses the same loads with row = lane >> 2, quarter = lane & 3 and a DPP reduction
+// over each quad.
+// ---------------------------------------------------------------------------------------------
+struct RowArgs {
+    const u32x4 *x;     // 16-byte aligned
+    u64 nseg;
+    unsigned nvec;      // 16-byte vectors per segment (1 .. 64)
+    void *out;
+};
+
+struct F16MfmaRows {
+    typedef float Out;
+    typedef f32x4 Acc;
+    static __device__ __forceinline__ unsigned row(unsigned lane) { return lane & 15u; }
+    static __device__ __forceinline__ unsigned quarter(unsigned lane) { return lane >> 4; }
+    static __device__ __forceinline__ Acc zero() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+    static __device__ __forceinline__ void consume(Acc &d, u32x4 v)
+    {
+        const f16x8 ones = {1, 1, 1, 1, 1, 1, 1, 1};
+        d = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, v), ones, d, 0, 0, 0);
+    }
+    // lane l, register r holds D[4*(l/16)+r][l%16]; column 0 lives in lanes 0, 16, 32, 48
+    static __device__ __forceinline__ void store(const Acc &d, Out *out, u64 seg0, u64 nseg, unsigned lane)
+    {
+        if ((lane & 15u) == 0) {
+            const u64 s = seg0 + 4 * (lane >> 4);
+            if (s + 4 <= nseg && ((uintptr_t)(out + s) & 15u) == 0) {
+                *(f32x4 *)(out + s) = d;               // four results in one 16-byte store
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (s + r < nseg) out[s + r] = d[r];
+            }
+        }
+    }
+};
+
+struct I8MfmaRows {
+    typedef i64 Out;
+    typedef i32x4 Acc;
+    static __device__ __forceinline__ unsigned row(unsigned lane) { return lane & 15u; }
+    static __device__ __forceinline__ unsigned quarter(unsigned lane) { return lane >> 4; }
+    static __device__ __forceinline__ Acc zero() { return i32x4{0, 0, 0, 0}; }
+    static __device__ __forceinline__ void consume(Acc &d, u32x4 v)
+    {
+        const i32x4 ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+        d = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, v), ones, d, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void store(const Acc &d, Out *out, u64 seg0, u64 nseg, unsigned lane)
+    {
+        if ((lane & 15u) == 0) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                u64 s = seg0 + 4 * (lane >> 4) + r;
+                if (s < nseg) out[s] = (i64)d[r];
+            }
+        }
+    }
+};
+
+struct F16ClassicRows {
+    typedef float Out;
+    typedef float Acc;
+    static __device__ __forceinline__ unsigned row(unsigned lane) { return lane >> 2; }
+    static __device__ __forceinline__ unsigned quarter(unsigned lane) { return lane & 3u; }
+    static __device__ __forceinline__ Acc zero() { return 0.f; }
+    static __device__ __forceinline__ void consume(Acc &s, u32x4 v)
+    {
+        f16x8 h = __builtin_bit_cast(f16x8, v);
+        float a = ((float)h[0] + (float)h[1]) + ((float)h[2] + (float)h[3]);
+        float b = ((float)h[4] + (float)h[5]) + ((float)h[6] + (float)h[7]);
+        s += a + b;
+    }
+    static __device__ __forceinline__ void store(const Acc &s, Out *out, u64 seg0, u64 nseg, unsigned lane)
+    {
+        float v = s;
+        v += __builtin_bit_cast(float, dpp_i32<kQuadXor1>(__builtin_bit_cast(int, v)));
+        v += __builtin_bit_cast(float, dpp_i32<kQuadXor2>(__builtin_bit_cast(int, v)));
+        u64 sg = seg0 + (lane >> 2);
+        if ((lane & 3u) == 0 && sg < nseg) out[sg] = v;
+    }
+};
+
+struct I8ClassicRows {
+    typedef i64 Out;
+    typedef int Acc;
+    static __device__ __forceinline__ unsigned row(unsigned lane) { return lane >> 2; }
+    static __device__ __forceinline__ unsigned quarter(unsigned lane) { return lane & 3u; }
+    static __device__ __forceinline__ Acc zero() { return 0; }
+    static __device__ __forceinline__ void consume(Acc &s, u32x4 v)
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s = __builtin_amdgcn_sdot4((int)v[k], 0x01010101, s, false);
+    }
+    static __device__ __forceinline__ void store(const Acc &s, Out *out, u64 seg0, u64 nseg, unsigned lane)
+    {
+        int v = s;                      // at most 64 vectors x 16 x 128 per lane: far inside int32
+        v += dpp_i32<kQuadXor1>(v);
+        v += dpp_i32<kQuadXor2>(v);
+        u64 sg = seg0 + (lane >> 2);
+        if ((lane & 3u) == 0 && sg < nseg) out[sg] = (i64)v;
+    }
+};
+
+// TC = loads per row group per iteration (1, 2, 4 or 8); a wavefront keeps 8 loads in flight by
+// working on GRP = 8 / TC groups of sixteen segments at a time.
+template <class R, int TC, bool NT>
+__global__ void __launch_bounds__(kBlock) sum_rows_kernel(RowArgs a)
+{
+    constexpr int GRP = 8 / TC;
+    const unsigned lane = threadIdx.x & 63u;
+    const unsigned row = R::row(lane), quarter = R::quarter(lane);
+    const u64 wave_global = (u64)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const u64 nwaves = (u64)gridDim.x * kWaves;
+    const u64 ngroups = (a.nseg + 15) / 16;
+    const u64 nsuper = (ngroups + GRP - 1) / GRP;
+
+    for (u64 sg = wave_global; sg < nsuper; sg += nwaves) {
+        typename R::Acc acc[GRP];
+#pragma unroll
+        for (int g = 0; g < GRP; ++g) acc[g] = R::zero();
+        for (unsigned t0 = 0; t0 < a.nvec; t0 += 4 * TC) {       // one trip unless a segment has more than 4*TC vectors
+            u32x4 cur[GRP][TC];
+#pragma unroll
+            for (int g = 0; g < GRP; ++g) {
+                const u64 seg = (sg * GRP + g) * 16 + row;
+#pragma unroll
+                for (int t = 0; t < TC; ++t) {
+                    const unsigned vi = t0 + 4 * t + quarter;
+                    u32x4 v = {0u, 0u, 0u, 0u};
+                    if (seg < a.nseg && vi < a.nvec) v = load16<NT>(a.x + seg * a.nvec + vi);
+                    cur[g][t] = v;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 0; g < GRP; ++g)
+#pragma unroll
+                for (int t = 0; t < TC; ++t) R::consume(acc[g], cur[g][t]);
+        }
+#pragma unroll
+        for (int g = 0; g < GRP; ++g)
+            R::store(acc[g], (typename R::Out *)a.out, (sg * GRP + g) * 16, a.nseg, lane);
     }
 }
 

@@ -18,7 +18,7 @@ VARIANTS = {"auto": 0, "mfma": 1, "classic": 2}
 
 # every symbol include/redux.h declares
 SYMBOLS = (
-    "redux_sum", "redux_sum_segmented", "redux_mma_group_probe", "redux_calibration_copy",
+    "redux_sum", "redux_sum_segmented", "redux_sum_multipass", "redux_mma_group_probe", "redux_calibration_copy",
     "redux_set_variant", "redux_get_variant", "redux_set_param", "redux_get_param",
     "redux_strerror", "redux_last_hip_error", "redux_shutdown", "redux_version",
 )
@@ -46,6 +46,8 @@ def load():
         lib.redux_sum.argtypes = [vp, sz, ci, vp, vp]
         lib.redux_sum_segmented.restype = ci
         lib.redux_sum_segmented.argtypes = [vp, sz, sz, ci, vp, vp]
+        lib.redux_sum_multipass.restype = ci
+        lib.redux_sum_multipass.argtypes = [vp, sz, ci, vp, ctypes.POINTER(ci), vp]
         lib.redux_mma_group_probe.restype = ci
         lib.redux_mma_group_probe.argtypes = [vp, sz, ci, vp, vp, vp]
         lib.redux_calibration_copy.restype = ci
@@ -114,6 +116,13 @@ def sum_segmented_raw(x_ptr: int, nseg: int, seglen: int, dtype: int, out_ptr: i
     return load().redux_sum_segmented(x_ptr, nseg, seglen, dtype, out_ptr, stream)
 
 
+def sum_multipass_raw(x_ptr: int, n: int, dtype: int, out_ptr: int, stream: int = 0):
+    """Returns (status, levels)."""
+    levels = ctypes.c_int(0)
+    rc = load().redux_sum_multipass(x_ptr, n, dtype, out_ptr, ctypes.byref(levels), stream)
+    return rc, levels.value
+
+
 def mma_group_probe_raw(x_ptr: int, count: int, dtype: int, d_ptr: int, dp_ptr: int, stream: int = 0) -> int:
     return load().redux_mma_group_probe(x_ptr, count, dtype, d_ptr, dp_ptr, stream)
 
@@ -152,6 +161,19 @@ def sum(x, out=None):
     with torch.cuda.device(x.device):
         _check(sum_raw(x.data_ptr() if x.numel() else 0, x.numel(), dt, out.data_ptr(), stream), "redux_sum")
     return out
+
+
+def sum_multipass(x, out=None):
+    """The level-by-level form of the sum (one kernel launch per level); returns (1-element tensor, levels)."""
+    import torch
+    stream = _prep(x)
+    dt = _dtype_of(x)
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32 if dt == F16 else torch.int64, device=x.device)
+    with torch.cuda.device(x.device):
+        rc, levels = sum_multipass_raw(x.data_ptr() if x.numel() else 0, x.numel(), dt, out.data_ptr(), stream)
+    _check(rc, "redux_sum_multipass")
+    return out, levels
 
 
 def sum_segmented(x, nseg: Optional[int] = None, seglen: Optional[int] = None, out=None):

@@ -74,3 +74,19 @@ def test_segmented_config(variant):
     assert got.shape == (cfg.nseg,)
     assert np.all(np.abs(got - want) <= TOL * want_abs)
     print("C5 %s: worst err/sum|x| %.3g" % (variant, np.max(np.abs(got - want) / want_abs)))
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4"])
+def test_multipass_configs(name):
+    """The level-by-level form at full size: result and number of launches."""
+    from oracle import mma_reduction as mr
+    cfg, host, x, want = config_data(name)
+    out, levels = redux.sum_multipass(x)
+    torch.cuda.synchronize()
+    if cfg.dtype == "i8":
+        assert int(out.item()) == want[0]
+        assert levels == 1 + mr.expected_levels(-(-cfg.n // 512), 256)
+    else:
+        assert abs(float(out.item()) - want[0]) <= TOL * want[1]
+        assert levels == mr.expected_levels(cfg.n, 256)
+        print("%s multipass: levels %d err/sum|x| %.3g" % (name, levels, abs(float(out.item()) - want[0]) / want[1]))

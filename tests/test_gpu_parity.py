@@ -45,7 +45,8 @@ def default_params():
     for name, val in (("unroll", 0), ("nontemporal", 1), ("max_chain", 256),
                       ("max_grid", 16384), ("blocks_per_cu", DEFAULTS["blocks_per_cu"]),
                       ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
-                      ("finish", DEFAULTS["finish"])):
+                      ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("lit_unroll", 0),
+                      ("lit_blocks_per_cu", 0)):
         redux.set_param(name, val)
     redux.set_variant("auto")
 
@@ -350,3 +351,125 @@ def test_segmented_params(dev, variant):
             got = redux.sum_segmented(xd, 513, 4100)
             torch.cuda.synchronize()
             assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
+
+
+# ---- segmented sums: the short-segment (row per segment) and long-segment (pieces) kernels ----------------
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("seglen", [8, 16, 24, 32, 40, 64, 72, 128, 248, 256, 504, 512])
+def test_segmented_short_rows_f16(dev, variant, seglen):
+    redux.set_variant(variant)
+    for nseg in (1, 15, 16, 17, 100, 4097, 70000):
+        x = workloads.normal_f16(seglen + nseg, nseg * seglen)
+        xd = to_dev(x, dev)
+        want, want_abs = oracle.sum_segmented_f16(x, nseg, seglen)
+        got = redux.sum_segmented(xd, nseg, seglen)
+        redux.set_param("rows_max_vec", 0)                          # the general kernel on the same input
+        ref = redux.sum_segmented(xd, nseg, seglen)
+        redux.set_param("rows_max_vec", 64)
+        torch.cuda.synchronize()
+        assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
+        assert np.all(np.abs(ref.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("seglen", [16, 32, 48, 64, 128, 144, 512, 1008, 1024])
+def test_segmented_short_rows_i8(dev, variant, seglen):
+    redux.set_variant(variant)
+    for nseg in (1, 15, 16, 17, 100, 4097, 70000):
+        x = workloads.uniform_i8(seglen + nseg, nseg * seglen)
+        want, _ = oracle.sum_segmented_i8(x, nseg, seglen)
+        got = redux.sum_segmented(to_dev(x, dev), nseg, seglen)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), want)
+    # extremes: every element -128 / 127
+    for c in (-128, 127):
+        x = torch.full((1000 * seglen,), c, dtype=torch.int8, device=dev)
+        got = redux.sum_segmented(x, 1000, seglen)
+        torch.cuda.synchronize()
+        assert torch.all(got == c * seglen)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("nseg,seglen,parts", [(3, (1 << 20) + 3, 0), (2, 1 << 22, 0), (256, 65536, 0), (5, 100003, 8),
+                                               (1, (1 << 23) + 17, 0), (7, 5000, 4), (16, 1 << 16, 64), (3, 40, 2)])
+def test_segmented_long_pieces(dev, variant, nseg, seglen, parts):
+    redux.set_variant(variant)
+    redux.set_param("seg_parts", parts)
+    x = workloads.normal_f16(nseg + parts, nseg * seglen)
+    want, want_abs = oracle.sum_segmented_f16(x, nseg, seglen)
+    got = redux.sum_segmented(to_dev(x, dev, 1), nseg, seglen)
+    xi = workloads.uniform_i8(nseg + parts, nseg * seglen)
+    wanti, _ = oracle.sum_segmented_i8(xi, nseg, seglen)
+    goti = redux.sum_segmented(to_dev(xi, dev), nseg, seglen)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
+    assert np.array_equal(goti.cpu().numpy(), wanti)
+
+
+# ---- the level-by-level form (groups of m*m = 256, C = 0 per group, one launch per level) -------------------
+
+MULTIPASS_N = [0, 1, 2, 255, 256, 257, 511, 512, 513, 4095, 65535, 65536, 65537, 3 * 65536 + 17,
+               (1 << 20) + 3, (1 << 24) - 1, 1 << 24, (1 << 24) + 1]
+
+
+def i8_levels(n):
+    if n == 0:
+        return 0
+    n1 = -(-n // 512)
+    return 1 + (mr.expected_levels(n1, 256) if n1 > 1 else 0)
+
+
+@pytest.mark.parametrize("n", MULTIPASS_N)
+def test_multipass_f16(dev, n):
+    x = workloads.normal_f16(300 + n % 91, n)
+    xd = to_dev(x, dev) if n else torch.empty(0, dtype=torch.float16, device=dev)
+    out, levels = redux.sum_multipass(xd)
+    torch.cuda.synchronize()
+    check_f16(out.item(), x)
+    assert levels == mr.expected_levels(n, 256)          # ceil(log_{m*m} n) launches, m = 16
+
+
+@pytest.mark.parametrize("n", MULTIPASS_N)
+def test_multipass_i8(dev, n):
+    x = workloads.uniform_i8(400 + n % 91, n)
+    xd = to_dev(x, dev) if n else torch.empty(0, dtype=torch.int8, device=dev)
+    out, levels = redux.sum_multipass(xd)
+    torch.cuda.synchronize()
+    assert out.item() == oracle.sum_i8(x)[0]
+    assert levels == i8_levels(n)
+
+
+def test_multipass_misaligned_unrolls_and_closed_forms(dev):
+    for off in (1, 2, 3, 5):
+        for n in (100, 70001, (1 << 18) + 9):
+            x = workloads.uniform_f16(off, n, symmetric=True)
+            out, _ = redux.sum_multipass(to_dev(x, dev, off))
+            xi = workloads.uniform_i8(off, n)
+            outi, _ = redux.sum_multipass(to_dev(xi, dev, off))
+            torch.cuda.synchronize()
+            check_f16(out.item(), x)
+            assert outi.item() == oracle.sum_i8(xi)[0]
+    n = (1 << 21) + 77
+    x = workloads.normal_f16(8, n)
+    xi = workloads.uniform_i8(8, n)
+    xd, xid = to_dev(x, dev), to_dev(xi, dev)
+    for unroll in (1, 2, 4, 8, 16):
+        for bpc, max_grid in ((4, 16384), (1, 3)):
+            redux.set_param("lit_unroll", unroll)
+            redux.set_param("lit_blocks_per_cu", bpc)
+            redux.set_param("max_grid", max_grid)
+            out, levels = redux.sum_multipass(xd)
+            outi, _ = redux.sum_multipass(xid)
+            torch.cuda.synchronize()
+            check_f16(out.item(), x)
+            assert outi.item() == oracle.sum_i8(xi)[0] and levels == 3
+    for n in (256, 65536, 1 << 22):
+        out, levels = redux.sum_multipass(torch.ones(n, dtype=torch.float16, device=dev))
+        outi, _ = redux.sum_multipass(torch.full((n,), -128, dtype=torch.int8, device=dev))
+        torch.cuda.synchronize()
+        assert out.item() == float(n) and outi.item() == -128 * n
+    sub = torch.full((70000,), 2.0 ** -24, dtype=torch.float16, device=dev)
+    out, _ = redux.sum_multipass(sub)
+    torch.cuda.synchronize()
+    assert abs(out.item() - 70000 * 2.0 ** -24) <= TOL * 70000 * 2.0 ** -24
