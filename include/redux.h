@@ -102,11 +102,12 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
 
 /*
  * redux_sum_multipass -- the same sum computed exactly as Sections IV-A and IV-B lay the algorithm out,
- * level by level: the input is cut into contiguous groups of m*m = 256 numbers (the first int8 level:
- * 512, the narrowest int8 tile being 16 x 32); every group goes through both MMAs with C = 0
+ * level by level: the input is cut into contiguous groups of m*m numbers (m = 16 unless the "lit_m"
+ * parameter says 4 or 32; int8: always 512 on the first level, the narrowest int8 tile being 16 x 32,
+ * then 256); every group goes through both MMAs with C = 0
  * (D = A x 1, D' = 1 x D) and the thread in charge writes D'[1,1] into an array of partial sums in
  * global memory; each level is one kernel launch and the partial sums are the next level's input,
- * until one value is left (recurrence R_tc; ceil(log_256 n) levels for binary16).  A last group that
+ * until one value is left (recurrence R_tc; ceil(log_{m*m} n) levels for binary16).  A last group that
  * is not full is zero padded.  Binary16: partial sums are binary32 at every level.  Int8: int32 inside
  * the first MMA, int64 partial sums, later levels in binary64 (exact below 2^53).
  *
@@ -158,10 +159,11 @@ int redux_get_variant(void);
  *                               aligned) take the sixteen-segments-per-wavefront kernel; 0 = never (default 64)
  *   "seg_parts"         0,1,2,4,...,4096  segmented sum: pieces a long segment is cut into; 0 = from the
  *                               shape (default 0); ignored if nseg * pieces exceeds the workspace (16384)
- *   "lit_unroll"        0,1,2,4,8,16  redux_sum_multipass: groups per wavefront iteration; 0 = 16 for
- *                               binary16, 4 for int8 (default 0)
- *   "lit_blocks_per_cu" 0..16   redux_sum_multipass: 256-thread blocks per compute unit; 0 = 4 for binary16,
- *                               8 for int8 (default 0)
+ *   "lit_m"             4,16,32 redux_sum_multipass, binary16: linear size m of the MMA matrices (default 16)
+ *   "lit_unroll"        0,1,2,4,8,16  redux_sum_multipass: wavefront steps per loop iteration; 0 = the
+ *                               measured best for the shape (default 0)
+ *   "lit_blocks_per_cu" 0..16   redux_sum_multipass: 256-thread blocks per compute unit; 0 = the measured
+ *                               best for the shape (default 0)
  *   "layout"            0..2    which part of the array a block reads: 0 = blocks interleaved over the
  *                               whole array, 1 = one contiguous share per block, 2 = one contiguous
  *                               eighth per accelerator die, interleaved among that die's blocks (default 2)

@@ -63,8 +63,14 @@ def group_reduce(group: np.ndarray, rows: int, depth: int | None = None, cols: i
     return D, Dp
 
 
-def reduce_level(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=np.float64) -> np.ndarray:
-    """One level: every group of rows*depth inputs is replaced by its D'[0, 0]."""
+def reduce_level(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=np.float64,
+                 store_dtype=None) -> np.ndarray:
+    """One level: every group of rows*depth inputs is replaced by its D'[0, 0].
+
+    ``store_dtype`` is the type of the array the partial sums are written to.  The paper writes
+    them back into X itself (Section IV-B), whose elements are binary16, while noting that D can
+    be kept in FP32 (Section I-B); passing np.float16 here replays the first reading, None (keep
+    acc_dtype) the second."""
     depth = rows if depth is None else depth
     gsz = rows * depth
     x = np.asarray(x).reshape(-1)
@@ -73,11 +79,14 @@ def reduce_level(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=n
     for k in range(ngroups):
         _, Dp = group_reduce(x[k * gsz: (k + 1) * gsz], rows, depth, acc_dtype=acc_dtype)
         out[k] = Dp[0, 0]
+    if store_dtype is not None:
+        with np.errstate(over="ignore"):
+            out = out.astype(store_dtype).astype(acc_dtype)
     return out
 
 
-def reduce_tc(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=np.float64
-              ) -> Tuple[float, int, List[int]]:
+def reduce_tc(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=np.float64,
+              store_dtype=None) -> Tuple[float, int, List[int]]:
     """R_tc(X): apply levels until one value is left.
 
     Returns (result, number of levels, problem size entering each level).
@@ -90,7 +99,7 @@ def reduce_tc(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=np.f
     cur = x
     while True:
         sizes.append(int(cur.size))
-        cur = reduce_level(cur, rows, depth, acc_dtype=acc_dtype)
+        cur = reduce_level(cur, rows, depth, acc_dtype=acc_dtype, store_dtype=store_dtype)
         if cur.size == 1:
             return cur[0].item(), len(sizes), sizes
 

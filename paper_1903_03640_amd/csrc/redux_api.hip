@@ -29,6 +29,7 @@ struct Settings {
     long seg_parts = 0;           // 0 = pieces per long segment chosen from the shape
     long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
     long lit_blocks_per_cu = 0;
+    long lit_m = 16;              // linear size m of the MMA matrices of the level-by-level form
     long finish = -1;             // -1 = from the grid size
 };
 Settings g_set;
@@ -125,23 +126,25 @@ int get_level_buffers(int dev, hipStream_t st, size_t bytes0, size_t bytes1, Lev
     return REDUX_OK;
 }
 
-template <int U>
-void launch_literal_level(int dtype, bool first, bool fast, const void *in, u64 n, void *outp, unsigned grid, hipStream_t st)
+template <int M, int U>
+void launch_literal_f16(bool first, bool fast, const void *in, u64 n, void *outp, unsigned grid, hipStream_t st)
 {
-    if (dtype == REDUX_F16) {
-        if (first) {
-            if (fast) hipLaunchKernelGGL((literal_level_f16_kernel<U, true>), dim3(grid), dim3(kBlock), 0, st, (const unsigned short *)in, n, (float *)outp);
-            else      hipLaunchKernelGGL((literal_level_f16_kernel<U, false>), dim3(grid), dim3(kBlock), 0, st, (const unsigned short *)in, n, (float *)outp);
-        } else {
-            hipLaunchKernelGGL((literal_level_f32_kernel<U>), dim3(grid), dim3(kBlock), 0, st, (const float *)in, n, (float *)outp);
-        }
+    if (first) {
+        if (fast) hipLaunchKernelGGL((literal_level_kernel<M, true, U, true>), dim3(grid), dim3(kBlock), 0, st, in, n, (float *)outp);
+        else      hipLaunchKernelGGL((literal_level_kernel<M, true, U, false>), dim3(grid), dim3(kBlock), 0, st, in, n, (float *)outp);
     } else {
-        if (first) {
-            if (fast) hipLaunchKernelGGL((literal_level_i8_kernel<U, true>), dim3(grid), dim3(kBlock), 0, st, (const signed char *)in, n, (i64 *)outp);
-            else      hipLaunchKernelGGL((literal_level_i8_kernel<U, false>), dim3(grid), dim3(kBlock), 0, st, (const signed char *)in, n, (i64 *)outp);
-        } else {
-            hipLaunchKernelGGL((literal_level_i64_kernel<U>), dim3(grid), dim3(kBlock), 0, st, (const i64 *)in, n, (i64 *)outp);
-        }
+        hipLaunchKernelGGL((literal_level_kernel<M, false, U, true>), dim3(grid), dim3(kBlock), 0, st, in, n, (float *)outp);
+    }
+}
+
+template <int U>
+void launch_literal_i8(bool first, bool fast, const void *in, u64 n, void *outp, unsigned grid, hipStream_t st)
+{
+    if (first) {
+        if (fast) hipLaunchKernelGGL((literal_level_i8_kernel<U, true>), dim3(grid), dim3(kBlock), 0, st, (const signed char *)in, n, (i64 *)outp);
+        else      hipLaunchKernelGGL((literal_level_i8_kernel<U, false>), dim3(grid), dim3(kBlock), 0, st, (const signed char *)in, n, (i64 *)outp);
+    } else {
+        hipLaunchKernelGGL((literal_level_i64_kernel<U>), dim3(grid), dim3(kBlock), 0, st, (const i64 *)in, n, (i64 *)outp);
     }
 }
 
@@ -220,6 +223,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "max_grid")) { *lo = 1; *hi = kMaxGrid; return &g_set.max_grid; }
     if (!std::strcmp(name, "rows_max_vec")) { *lo = 0; *hi = 64; return &g_set.rows_max_vec; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
+    if (!std::strcmp(name, "lit_m")) { *lo = 4; *hi = 32; return &g_set.lit_m; }
     if (!std::strcmp(name, "lit_unroll")) { *lo = 0; *hi = 16; return &g_set.lit_unroll; }
     if (!std::strcmp(name, "lit_blocks_per_cu")) { *lo = 0; *hi = 16; return &g_set.lit_blocks_per_cu; }
     if (!std::strcmp(name, "layout")) { *lo = 0; *hi = 2; return &g_set.layout; }
@@ -447,36 +451,53 @@ int redux_sum_multipass(const void *x, size_t n, int dtype, void *out, int *leve
     if (e != hipSuccess) return hip_fail(e);
     if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
 
-    const u64 first_group = dtype == REDUX_F16 ? kLitGroup : kLitGroupI8;
+    // group size m*m (m = 4, 16 or 32) for binary16; the int8 form has one shape (16 x 32, then 16 x 16)
+    const int m = dtype == REDUX_F16 ? (int)g_set.lit_m : 16;
+    const u64 group = (u64)m * m;
+    const u64 first_group = dtype == REDUX_F16 ? group : (u64)kLitGroupI8;
+    const u64 tile = m == 32 ? 1024 : 256;                                   // elements one wavefront step consumes
     const size_t ps = dtype == REDUX_F16 ? sizeof(float) : sizeof(i64);     // size of a partial sum
     const u64 n1 = ((u64)n + first_group - 1) / first_group;                 // partial sums after level 1
-    const u64 n2 = (n1 + kLitGroup - 1) / kLitGroup;                         // ... after level 2
+    const u64 n2 = (n1 + group - 1) / group;                                 // ... after level 2
     LevelBuffers lb;
     if (n1 > 1 && (rc = get_level_buffers(dev, st, (size_t)n1 * ps + 16, (size_t)n2 * ps + 16, &lb)) != REDUX_OK) return rc;
 
-    // measured best on MI355X (the kernels are bound by the matrix unit, not by HBM)
-    const int U = g_set.lit_unroll ? (int)g_set.lit_unroll : (dtype == REDUX_F16 ? 16 : 4);
-    const u64 bpc = g_set.lit_blocks_per_cu ? (u64)g_set.lit_blocks_per_cu : (dtype == REDUX_F16 ? 4 : 8);
+    // measured best on MI355X (these kernels are bound by the matrix unit, not by HBM)
+    const int U = g_set.lit_unroll ? (int)g_set.lit_unroll : (dtype == REDUX_I8 ? 4 : m == 4 ? 4 : m == 16 ? 16 : 8);
+    const u64 bpc = g_set.lit_blocks_per_cu ? (u64)g_set.lit_blocks_per_cu : (dtype == REDUX_I8 ? 8 : m == 32 ? 2 : 4);
     const void *in = x;
     u64 count = n;
     int level = 0;
     while (true) {
-        const u64 group = level == 0 ? first_group : (u64)kLitGroup;
-        const u64 ngroups = (count + group - 1) / group;
+        const u64 gsz = level == 0 ? first_group : group;
+        const u64 ngroups = (count + gsz - 1) / gsz;
+        const u64 ntiles = dtype == REDUX_F16 ? (count + tile - 1) / tile : ngroups;
         void *outp = ngroups == 1 ? out : lb.buf[level & 1];
-        const u64 nbatch = (ngroups + U - 1) / U;
+        const u64 nbatch = (ntiles + U - 1) / U;
         u64 blocks = (nbatch + kWaves - 1) / kWaves;
         u64 gmax = (u64)cus * bpc;
         if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
         const unsigned grid = (unsigned)(blocks < gmax ? blocks : gmax);
-        const bool fast = ((uintptr_t)in % 8) == 0;
-        switch (U) {
-        case 16: launch_literal_level<16>(dtype, level == 0, fast, in, count, outp, grid, st); break;
-        case 8: launch_literal_level<8>(dtype, level == 0, fast, in, count, outp, grid, st); break;
-        case 4: launch_literal_level<4>(dtype, level == 0, fast, in, count, outp, grid, st); break;
-        case 2: launch_literal_level<2>(dtype, level == 0, fast, in, count, outp, grid, st); break;
-        default: launch_literal_level<1>(dtype, level == 0, fast, in, count, outp, grid, st); break;
+        const bool first = level == 0;
+        const bool fast = ((uintptr_t)in % (dtype == REDUX_F16 && m == 32 ? 16 : 8)) == 0;
+#define REDUX_LIT_U(CALL) switch (U) { case 16: CALL(16); break; case 8: CALL(8); break; case 4: CALL(4); break; \
+                                       case 2: CALL(2); break; default: CALL(1); break; }
+        if (dtype == REDUX_F16) {
+#define REDUX_LIT_M4(UU) launch_literal_f16<4, UU>(first, fast, in, count, outp, grid, st)
+#define REDUX_LIT_M16(UU) launch_literal_f16<16, UU>(first, fast, in, count, outp, grid, st)
+#define REDUX_LIT_M32(UU) launch_literal_f16<32, UU>(first, fast, in, count, outp, grid, st)
+            if (m == 4) REDUX_LIT_U(REDUX_LIT_M4)
+            else if (m == 32) REDUX_LIT_U(REDUX_LIT_M32)
+            else REDUX_LIT_U(REDUX_LIT_M16)
+#undef REDUX_LIT_M4
+#undef REDUX_LIT_M16
+#undef REDUX_LIT_M32
+        } else {
+#define REDUX_LIT_I8(UU) launch_literal_i8<UU>(first, fast, in, count, outp, grid, st)
+            REDUX_LIT_U(REDUX_LIT_I8)
+#undef REDUX_LIT_I8
         }
+#undef REDUX_LIT_U
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
         ++level;
@@ -547,6 +568,7 @@ int redux_set_param(const char *name, long value)
     if (!slot || value < lo || value > hi) return REDUX_ERR_PARAM;
     if ((slot == &g_set.unroll || slot == &g_set.seg_parts || slot == &g_set.lit_unroll) && (value & (value - 1)) != 0)
         return REDUX_ERR_PARAM;   // 0 or a power of two
+    if (slot == &g_set.lit_m && value != 4 && value != 16 && value != 32) return REDUX_ERR_PARAM;
     *slot = value;
     return REDUX_OK;
 }

@@ -49,93 +49,176 @@ __device__ __forceinline__ double lit_mma2_f64(f64x4 d)
     return dp[0];
 }
 
-// ---- level over the binary16 input -------------------------------------------------------------------------
-// One wavefront reduces U groups per iteration and writes U consecutive partial sums.
-// FAST: x is 8-byte aligned, so a lane's four elements are one 8-byte load; otherwise element loads.
-template <int U, bool FAST>
-__global__ void __launch_bounds__(kBlock) literal_level_f16_kernel(const unsigned short *x, u64 n, float *partial)
-{
-    const unsigned lane = threadIdx.x & 63u;
-    const u64 wave_global = (u64)blockIdx.x * kWaves + (threadIdx.x >> 6);
-    const u64 nwaves = (u64)gridDim.x * kWaves;
-    const u64 ngroups = (n + kLitGroup - 1) / kLitGroup;
-    const u64 nfull = n / kLitGroup;
-    const u64 nbatch = (ngroups + U - 1) / U;
-    const f16x4 ones = {1, 1, 1, 1};
+// ---- group shapes: m = 4, 16, 32 -----------------------------------------------------------------------------
+// A "tile" is what one wavefront pushes through one first-MMA / second-MMA sequence:
+//   m = 4    sixteen groups of 16 at once (the 4x4x4 MFMA works on 16 independent blocks; block b = lanes 4b..4b+3);
+//            the sixteen results sit in lanes 0, 4, 8, ...
+//   m = 16   one group of 256; the result sits in every lane
+//   m = 32   one group of 1024 (four K-slices of 32x32x8 for binary16, sixteen of 32x32x2 for binary32)
+// Both levels of a shape consume the lane's raw words in order: word w of lane l is byte
+// (w / kChunkWords) * 64 * kChunkBytes + l * kChunkBytes + (w % kChunkWords) * 4 of the tile, so that every load
+// instruction of the wavefront is contiguous.
+template <int M> struct LitShape;
 
-    for (u64 b = wave_global; b < nbatch; b += nwaves) {
-        const u64 g0 = b * U;
-        u32x2 raw[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const u64 g = g0 + u;
-            u32x2 v = {0u, 0u};
-            if (FAST && g < nfull) {
-                v = __builtin_nontemporal_load((const u32x2 *)(x + g * kLitGroup) + lane);
-            } else if (g < ngroups) {                      // ragged last group or unaligned input: zero padded
-                unsigned short e[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const u64 idx = g * kLitGroup + 4 * lane + k;
-                    e[k] = idx < n ? x[idx] : (unsigned short)0;
-                }
-                v = u32x2{(unsigned)e[0] | ((unsigned)e[1] << 16), (unsigned)e[2] | ((unsigned)e[3] << 16)};
-            }
-            raw[u] = v;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        float mine = 0.f;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};       // C = 0 for every group
-            f32x4 d = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, raw[u]), ones, zero, 0, 0, 0);
-            const float group_sum = lit_mma2_f32(d);
-            if (lane == (unsigned)u) mine = group_sum;     // lane u is in charge of group g0 + u
-        }
-        if (lane < (unsigned)U && g0 + lane < ngroups) partial[g0 + lane] = mine;
+template <> struct LitShape<4> {
+    static constexpr unsigned kGroup = 16, kTileElems = 256, kResults = 16;
+    static __device__ __forceinline__ void mma_f16(const unsigned *raw, float *res)
+    {
+        const f16x4 ones = {1, 1, 1, 1};
+        const f16x4 a = __builtin_bit_cast(f16x4, u32x2{raw[0], raw[1]});
+        f32x4 d = __builtin_amdgcn_mfma_f32_4x4x4f16(a, ones, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);   // D_b = A_b x 1
+        *res = mma2(d);
     }
-}
+    static __device__ __forceinline__ void mma_f32(const unsigned *raw, float *res)
+    {
+        f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < 4; ++k)                            // A_b[i][k] x 1, one K-slice at a time
+            d = __builtin_amdgcn_mfma_f32_4x4x1f32(__builtin_bit_cast(float, raw[k]), 1.0f, d, 0, 0, 0);
+        *res = mma2(d);
+    }
+    // lane 4b+j, register i of D holds D_b[i][j]; used as the B operand of a 4x4x1 step it is row i of D_b
+    static __device__ __forceinline__ float mma2(f32x4 d)
+    {
+        f32x4 dp = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) dp = __builtin_amdgcn_mfma_f32_4x4x1f32(1.0f, d[k], dp, 0, 0, 0);
+        return dp[0];
+    }
+};
 
-// ---- level over binary32 partial sums (16-byte aligned, library-owned) ----------------------------------------
-template <int U>
-__global__ void __launch_bounds__(kBlock) literal_level_f32_kernel(const float *x, u64 n, float *partial)
+template <> struct LitShape<16> {
+    static constexpr unsigned kGroup = 256, kTileElems = 256, kResults = 1;
+    static __device__ __forceinline__ void mma_f16(const unsigned *raw, float *res)
+    {
+        const f16x4 ones = {1, 1, 1, 1};
+        const f16x4 a = __builtin_bit_cast(f16x4, u32x2{raw[0], raw[1]});
+        f32x4 d = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        *res = lit_mma2_f32(d);
+    }
+    static __device__ __forceinline__ void mma_f32(const unsigned *raw, float *res)
+    {
+        f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            d = __builtin_amdgcn_mfma_f32_16x16x4f32(__builtin_bit_cast(float, raw[k]), 1.0f, d, 0, 0, 0);
+        *res = lit_mma2_f32(d);
+    }
+};
+
+template <> struct LitShape<32> {
+    static constexpr unsigned kGroup = 1024, kTileElems = 1024, kResults = 1;
+    typedef float f32x16 __attribute__((ext_vector_type(16)));
+    static __device__ __forceinline__ f32x16 zero16()
+    {
+        f32x16 z;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) z[r] = 0.f;
+        return z;
+    }
+    // lane l, register r of a 32x32 accumulator holds D[8*(r/4) + 4*(l/32) + r%4][l%32]; as the B operand of
+    // a 32x32x2 step (B[l/32][l%32]) register r contributes two rows, and sixteen chained steps cover all 32.
+    static __device__ __forceinline__ float mma2(f32x16 d)
+    {
+        f32x16 dp = zero16();
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dp = __builtin_amdgcn_mfma_f32_32x32x2f32(1.0f, d[r], dp, 0, 0, 0);
+        return dp[0];
+    }
+    static __device__ __forceinline__ void mma_f16(const unsigned *raw, float *res)
+    {
+        const f16x4 ones = {1, 1, 1, 1};
+        f32x16 d = zero16();
+#pragma unroll
+        for (int t = 0; t < 4; ++t)                            // K = 32 as four slices of 8
+            d = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_bit_cast(f16x4, u32x2{raw[2 * t], raw[2 * t + 1]}), ones, d, 0, 0, 0);
+        *res = mma2(d);
+    }
+    static __device__ __forceinline__ void mma_f32(const unsigned *raw, float *res)
+    {
+        f32x16 d = zero16();
+#pragma unroll
+        for (int k = 0; k < 16; ++k)                           // K = 32 as sixteen slices of 2
+            d = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, raw[k]), 1.0f, d, 0, 0, 0);
+        *res = mma2(d);
+    }
+};
+
+// ---- one level: binary16 input (F16IN) or binary32 partial sums -------------------------------------------------
+// One wavefront reduces U tiles per iteration.  FAST: the input is aligned to the load width, so a lane's
+// words come from 8- or 16-byte loads; otherwise (and for the ragged last tile) element loads with zero padding.
+template <int M, bool F16IN, int U, bool FAST>
+__global__ void __launch_bounds__(kBlock) literal_level_kernel(const void *xin, u64 n, float *partial)
 {
+    typedef LitShape<M> S;
+    constexpr unsigned kElemBytes = F16IN ? 2 : 4;
+    constexpr unsigned kWords = S::kTileElems * kElemBytes / 4 / 64;      // raw 32-bit words per lane per tile
+    constexpr unsigned kChunkWords = kWords >= 4 ? 4 : kWords;            // words per load instruction (2 or 4)
+    constexpr unsigned kChunkBytes = kChunkWords * 4;
+    constexpr unsigned kChunks = kWords / kChunkWords;
     const unsigned lane = threadIdx.x & 63u;
     const u64 wave_global = (u64)blockIdx.x * kWaves + (threadIdx.x >> 6);
     const u64 nwaves = (u64)gridDim.x * kWaves;
-    const u64 ngroups = (n + kLitGroup - 1) / kLitGroup;
-    const u64 nfull = n / kLitGroup;
-    const u64 nbatch = (ngroups + U - 1) / U;
+    const u64 ngroups = (n + S::kGroup - 1) / S::kGroup;
+    const u64 ntiles = (n + S::kTileElems - 1) / S::kTileElems;
+    const u64 nfull = n / S::kTileElems;
+    const u64 nbatch = (ntiles + U - 1) / U;
+    const unsigned char *x = (const unsigned char *)xin;
 
     for (u64 b = wave_global; b < nbatch; b += nwaves) {
-        const u64 g0 = b * U;
-        f32x4 raw[U];
+        const u64 t0 = b * U;
+        unsigned raw[U][kWords];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const u64 g = g0 + u;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (g < nfull) {
-                v = *((const f32x4 *)(x + g * kLitGroup) + lane);
-            } else if (g < ngroups) {
+            const u64 t = t0 + u;
+            const unsigned char *tile = x + t * S::kTileElems * kElemBytes;
+            if (FAST && t < nfull) {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const u64 idx = g * kLitGroup + 4 * lane + k;
-                    v[k] = idx < n ? x[idx] : 0.f;
+                for (unsigned c = 0; c < kChunks; ++c) {
+                    const unsigned char *p = tile + (u64)c * 64 * kChunkBytes + lane * kChunkBytes;
+                    if (kChunkWords == 4) {
+                        u32x4 v = F16IN ? __builtin_nontemporal_load((const u32x4 *)p) : *(const u32x4 *)p;
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) raw[u][4 * c + w] = v[w];
+                    } else {
+                        u32x2 v = F16IN ? __builtin_nontemporal_load((const u32x2 *)p) : *(const u32x2 *)p;
+                        raw[u][2 * c] = v[0];
+                        raw[u][2 * c + 1] = v[1];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (unsigned w = 0; w < kWords; ++w) {
+                    unsigned word = 0;
+                    if (t < ntiles) {
+                        const u64 byte0 = (u64)(w / kChunkWords) * 64 * kChunkBytes + lane * kChunkBytes + (w % kChunkWords) * 4;
+                        const u64 e0 = t * S::kTileElems + byte0 / kElemBytes;       // first element of this word
+                        if (F16IN) {
+                            const unsigned short *h = (const unsigned short *)xin;
+                            const unsigned lo = e0 < n ? h[e0] : 0u, hi = e0 + 1 < n ? h[e0 + 1] : 0u;
+                            word = lo | (hi << 16);
+                        } else {
+                            word = e0 < n ? ((const unsigned *)xin)[e0] : 0u;
+                        }
+                    }
+                    raw[u][w] = word;
                 }
             }
-            raw[u] = v;
         }
         __builtin_amdgcn_sched_barrier(0);
         float mine = 0.f;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            f32x4 d = {0.f, 0.f, 0.f, 0.f};                // C = 0; the 16 x 16 x 16 product as four K-slices
-#pragma unroll
-            for (int k = 0; k < 4; ++k) d = __builtin_amdgcn_mfma_f32_16x16x4f32(raw[u][k], 1.0f, d, 0, 0, 0);
-            const float group_sum = lit_mma2_f32(d);
-            if (lane == (unsigned)u) mine = group_sum;
+            float res;
+            if (F16IN) S::mma_f16(raw[u], &res); else S::mma_f32(raw[u], &res);
+            if (S::kResults == 1) {
+                if (lane == (unsigned)u) mine = res;           // lane u is in charge of tile t0 + u
+            } else {                                           // m = 4: lane 4b is in charge of block b of the tile
+                const u64 g = (t0 + u) * S::kResults + (lane >> 2);
+                if ((lane & 3u) == 0 && g < ngroups) partial[g] = res;
+            }
         }
-        if (lane < (unsigned)U && g0 + lane < ngroups) partial[g0 + lane] = mine;
+        if (S::kResults == 1 && lane < (unsigned)U && t0 + lane < ngroups) partial[t0 + lane] = mine;
     }
 }
 

@@ -46,7 +46,7 @@ def default_params():
                       ("max_grid", 16384), ("blocks_per_cu", DEFAULTS["blocks_per_cu"]),
                       ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
                       ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("lit_unroll", 0),
-                      ("lit_blocks_per_cu", 0)):
+                      ("lit_blocks_per_cu", 0), ("lit_m", 16)):
         redux.set_param(name, val)
     redux.set_variant("auto")
 
@@ -420,14 +420,16 @@ def i8_levels(n):
     return 1 + (mr.expected_levels(n1, 256) if n1 > 1 else 0)
 
 
-@pytest.mark.parametrize("n", MULTIPASS_N)
-def test_multipass_f16(dev, n):
+@pytest.mark.parametrize("m", [4, 16, 32])
+@pytest.mark.parametrize("n", MULTIPASS_N + [15, 16, 17, 1023, 1024, 1025, (1 << 20) - 1])
+def test_multipass_f16(dev, n, m):
+    redux.set_param("lit_m", m)
     x = workloads.normal_f16(300 + n % 91, n)
     xd = to_dev(x, dev) if n else torch.empty(0, dtype=torch.float16, device=dev)
     out, levels = redux.sum_multipass(xd)
     torch.cuda.synchronize()
     check_f16(out.item(), x)
-    assert levels == mr.expected_levels(n, 256)          # ceil(log_{m*m} n) launches, m = 16
+    assert levels == mr.expected_levels(n, m * m)        # ceil(log_{m*m} n) launches
 
 
 @pytest.mark.parametrize("n", MULTIPASS_N)
@@ -440,7 +442,9 @@ def test_multipass_i8(dev, n):
     assert levels == i8_levels(n)
 
 
-def test_multipass_misaligned_unrolls_and_closed_forms(dev):
+@pytest.mark.parametrize("m", [4, 16, 32])
+def test_multipass_misaligned_unrolls_and_closed_forms(dev, m):
+    redux.set_param("lit_m", m)
     for off in (1, 2, 3, 5):
         for n in (100, 70001, (1 << 18) + 9):
             x = workloads.uniform_f16(off, n, symmetric=True)
@@ -463,7 +467,7 @@ def test_multipass_misaligned_unrolls_and_closed_forms(dev):
             outi, _ = redux.sum_multipass(xid)
             torch.cuda.synchronize()
             check_f16(out.item(), x)
-            assert outi.item() == oracle.sum_i8(xi)[0] and levels == 3
+            assert outi.item() == oracle.sum_i8(xi)[0] and levels == mr.expected_levels(n, m * m)
     for n in (256, 65536, 1 << 22):
         out, levels = redux.sum_multipass(torch.ones(n, dtype=torch.float16, device=dev))
         outi, _ = redux.sum_multipass(torch.full((n,), -128, dtype=torch.int8, device=dev))

@@ -98,3 +98,18 @@ def test_cost_model_values_printed_in_the_paper():
             assert mr.model_steps_classic(2) == val
         else:
             raise AssertionError(kind)
+
+
+def test_partial_sums_stored_as_binary16_lose_precision_and_overflow():
+    # Section IV-B writes each group's result back into X; if X stays binary16 the partial sums are
+    # rounded to 11 bits at every level and saturate to infinity above 65504.
+    x = np.random.default_rng(3).random(1 << 16).astype(np.float16)
+    exact = oracle.sum_f16(x)[0]
+    kept, _, _ = mr.reduce_tc(x, 16, acc_dtype=np.float32)
+    assert abs(kept - exact) <= 1e-6 * exact
+    rounded, _, _ = mr.reduce_tc(x, 16, acc_dtype=np.float32, store_dtype=np.float16)
+    assert 1e-6 * exact < abs(rounded - exact) < 1e-2 * exact
+    assert abs(rounded - exact) > 10 * abs(kept - exact)
+    big = np.ones(1 << 17, dtype=np.float16)            # true sum 131072 > 65504
+    assert mr.reduce_tc(big, 16, acc_dtype=np.float32)[0] == float(1 << 17)
+    assert np.isinf(mr.reduce_tc(big, 16, acc_dtype=np.float32, store_dtype=np.float16)[0])
