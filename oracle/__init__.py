@@ -44,7 +44,9 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        # REDUX_ORACLE_LIB: load this build instead; the mutation test points it at deliberately broken
+        # copies of redux_oracle.c to show that the pins catch them.
+        lib = ctypes.CDLL(os.environ.get("REDUX_ORACLE_LIB") or build())
         c_sz, c_dp = ctypes.c_size_t, ctypes.POINTER(ctypes.c_double)
         c_ip = ctypes.POINTER(ctypes.c_int64)
         vp = ctypes.c_void_p
