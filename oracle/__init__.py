@@ -65,6 +65,19 @@ def _load():
         lib.redux_oracle_sum_segmented_f16.argtypes = [vp, c_sz, c_sz, vp, vp]
         lib.redux_oracle_sum_segmented_i8.restype = ctypes.c_int
         lib.redux_oracle_sum_segmented_i8.argtypes = [vp, c_sz, c_sz, vp, vp]
+        for name in ("redux_oracle_sum_any", "redux_oracle_sum_any_neumaier"):
+            fn = getattr(lib, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = [vp, c_sz, ctypes.c_int, c_dp, c_dp]
+        lib.redux_oracle_sum_f8_exact.restype = ctypes.c_int
+        lib.redux_oracle_sum_f8_exact.argtypes = [vp, c_sz, ctypes.c_int, c_ip, c_ip, ctypes.POINTER(ctypes.c_int)]
+        lib.redux_oracle_sum_segmented_any.restype = ctypes.c_int
+        lib.redux_oracle_sum_segmented_any.argtypes = [vp, c_sz, c_sz, ctypes.c_int, vp, vp]
+        for name, argt in (("redux_oracle_bf16_decode", ctypes.c_uint16), ("redux_oracle_f32_decode", ctypes.c_uint32),
+                           ("redux_oracle_f8e4m3_decode", ctypes.c_uint8), ("redux_oracle_f8e5m2_decode", ctypes.c_uint8)):
+            fn = getattr(lib, name)
+            fn.restype = ctypes.c_double
+            fn.argtypes = [argt]
         _lib = lib
     return _lib
 
@@ -168,4 +181,60 @@ def sum_segmented_i8(x, nseg: int, seglen: int) -> Tuple[np.ndarray, np.ndarray]
     rc = _load().redux_oracle_sum_segmented_i8(_ptr(a), nseg, seglen, _ptr(s), _ptr(sa))
     if rc:
         raise RuntimeError("redux_oracle_sum_segmented_i8 failed: %d" % rc)
+    return s, sa
+
+
+# ---- bfloat16, binary32 and the OCP 8-bit formats (raw storage patterns in, binary64 out) --------------------
+
+BF16, F32, F8E4M3, F8E5M2 = 2, 3, 4, 5
+_STORAGE = {BF16: np.uint16, F32: np.uint32, F8E4M3: np.uint8, F8E5M2: np.uint8}
+
+
+def _as_storage(x, dtype: int) -> np.ndarray:
+    a = np.asarray(x)
+    want = _STORAGE[dtype]
+    if dtype == F32 and a.dtype == np.float32:
+        a = a.view(np.uint32)
+    if a.dtype != want:
+        raise TypeError("dtype %d wants %s storage (raw bit patterns), got %s" % (dtype, want.__name__, a.dtype))
+    return np.ascontiguousarray(a).reshape(-1)
+
+
+def decode(pattern: int, dtype: int) -> float:
+    """Exact binary64 value of one storage pattern of dtype BF16 / F32 / F8E4M3 / F8E5M2."""
+    fn = {BF16: "redux_oracle_bf16_decode", F32: "redux_oracle_f32_decode",
+          F8E4M3: "redux_oracle_f8e4m3_decode", F8E5M2: "redux_oracle_f8e5m2_decode"}[dtype]
+    return float(getattr(_load(), fn)(int(pattern)))
+
+
+def sum_any(x, dtype: int, method: str = "pairwise") -> Tuple[float, float]:
+    """(sum, sum|x|) of raw patterns of dtype BF16 / F32 / F8E4M3 / F8E5M2; method 'pairwise' or 'neumaier'."""
+    a = _as_storage(x, dtype)
+    s, sa = ctypes.c_double(), ctypes.c_double()
+    fn = "redux_oracle_sum_any" if method == "pairwise" else "redux_oracle_sum_any_neumaier"
+    rc = getattr(_load(), fn)(_ptr(a), a.size, dtype, ctypes.byref(s), ctypes.byref(sa))
+    if rc:
+        raise RuntimeError("%s failed: %d" % (fn, rc))
+    return s.value, sa.value
+
+
+def sum_f8_exact(x, dtype: int):
+    """Exact sum of an 8-bit format: (units, units of sum|x|, scale, nonfinite) with value = units * scale."""
+    a = _as_storage(x, dtype)
+    u, ua, nf = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int()
+    rc = _load().redux_oracle_sum_f8_exact(_ptr(a), a.size, dtype, ctypes.byref(u), ctypes.byref(ua), ctypes.byref(nf))
+    if rc:
+        raise RuntimeError("redux_oracle_sum_f8_exact failed: %d" % rc)
+    return u.value, ua.value, 2.0 ** (-9 if dtype == F8E4M3 else -16), bool(nf.value)
+
+
+def sum_segmented_any(x, nseg: int, seglen: int, dtype: int) -> Tuple[np.ndarray, np.ndarray]:
+    a = _as_storage(x, dtype)
+    if a.size != nseg * seglen:
+        raise ValueError("size %d != nseg*seglen %d" % (a.size, nseg * seglen))
+    s = np.zeros(nseg, dtype=np.float64)
+    sa = np.zeros(nseg, dtype=np.float64)
+    rc = _load().redux_oracle_sum_segmented_any(_ptr(a), nseg, seglen, dtype, _ptr(s), _ptr(sa))
+    if rc:
+        raise RuntimeError("redux_oracle_sum_segmented_any failed: %d" % rc)
     return s, sa

@@ -28,6 +28,11 @@
  *                    accumulated exactly in a 128-bit integer (n < 2^86) and
  *                    converted once.
  *   int8 input      -> int64 serial sum (exact for n < 2^56).
+ *   bfloat16, binary32, and the two 8-bit floating-point formats of the OCP
+ *   8-bit floating point specification (E4M3: no infinities, one NaN pattern per
+ *   sign; E5M2: IEEE-like) -> each value decoded exactly to binary64, then the
+ *   same pairwise and Neumaier sums; the 8-bit formats also have an exact
+ *   fixed-point sum (every value is a multiple of 2^-9 resp. 2^-16).
  *
  * Every routine also returns sum |x_i|, which the tolerance for cancelling
  * sums is stated against.
@@ -218,5 +223,157 @@ int redux_oracle_sum_segmented_i8(const int8_t *x, size_t nseg, size_t seglen,
         int rc = redux_oracle_sum_i8(x + s * seglen, seglen, &sum[s], &sum_abs[s]);
         if (rc) return rc;
     }
+    return ORACLE_OK;
+}
+
+/* ---- other floating-point element types: decode exactly, then the same sums ------------------------ */
+
+#define ORACLE_BF16 2
+#define ORACLE_F32 3
+#define ORACLE_F8E4M3 4
+#define ORACLE_F8E5M2 5
+#define ORACLE_ERR_DTYPE (-2)
+
+/* bfloat16: the upper 16 bits of a binary32 (1 sign, 8 exponent bits with bias 127, 7 fraction bits). */
+double redux_oracle_bf16_decode(uint16_t h)
+{
+    int sign = (h >> 15) & 1, e = (h >> 7) & 0xff, f = h & 0x7f;
+    double v;
+    if (e == 0) v = ldexp((double)f, -133);                  /* subnormal: f * 2^-7 * 2^-126 */
+    else if (e == 255) v = (f == 0) ? INFINITY : NAN;
+    else v = ldexp((double)(128 + f), e - 134);              /* (1 + f/128) * 2^(e-127) */
+    return sign ? -v : v;
+}
+
+/* binary32 from its bit pattern (1, 8 with bias 127, 23). */
+double redux_oracle_f32_decode(uint32_t w)
+{
+    int sign = (w >> 31) & 1, e = (w >> 23) & 0xff;
+    uint32_t f = w & 0x7fffffu;
+    double v;
+    if (e == 0) v = ldexp((double)f, -149);
+    else if (e == 255) v = (f == 0) ? INFINITY : NAN;
+    else v = ldexp((double)(0x800000u + f), e - 150);
+    return sign ? -v : v;
+}
+
+/* OCP E4M3: 1 sign, 4 exponent bits (bias 7), 3 fraction bits; no infinities; S.1111.111 is NaN;
+ * largest finite value 448 = 1.75 * 2^8. */
+double redux_oracle_f8e4m3_decode(uint8_t b)
+{
+    int sign = (b >> 7) & 1, e = (b >> 3) & 0xf, f = b & 7;
+    double v;
+    if (e == 15 && f == 7) v = NAN;
+    else if (e == 0) v = ldexp((double)f, -9);               /* f/8 * 2^-6 */
+    else v = ldexp((double)(8 + f), e - 10);                 /* (1 + f/8) * 2^(e-7) */
+    return sign ? -v : v;
+}
+
+/* OCP E5M2: 1 sign, 5 exponent bits (bias 15), 2 fraction bits; IEEE-like infinities and NaNs. */
+double redux_oracle_f8e5m2_decode(uint8_t b)
+{
+    int sign = (b >> 7) & 1, e = (b >> 2) & 0x1f, f = b & 3;
+    double v;
+    if (e == 31) v = (f == 0) ? INFINITY : NAN;
+    else if (e == 0) v = ldexp((double)f, -16);              /* f/4 * 2^-14 */
+    else v = ldexp((double)(4 + f), e - 17);                 /* (1 + f/4) * 2^(e-15) */
+    return sign ? -v : v;
+}
+
+static double decode_at(const void *x, size_t i, int dtype)
+{
+    switch (dtype) {
+    case ORACLE_BF16: return redux_oracle_bf16_decode(((const uint16_t *)x)[i]);
+    case ORACLE_F32: return redux_oracle_f32_decode(((const uint32_t *)x)[i]);
+    case ORACLE_F8E4M3: return redux_oracle_f8e4m3_decode(((const uint8_t *)x)[i]);
+    default: return redux_oracle_f8e5m2_decode(((const uint8_t *)x)[i]);
+    }
+}
+
+static void pairwise_any(const void *x, size_t lo, size_t n, int dtype, double *s, double *a)
+{
+    if (n <= 128) {
+        double ss = 0.0, aa = 0.0;
+        for (size_t i = 0; i < n; ++i) {
+            double v = decode_at(x, lo + i, dtype);
+            ss += v;
+            aa += fabs(v);
+        }
+        *s = ss;
+        *a = aa;
+        return;
+    }
+    size_t half = n / 2;
+    double s0, a0, s1, a1;
+    pairwise_any(x, lo, half, dtype, &s0, &a0);
+    pairwise_any(x, lo + half, n - half, dtype, &s1, &a1);
+    *s = s0 + s1;
+    *a = a0 + a1;
+}
+
+/* Primary oracle for dtype 2..5: binary64 pairwise sum and sum of |x|. */
+int redux_oracle_sum_any(const void *x, size_t n, int dtype, double *sum, double *sum_abs)
+{
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F8E5M2) return ORACLE_ERR_DTYPE;
+    if ((n && !x) || !sum || !sum_abs) return ORACLE_ERR_NULL;
+    pairwise_any(x, 0, n, dtype, sum, sum_abs);
+    return ORACLE_OK;
+}
+
+/* Cross-check for dtype 2..5: Neumaier-compensated serial sum. */
+int redux_oracle_sum_any_neumaier(const void *x, size_t n, int dtype, double *sum, double *sum_abs)
+{
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F8E5M2) return ORACLE_ERR_DTYPE;
+    if ((n && !x) || !sum || !sum_abs) return ORACLE_ERR_NULL;
+    double s = 0.0, c = 0.0, a = 0.0;
+    int nonfinite = 0;
+    for (size_t i = 0; i < n; ++i) {
+        double v = decode_at(x, i, dtype);
+        if (!isfinite(v)) nonfinite = 1;
+        double tt = s + v;
+        if (fabs(s) >= fabs(v)) c += (s - tt) + v;
+        else                    c += (v - tt) + s;
+        s = tt;
+        a += fabs(v);
+    }
+    *sum = nonfinite ? s : s + c;
+    *sum_abs = a;
+    return ORACLE_OK;
+}
+
+/* Exact fixed-point sum for the 8-bit formats, in units of 2^-9 (E4M3) or 2^-16 (E5M2); NaN/Inf are
+ * skipped and reported.  |units| <= 448 * 2^9 resp. 57344 * 2^16 per element, so int64 holds any n < 2^31. */
+int redux_oracle_sum_f8_exact(const uint8_t *x, size_t n, int dtype, int64_t *units, int64_t *units_abs, int *nonfinite)
+{
+    if (dtype != ORACLE_F8E4M3 && dtype != ORACLE_F8E5M2) return ORACLE_ERR_DTYPE;
+    if ((n && !x) || !units || !units_abs || !nonfinite) return ORACLE_ERR_NULL;
+    int64_t s = 0, a = 0;
+    int nf = 0;
+    for (size_t i = 0; i < n; ++i) {
+        uint8_t b = x[i];
+        int64_t u;
+        if (dtype == ORACLE_F8E4M3) {
+            int e = (b >> 3) & 0xf, f = b & 7;
+            if (e == 15 && f == 7) { nf = 1; continue; }
+            u = e == 0 ? f : (int64_t)(8 + f) << (e - 1);      /* (8+f) * 2^(e-10) = ((8+f) << (e-1)) * 2^-9 */
+        } else {
+            int e = (b >> 2) & 0x1f, f = b & 3;
+            if (e == 31) { nf = 1; continue; }
+            u = e == 0 ? f : (int64_t)(4 + f) << (e - 1);      /* (4+f) * 2^(e-17) = ((4+f) << (e-1)) * 2^-16 */
+        }
+        a += u;
+        s += (b & 0x80) ? -u : u;
+    }
+    *units = s;
+    *units_abs = a;
+    *nonfinite = nf;
+    return ORACLE_OK;
+}
+
+int redux_oracle_sum_segmented_any(const void *x, size_t nseg, size_t seglen, int dtype, double *sum, double *sum_abs)
+{
+    if (dtype < ORACLE_BF16 || dtype > ORACLE_F8E5M2) return ORACLE_ERR_DTYPE;
+    if ((nseg && seglen && !x) || (nseg && (!sum || !sum_abs))) return ORACLE_ERR_NULL;
+    for (size_t s = 0; s < nseg; ++s) pairwise_any(x, s * seglen, seglen, dtype, &sum[s], &sum_abs[s]);
     return ORACLE_OK;
 }
