@@ -41,8 +41,12 @@ extern "C" {
 
 /* Element type of the input array. */
 typedef enum {
-    REDUX_F16 = 0, /* IEEE binary16 in, binary32 MMA accumulation, one binary32 result */
-    REDUX_I8  = 1  /* int8 in, int32 MMA accumulation flushed to int64, one int64 result */
+    REDUX_F16    = 0, /* IEEE binary16 in, binary32 MMA accumulation, one binary32 result (the paper's case) */
+    REDUX_I8     = 1, /* int8 in, int32 MMA accumulation flushed to int64, one int64 result */
+    REDUX_BF16   = 2, /* bfloat16 in (v_mfma_f32_16x16x32_bf16), binary32 accumulation and result */
+    REDUX_F32    = 3, /* binary32 in (v_mfma_f32_16x16x4_f32, four K-slices per 16-byte load), binary32 result */
+    REDUX_F8E4M3 = 4, /* OCP 8-bit E4M3 in (v_mfma_f32_16x16x32_fp8_fp8), binary32 accumulation and result */
+    REDUX_F8E5M2 = 5  /* OCP 8-bit E5M2 in (v_mfma_f32_16x16x32_bf8_bf8), binary32 accumulation and result */
 } redux_dtype;
 
 typedef enum {
@@ -59,7 +63,7 @@ typedef enum {
 
 /* Which kernel family computes the sum. */
 typedef enum {
-    REDUX_VARIANT_AUTO    = 0, /* the library's default choice (the measured winner per dtype/shape) */
+    REDUX_VARIANT_AUTO    = 0, /* the library's default choice: MFMA, except CLASSIC for the 8-bit floats */
     REDUX_VARIANT_MFMA    = 1, /* MMA encoding: data tile x all-ones, accumulator chained through C   */
     REDUX_VARIANT_CLASSIC = 2  /* per-lane serial accumulation + wavefront tree (Section III)         */
 } redux_variant;
@@ -70,17 +74,21 @@ typedef enum {
  * scheme of Section III when the classic variant is selected).
  *
  *   x      device pointer, read only, n contiguous elements of `dtype`; must be
- *          aligned to the element size only (2 for F16, 1 for I8).  May be NULL iff n == 0.
+ *          aligned to the element size only (1, 2 or 4 bytes).  May be NULL iff n == 0.
  *   n      number of elements; 0 is allowed and yields the empty sum 0.
  *   dtype  a redux_dtype.
- *   out    device pointer owned by the caller: one float (F16, 4-byte aligned) or one
- *          int64_t (I8, 8-byte aligned).  Must not lie inside [x, x + n*elemsize).
+ *   out    device pointer owned by the caller: one int64_t (I8, 8-byte aligned) or one float (every
+ *          floating-point dtype, 4-byte aligned).  Must not lie inside [x, x + n*elemsize).
  *   stream hipStream_t or NULL.
  *
- * F16: elements past the end of the last MMA tile count as zeros; binary32 partial
+ * Floating-point dtypes: elements past the end of the last MMA tile count as zeros; binary32 partial
  * sums are combined across wavefronts and blocks in binary64 and rounded once to
  * binary32.  IEEE semantics for Inf/NaN; subnormal inputs are not flushed.
  * I8: the result is exact for any n that fits in device memory.
+ * F8E4M3 / F8E5M2 with the MFMA family: the matrix unit keeps only 14 bits below the largest of the
+ * eight products a lane contributes to one MFMA, so the error can reach 7 * 2^-14 (4.3e-4) of sum|x|
+ * when values differ by more than 2^14 in magnitude; the classic family (the default for these two
+ * dtypes) adds in binary32 and stays within 1e-4 of sum|x| like the others.
  */
 int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
 
@@ -111,7 +119,7 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
  * is not full is zero padded.  Binary16: partial sums are binary32 at every level.  Int8: int32 inside
  * the first MMA, int64 partial sums, later levels in binary64 (exact below 2^53).
  *
- *   x, n, dtype, out, stream   as for redux_sum.
+ *   x, n, dtype, out, stream   as for redux_sum; dtype REDUX_F16 or REDUX_I8 only (REDUX_ERR_DTYPE otherwise).
  *   levels   host pointer or NULL; receives the number of levels (= kernel launches); 0 for n == 0.
  *
  * The arrays of partial sums (n/256 and n/65536 entries) are library-owned per (device, stream) and grow

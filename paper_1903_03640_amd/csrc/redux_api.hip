@@ -186,12 +186,24 @@ void launch_seg(int unroll, bool nt, unsigned grid, hipStream_t st, const SegArg
 }
 
 // ---- argument checks shared by the entry points ---------------------------------------------------
+// element size and result size of a dtype; 0 for an unknown dtype
+size_t elem_size_of(int dtype)
+{
+    switch (dtype) {
+    case REDUX_F16: case REDUX_BF16: return 2;
+    case REDUX_I8: case REDUX_F8E4M3: case REDUX_F8E5M2: return 1;
+    case REDUX_F32: return 4;
+    default: return 0;
+    }
+}
+size_t out_size_of(int dtype) { return dtype == REDUX_I8 ? 8 : 4; }
+
 int check_common(const void *x, size_t count, int dtype, const void *out, size_t nout, size_t *elem_size)
 {
-    if (dtype != REDUX_F16 && dtype != REDUX_I8) return REDUX_ERR_DTYPE;
-    const size_t es = dtype == REDUX_F16 ? 2 : 1;
-    const size_t os = dtype == REDUX_F16 ? 4 : 8;
-    if (count > ((size_t)1 << 62)) return REDUX_ERR_SIZE;
+    const size_t es = elem_size_of(dtype);
+    if (es == 0) return REDUX_ERR_DTYPE;
+    const size_t os = out_size_of(dtype);
+    if (count > ((size_t)1 << 62) / es) return REDUX_ERR_SIZE;
     if (!out && nout) return REDUX_ERR_NULL;
     if (!x && count) return REDUX_ERR_NULL;
     if ((uintptr_t)x % es) return REDUX_ERR_ALIGN;
@@ -205,11 +217,42 @@ int check_common(const void *x, size_t count, int dtype, const void *out, size_t
     return REDUX_OK;
 }
 
+// the kernel family of (dtype, variant), handed to a generic callable
+template <class Fn>
+void with_flat_family(int dtype, bool mfma, Fn &&fn)
+{
+    switch (dtype) {
+    case REDUX_F16:    if (mfma) fn(FloatMfmaT<kF16, 4>());  else fn(FloatClassic<kF16>());  break;
+    case REDUX_BF16:   if (mfma) fn(FloatMfmaT<kBF16, 4>()); else fn(FloatClassic<kBF16>()); break;
+    case REDUX_F32:    if (mfma) fn(FloatMfmaT<kF32, 4>());  else fn(FloatClassic<kF32>());  break;
+    case REDUX_F8E4M3: if (mfma) fn(FloatMfmaT<kE4M3, 4>()); else fn(FloatClassic<kE4M3>()); break;
+    case REDUX_F8E5M2: if (mfma) fn(FloatMfmaT<kE5M2, 4>()); else fn(FloatClassic<kE5M2>()); break;
+    default:           if (mfma) fn(I8Mfma());               else fn(I8Classic());           break;
+    }
+}
+
+template <class Fn>
+void with_seg_family(int dtype, bool mfma, Fn &&fn)
+{
+    switch (dtype) {
+    case REDUX_F16:    if (mfma) fn(FloatMfmaT<kF16, 1>());  else fn(FloatClassic<kF16>());  break;
+    case REDUX_BF16:   if (mfma) fn(FloatMfmaT<kBF16, 1>()); else fn(FloatClassic<kBF16>()); break;
+    case REDUX_F32:    if (mfma) fn(FloatMfmaT<kF32, 1>());  else fn(FloatClassic<kF32>());  break;
+    case REDUX_F8E4M3: if (mfma) fn(FloatMfmaT<kE4M3, 1>()); else fn(FloatClassic<kE4M3>()); break;
+    case REDUX_F8E5M2: if (mfma) fn(FloatMfmaT<kE5M2, 1>()); else fn(FloatClassic<kE5M2>()); break;
+    default:           if (mfma) fn(I8MfmaSeg());            else fn(I8Classic());           break;
+    }
+}
+
 int effective_variant(int dtype)
 {
-    (void)dtype;
     int v = g_set.variant;
-    return v == REDUX_VARIANT_AUTO ? REDUX_VARIANT_MFMA : v;
+    if (v != REDUX_VARIANT_AUTO) return v;
+    // The 8-bit floating-point MFMAs align the eight products of a lane to the largest of them and keep
+    // only 14 bits below it (measured), so small terms next to a large one are dropped: up to
+    // 7 * 2^-14 of sum|x|, above the 1e-4 this library promises.  Their default is the classic family.
+    if (dtype == REDUX_F8E4M3 || dtype == REDUX_F8E5M2) return REDUX_VARIANT_CLASSIC;
+    return REDUX_VARIANT_MFMA;
 }
 
 long *param_slot(const char *name, long *lo, long *hi)
@@ -247,8 +290,8 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
     std::lock_guard<std::mutex> lock(g_mu);
 
     if (n == 0) {  // the empty sum
-        if (dtype == REDUX_F16) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(1), dim3(64), 0, st, (float *)out, (u64)1);
-        else                    hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(1), dim3(64), 0, st, (i64 *)out, (u64)1);
+        if (dtype != REDUX_I8) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(1), dim3(64), 0, st, (float *)out, (u64)1);
+        else                   hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(1), dim3(64), 0, st, (i64 *)out, (u64)1);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? REDUX_OK : hip_fail(e);
     }
@@ -261,7 +304,7 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
     if ((rc = get_workspace(dev, st, &ws)) != REDUX_OK) return rc;
 
     FlatArgs a;
-    a.run = (es == 2) ? make_run<2>(x, n) : make_run<1>(x, n);
+    a.run = es == 4 ? make_run<4>(x, n) : es == 2 ? make_run<2>(x, n) : make_run<1>(x, n);
     a.partials = ws.partials;
     a.ticket = ws.ticket;
     a.out = out;
@@ -289,22 +332,13 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
 
     const bool nt = g_set.nontemporal != 0;
     const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
-    if (dtype == REDUX_F16) {
-        if (mfma) launch_flat<F16Mfma>(unroll, nt, grid, st, a);
-        else      launch_flat<F16Classic>(unroll, nt, grid, st, a);
-    } else {
-        if (mfma) launch_flat<I8Mfma>(unroll, nt, grid, st, a);
-        else      launch_flat<I8Classic>(unroll, nt, grid, st, a);
-    }
+    with_flat_family(dtype, mfma, [&](auto family) { launch_flat<decltype(family)>(unroll, nt, grid, st, a); });
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     if (a.finish == 2) {
-        if (dtype == REDUX_F16) {
-            if (mfma) hipLaunchKernelGGL(finish_kernel<F16Mfma>, dim3(1), dim3(kBlock), 0, st, a.partials, grid, out);
-            else      hipLaunchKernelGGL(finish_kernel<F16Classic>, dim3(1), dim3(kBlock), 0, st, a.partials, grid, out);
-        } else {
-            hipLaunchKernelGGL(finish_kernel<I8Classic>, dim3(1), dim3(kBlock), 0, st, a.partials, grid, out);
-        }
+        if (dtype == REDUX_I8) hipLaunchKernelGGL(finish_kernel<I8Classic>, dim3(1), dim3(kBlock), 0, st, a.partials, grid, out);
+        else if (mfma)         hipLaunchKernelGGL(finish_kernel<F16Mfma>, dim3(1), dim3(kBlock), 0, st, a.partials, grid, out);
+        else                   hipLaunchKernelGGL(finish_kernel<F16Classic>, dim3(1), dim3(kBlock), 0, st, a.partials, grid, out);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
     }
@@ -314,7 +348,7 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
 int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, void *out, void *stream)
 {
     std::call_once(g_env_once, read_env);
-    if (dtype != REDUX_F16 && dtype != REDUX_I8) return REDUX_ERR_DTYPE;
+    if (elem_size_of(dtype) == 0) return REDUX_ERR_DTYPE;
     if (seglen && nseg > ((size_t)1 << 62) / seglen) return REDUX_ERR_SIZE;
     if (nseg > ((size_t)1 << 59)) return REDUX_ERR_SIZE;
     size_t es = 0;
@@ -327,8 +361,8 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
 
     if (seglen == 0) {
         unsigned grid = (unsigned)((nseg + 255) / 256);
-        if (dtype == REDUX_F16) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(grid), dim3(256), 0, st, (float *)out, (u64)nseg);
-        else                    hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(grid), dim3(256), 0, st, (i64 *)out, (u64)nseg);
+        if (dtype != REDUX_I8) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(grid), dim3(256), 0, st, (float *)out, (u64)nseg);
+        else                   hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(grid), dim3(256), 0, st, (i64 *)out, (u64)nseg);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? REDUX_OK : hip_fail(e);
     }
@@ -343,7 +377,7 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     const u64 seg_bytes = (u64)seglen * es;
 
     // ---- short segments: sixteen per wavefront, one per row of the A operand -------------------------
-    if (g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 && (uintptr_t)x % 16 == 0 &&
+    if ((dtype == REDUX_F16 || dtype == REDUX_I8) && g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 && (uintptr_t)x % 16 == 0 &&
         seg_bytes / 16 <= (u64)g_set.rows_max_vec) {
         RowArgs r;
         r.x = (const u32x4 *)x;
@@ -406,23 +440,14 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
     unsigned grid = (unsigned)(blocks_needed < gmax ? blocks_needed : gmax);
 
-    if (dtype == REDUX_F16) {
-        if (mfma) launch_seg<F16MfmaSeg>(unroll, nt, grid, st, a);
-        else      launch_seg<F16Classic>(unroll, nt, grid, st, a);
-    } else {
-        if (mfma) launch_seg<I8MfmaSeg>(unroll, nt, grid, st, a);
-        else      launch_seg<I8Classic>(unroll, nt, grid, st, a);
-    }
+    with_seg_family(dtype, mfma, [&](auto family) { launch_seg<decltype(family)>(unroll, nt, grid, st, a); });
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     if (a.parts > 1) {
         const unsigned p = (unsigned)a.parts, g = (unsigned)nseg;
-        if (dtype == REDUX_F16) {
-            if (mfma) hipLaunchKernelGGL(finish_segments_kernel<F16Mfma>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
-            else      hipLaunchKernelGGL(finish_segments_kernel<F16Classic>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
-        } else {
-            hipLaunchKernelGGL(finish_segments_kernel<I8Classic>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
-        }
+        if (dtype == REDUX_I8) hipLaunchKernelGGL(finish_segments_kernel<I8Classic>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
+        else if (mfma)         hipLaunchKernelGGL(finish_segments_kernel<F16Mfma>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
+        else                   hipLaunchKernelGGL(finish_segments_kernel<F16Classic>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
     }
@@ -432,6 +457,7 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
 int redux_sum_multipass(const void *x, size_t n, int dtype, void *out, int *levels, void *stream)
 {
     std::call_once(g_env_once, read_env);
+    if (dtype != REDUX_F16 && dtype != REDUX_I8) return REDUX_ERR_DTYPE;     // this form exists for the paper's binary16 (and int8)
     size_t es = 0;
     int rc = check_common(x, n, dtype, out, 1, &es);
     if (rc != REDUX_OK) return rc;

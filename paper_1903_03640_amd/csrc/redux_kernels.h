@@ -128,11 +128,96 @@ __device__ __forceinline__ double uniform_f64(double v)
 //   edge           build a vector holding a single element in slot 0 (zero padding elsewhere)
 // ---------------------------------------------------------------------------------------------
 
-template <int NACC>
-struct F16MfmaT {
+// Floating-point element kinds.  Every kind accumulates in binary32 and differs only in how a
+// 16-byte vector is handed to the matrix unit (or converted, in the classic family).
+enum Kind { kF16 = 0, kBF16 = 1, kF32 = 2, kE4M3 = 3, kE5M2 = 4 };
+
+template <int KIND> struct KindTraits;
+template <> struct KindTraits<kF16>  { static constexpr int kElemSize = 2; };
+template <> struct KindTraits<kBF16> { static constexpr int kElemSize = 2; };
+template <> struct KindTraits<kF32>  { static constexpr int kElemSize = 4; };
+template <> struct KindTraits<kE4M3> { static constexpr int kElemSize = 1; };
+template <> struct KindTraits<kE5M2> { static constexpr int kElemSize = 1; };
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// one element, zero padded to a vector (slot 0)
+template <int ES>
+__device__ __forceinline__ u32x4 edge_bits(const void *p)
+{
+    if (ES == 4) return u32x4{*(const unsigned *)p, 0u, 0u, 0u};
+    if (ES == 2) return u32x4{(unsigned)*(const unsigned short *)p, 0u, 0u, 0u};
+    return u32x4{(unsigned)*(const unsigned char *)p, 0u, 0u, 0u};
+}
+
+// first MMA of Section IV-A with the accumulator chained through C:  D <- A x 1 + D
+template <int KIND>
+__device__ __forceinline__ f32x4 mma1_chain(u32x4 v, f32x4 d)
+{
+    if (KIND == kF16) {
+        const f16x8 ones = {1, 1, 1, 1, 1, 1, 1, 1};
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, v), ones, d, 0, 0, 0);
+    } else if (KIND == kBF16) {
+        const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};     // bfloat16 1.0 = 0x3F80
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v), __builtin_bit_cast(bf16x8, ones), d, 0, 0, 0);
+    } else if (KIND == kF32) {
+        // A is 16 x 4 binary32 per MFMA: the lane's four values are four K-slices
+        const f32x4 f = __builtin_bit_cast(f32x4, v);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) d = __builtin_amdgcn_mfma_f32_16x16x4f32(f[k], 1.0f, d, 0, 0, 0);
+        return d;
+    } else {
+        // 8-bit floating point: A is 16 x 32 per MFMA (8 bytes per lane), so a 16-byte vector is two MFMAs
+        const long lo = (long)(((u64)v[1] << 32) | v[0]), hi = (long)(((u64)v[3] << 32) | v[2]);
+        if (KIND == kE4M3) {
+            const long ones = 0x3838383838383838L;                                    // E4M3 1.0 = 0x38
+            d = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(lo, ones, d, 0, 0, 0);
+            return __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(hi, ones, d, 0, 0, 0);
+        } else {
+            const long ones = 0x3C3C3C3C3C3C3C3CL;                                    // E5M2 1.0 = 0x3C
+            d = __builtin_amdgcn_mfma_f32_16x16x32_bf8_bf8(lo, ones, d, 0, 0, 0);
+            return __builtin_amdgcn_mfma_f32_16x16x32_bf8_bf8(hi, ones, d, 0, 0, 0);
+        }
+    }
+}
+
+// sum of the elements of one 16-byte vector, binary32 (classic family)
+template <int KIND>
+__device__ __forceinline__ void add_vector(float *s /* 4 running sums */, u32x4 v)
+{
+    if (KIND == kF16) {
+        f16x8 h = __builtin_bit_cast(f16x8, v);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s[k & 3] += (float)h[k];
+    } else if (KIND == kBF16) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {                         // a bfloat16 is the upper half of a binary32
+            const unsigned w = v[k];
+            s[k] += __builtin_bit_cast(float, w << 16);
+            s[k] += __builtin_bit_cast(float, w & 0xFFFF0000u);
+        }
+    } else if (KIND == kF32) {
+        const f32x4 f = __builtin_bit_cast(f32x4, v);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s[k] += f[k];
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            f32x2 a, b;
+            if (KIND == kE4M3) { a = __builtin_amdgcn_cvt_pk_f32_fp8((int)v[k], false); b = __builtin_amdgcn_cvt_pk_f32_fp8((int)v[k], true); }
+            else               { a = __builtin_amdgcn_cvt_pk_f32_bf8((int)v[k], false); b = __builtin_amdgcn_cvt_pk_f32_bf8((int)v[k], true); }
+            s[k] += a[0] + a[1];
+            s[k] += b[0] + b[1];
+        }
+    }
+}
+
+template <int KIND, int NACC>
+struct FloatMfmaT {
     typedef double Total;
     typedef float Out;
-    static constexpr int kElemSize = 2;
+    static constexpr int kElemSize = KindTraits<KIND>::kElemSize;
     static constexpr int kNumAcc = NACC;   // independent accumulator chains per wavefront
     static constexpr bool kMfmaFinish = true;
     struct Acc { f32x4 d[kNumAcc]; };
@@ -142,12 +227,9 @@ struct F16MfmaT {
 #pragma unroll
         for (int i = 0; i < kNumAcc; ++i) c.d[i] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    // first MMA of Section IV-A with the accumulator chained through C:  D <- A x 1 + D
     static __device__ __forceinline__ void consume(Acc &c, int U, u32x4 v)
     {
-        const f16x8 ones = {1, 1, 1, 1, 1, 1, 1, 1};
-        c.d[U % kNumAcc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, v), ones,
-                                                                  c.d[U % kNumAcc], 0, 0, 0);
+        c.d[U % kNumAcc] = mma1_chain<KIND>(v, c.d[U % kNumAcc]);
     }
     // second MMA: D' <- 1 x D, chained over the four register slices of every accumulator
     static __device__ __forceinline__ Total fold(Acc &c)
@@ -161,42 +243,34 @@ struct F16MfmaT {
         clear(c);
         return (double)uniform_f32(dp[0]);
     }
-    static __device__ __forceinline__ u32x4 edge(const void *p)
-    {
-        return u32x4{(unsigned)*(const unsigned short *)p, 0u, 0u, 0u};
-    }
+    static __device__ __forceinline__ u32x4 edge(const void *p) { return edge_bits<kElemSize>(p); }
     static __device__ __forceinline__ Out to_out(Total t) { return (float)t; }
 };
 
+template <int NACC> using F16MfmaT = FloatMfmaT<kF16, NACC>;
 typedef F16MfmaT<4> F16Mfma;      // flat sum: four chains, folded once per wavefront
 typedef F16MfmaT<1> F16MfmaSeg;   // segmented sum: one chain, so the per-segment fold is four MFMAs
 
-struct F16Classic {
+template <int KIND>
+struct FloatClassic {
     typedef double Total;
     typedef float Out;
-    static constexpr int kElemSize = 2;
+    static constexpr int kElemSize = KindTraits<KIND>::kElemSize;
     static constexpr bool kMfmaFinish = false;
     struct Acc { float s[4]; };
 
     static __device__ __forceinline__ void clear(Acc &c) { c.s[0] = c.s[1] = c.s[2] = c.s[3] = 0.f; }
-    static __device__ __forceinline__ void consume(Acc &c, int U, u32x4 v)
-    {
-        f16x8 h = __builtin_bit_cast(f16x8, v);
-#pragma unroll
-        for (int k = 0; k < 8; ++k) c.s[k & 3] += (float)h[k];
-    }
+    static __device__ __forceinline__ void consume(Acc &c, int U, u32x4 v) { add_vector<KIND>(c.s, v); }
     static __device__ __forceinline__ Total fold(Acc &c)
     {
         float s = (c.s[0] + c.s[1]) + (c.s[2] + c.s[3]);
         clear(c);
         return (double)wave_sum_f32(s);
     }
-    static __device__ __forceinline__ u32x4 edge(const void *p)
-    {
-        return u32x4{(unsigned)*(const unsigned short *)p, 0u, 0u, 0u};
-    }
+    static __device__ __forceinline__ u32x4 edge(const void *p) { return edge_bits<kElemSize>(p); }
     static __device__ __forceinline__ Out to_out(Total t) { return (float)t; }
 };
+typedef FloatClassic<kF16> F16Classic;
 
 template <int NACC>
 struct I8MfmaT {

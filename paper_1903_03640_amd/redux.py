@@ -13,7 +13,7 @@ from typing import Optional
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libredux.so")
 
-F16, I8 = 0, 1
+F16, I8, BF16, F32, F8E4M3, F8E5M2 = 0, 1, 2, 3, 4, 5
 VARIANTS = {"auto": 0, "mfma": 1, "classic": 2}
 
 # every symbol include/redux.h declares
@@ -135,11 +135,11 @@ def calibration_copy_raw(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 
 
 def _dtype_of(x) -> int:
     import torch
-    if x.dtype == torch.float16:
-        return F16
-    if x.dtype == torch.int8:
-        return I8
-    raise TypeError("redux supports float16 and int8 tensors, got %s" % x.dtype)
+    table = {torch.float16: F16, torch.int8: I8, torch.bfloat16: BF16, torch.float32: F32,
+             torch.float8_e4m3fn: F8E4M3, torch.float8_e5m2: F8E5M2}
+    if x.dtype not in table:
+        raise TypeError("redux supports float16, int8, bfloat16, float32, float8_e4m3fn and float8_e5m2 tensors, got %s" % x.dtype)
+    return table[x.dtype]
 
 
 def _prep(x):
@@ -157,7 +157,7 @@ def sum(x, out=None):
     stream = _prep(x)
     dt = _dtype_of(x)
     if out is None:
-        out = torch.empty(1, dtype=torch.float32 if dt == F16 else torch.int64, device=x.device)
+        out = torch.empty(1, dtype=torch.int64 if dt == I8 else torch.float32, device=x.device)
     with torch.cuda.device(x.device):
         _check(sum_raw(x.data_ptr() if x.numel() else 0, x.numel(), dt, out.data_ptr(), stream), "redux_sum")
     return out
@@ -188,7 +188,7 @@ def sum_segmented(x, nseg: Optional[int] = None, seglen: Optional[int] = None, o
     if nseg * seglen != x.numel():
         raise ValueError("nseg*seglen != numel")
     if out is None:
-        out = torch.empty(nseg, dtype=torch.float32 if dt == F16 else torch.int64, device=x.device)
+        out = torch.empty(nseg, dtype=torch.int64 if dt == I8 else torch.float32, device=x.device)
     with torch.cuda.device(x.device):
         _check(sum_segmented_raw(x.data_ptr() if x.numel() else 0, nseg, seglen, dt,
                                  out.data_ptr() if nseg else 0, stream), "redux_sum_segmented")

@@ -142,6 +142,38 @@ def uniform_i8_numpy(seed: int, n: int, start: int = 0) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# inputs for the other element types (numpy recipes; storage returned as raw bit patterns)
+# --------------------------------------------------------------------------
+
+def normal_f32(seed: int, n: int, start: int = 0) -> np.ndarray:
+    """n binary32 values, N(0,1) by the same Box-Muller recipe, rounded once to binary32 (float32 array)."""
+    idx = np.arange(start, start + n, dtype=np.uint64)
+    u1 = _u24_numpy(seed, np.uint64(2) * idx)
+    u2 = _u24_numpy(seed, np.uint64(2) * idx + np.uint64(1))
+    return (np.sqrt(-2.0 * np.log(1.0 - u1)) * np.cos(2.0 * np.pi * u2)).astype(np.float32)
+
+
+def normal_bf16(seed: int, n: int, start: int = 0) -> np.ndarray:
+    """n bfloat16 patterns (uint16): N(0,1) in binary32, truncated to the upper 16 bits."""
+    return (normal_f32(seed, n, start).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def finite_f8(seed: int, n: int, fmt: str, start: int = 0) -> np.ndarray:
+    """n patterns (uint8) of an OCP 8-bit format, uniform over its finite values' patterns.
+
+    fmt 'e4m3': the two NaN patterns (0x7F, 0xFF) are replaced by zero of the same sign;
+    fmt 'e5m2': patterns with exponent 31 (Inf/NaN) get the top exponent bit cleared."""
+    b = uniform_i8(seed, n, start).view(np.uint8).copy()
+    if fmt == "e4m3":
+        b[(b & 0x7F) == 0x7F] &= 0x80
+    elif fmt == "e5m2":
+        b[(b & 0x7C) == 0x7C] &= 0xBF
+    else:
+        raise ValueError(fmt)
+    return b
+
+
+# --------------------------------------------------------------------------
 # the benchmark configurations
 # --------------------------------------------------------------------------
 

@@ -38,9 +38,11 @@ def test_argument_errors_come_before_any_hip_call():
     assert redux.sum_raw(p16, 1 << 63, redux.I8, p16 + 32, 0) == -3
     assert redux.sum_segmented_raw(p16, 1 << 40, 1 << 40, redux.F16, p16 + 32, 0) == -3
     assert redux.sum_segmented_raw(0, 4, 4, redux.F16, p16, 0) == -1
-    assert redux.sum_segmented_raw(p16, 4, 4, 2, p16 + 32, 0) == -2
+    assert redux.sum_segmented_raw(p16, 4, 4, 9, p16 + 32, 0) == -2
     assert redux.sum_segmented_raw(0, 0, 0, redux.F16, 0, 0) == 0  # no segments: a no-op, nothing launched
     assert redux.sum_segmented_raw(0, 0, 5, redux.I8, 0, 0) == 0
+    assert redux.sum_multipass_raw(p16, 8, redux.BF16, p16 + 32, 0)[0] == -2   # this form: binary16 / int8 only
+    assert redux.sum_raw(p16 + 2, 4, redux.F32, p16 + 32, 0) == -4             # binary32 input not 4-byte aligned
     assert redux.mma_group_probe_raw(p16, 513, redux.F16, p16, p16, 0) == -3
     assert redux.mma_group_probe_raw(p16, 1025, redux.I8, p16, p16, 0) == -3
     assert redux.mma_group_probe_raw(0, 4, redux.F16, p16, p16, 0) == -1
