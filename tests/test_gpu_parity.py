@@ -477,3 +477,44 @@ def test_multipass_misaligned_unrolls_and_closed_forms(dev, m):
     out, _ = redux.sum_multipass(sub)
     torch.cuda.synchronize()
     assert abs(out.item() - 70000 * 2.0 ** -24) <= TOL * 70000 * 2.0 ** -24
+
+
+# ---- stream capture: the library's launches replay correctly from a HIP graph ----------------------------------
+
+def test_graph_replay_matches_eager(dev):
+    """Warm up on the capture stream (the workspace is created by the first call on a stream, which must
+    not happen during capture), capture flat / segmented / multipass calls, replay several times with eager
+    work in between, and compare every replay with the eager results."""
+    n, nseg, seglen = (1 << 22) + 4321, 300, 4100
+    small_n = 70001                                           # small grid: finishes inside the main kernel
+    x = to_dev(workloads.normal_f16(61, n), dev)
+    xs = to_dev(workloads.uniform_f16(62, nseg * seglen, symmetric=True), dev)
+    xi = to_dev(workloads.uniform_i8(63, small_n), dev)
+    outs = [torch.zeros(1, dtype=torch.float32, device=dev), torch.zeros(nseg, dtype=torch.float32, device=dev),
+            torch.zeros(1, dtype=torch.int64, device=dev), torch.zeros(1, dtype=torch.float32, device=dev)]
+
+    def run_all():
+        redux.sum(x, out=outs[0])
+        redux.sum_segmented(xs, nseg, seglen, out=outs[1])
+        redux.sum(xi, out=outs[2])
+        redux.sum_multipass(x, out=outs[3])
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        run_all()                                             # creates this stream's workspaces
+    stream.synchronize()
+    eager = [o.clone() for o in outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        run_all()
+    for rep in range(4):
+        for o in outs:
+            o.fill_(-1)
+        redux.sum(x)                                          # eager work on another stream between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(outs, eager):
+            assert torch.equal(got, want), rep
+    check_f16(eager[0].item(), x.cpu().numpy())
+    assert eager[2].item() == oracle.sum_i8(xi.cpu().numpy())[0]
