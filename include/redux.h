@@ -178,7 +178,7 @@ int redux_get_variant(void);
  *   "finish"            -1..2   how block partials become the result: 0/1 = the block that arrives last
  *                               sums them in the same kernel (0: acquire+release on every block's ticket,
  *                               1: release only, acquire in the last block), 2 = a second one-block kernel
- *                               on the same stream, -1 = chosen from the grid size (default -1)
+ *                               on the same stream, -1 = chosen from the input size (default -1)
  *   "max_chain"         1..65536 loop iterations between folds of the MMA accumulators into the wide
  *                               per-wavefront total (bounds binary32 chain length; keeps int32
  *                               accumulators below 2^31 for any input)

@@ -326,9 +326,10 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
     }
     u64 nslab = a.run.nvec / ((u64)kBlock * unroll);
     unsigned grid = (unsigned)(nslab < 1 ? 1 : (nslab < gmax ? nslab : gmax));
-    // A second tiny kernel sums the partials faster than a device-wide release per block
-    // once there are many blocks; a handful of blocks finish in the same kernel.
-    if (a.finish < 0) a.finish = grid >= 128 ? 2 : 1;
+    // Measured: finishing inside the kernel (a device-wide release per block) costs about 7 us more than a
+    // second one-block kernel (4.5 us) once the input is 128 MiB or more, and 1-3 us less up to 32 MiB,
+    // where the second launch is what shows.
+    if (a.finish < 0) a.finish = a.run.nvec > ((u64)32 << 20) / 16 ? 2 : 1;
 
     const bool nt = g_set.nontemporal != 0;
     const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;

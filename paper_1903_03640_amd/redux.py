@@ -151,6 +151,23 @@ def _prep(x):
     return torch.cuda.current_stream(x.device).cuda_stream
 
 
+class _Device:
+    """Make x's device current for the call; a no-op (no context-manager cost) when it already is."""
+    __slots__ = ("ctx",)
+
+    def __init__(self, x):
+        import torch
+        self.ctx = None if torch.cuda.current_device() == x.device.index else torch.cuda.device(x.device)
+
+    def __enter__(self):
+        if self.ctx is not None:
+            self.ctx.__enter__()
+
+    def __exit__(self, *exc):
+        if self.ctx is not None:
+            self.ctx.__exit__(*exc)
+
+
 def sum(x, out=None):
     """Sum of all elements of a float16 (-> float32) or int8 (-> int64) device tensor; returns a 1-element tensor."""
     import torch
@@ -158,7 +175,7 @@ def sum(x, out=None):
     dt = _dtype_of(x)
     if out is None:
         out = torch.empty(1, dtype=torch.int64 if dt == I8 else torch.float32, device=x.device)
-    with torch.cuda.device(x.device):
+    with _Device(x):
         _check(sum_raw(x.data_ptr() if x.numel() else 0, x.numel(), dt, out.data_ptr(), stream), "redux_sum")
     return out
 
@@ -170,7 +187,7 @@ def sum_multipass(x, out=None):
     dt = _dtype_of(x)
     if out is None:
         out = torch.empty(1, dtype=torch.float32 if dt == F16 else torch.int64, device=x.device)
-    with torch.cuda.device(x.device):
+    with _Device(x):
         rc, levels = sum_multipass_raw(x.data_ptr() if x.numel() else 0, x.numel(), dt, out.data_ptr(), stream)
     _check(rc, "redux_sum_multipass")
     return out, levels
@@ -189,7 +206,7 @@ def sum_segmented(x, nseg: Optional[int] = None, seglen: Optional[int] = None, o
         raise ValueError("nseg*seglen != numel")
     if out is None:
         out = torch.empty(nseg, dtype=torch.int64 if dt == I8 else torch.float32, device=x.device)
-    with torch.cuda.device(x.device):
+    with _Device(x):
         _check(sum_segmented_raw(x.data_ptr() if x.numel() else 0, nseg, seglen, dt,
                                  out.data_ptr() if nseg else 0, stream), "redux_sum_segmented")
     return out
@@ -202,7 +219,7 @@ def mma_group_probe(x):
     dt = _dtype_of(x)
     D = torch.empty(16, 16, dtype=torch.float32 if dt == F16 else torch.int32, device=x.device)
     Dp = torch.empty(16, 16, dtype=torch.float32 if dt == F16 else torch.float64, device=x.device)
-    with torch.cuda.device(x.device):
+    with _Device(x):
         _check(mma_group_probe_raw(x.data_ptr() if x.numel() else 0, x.numel(), dt, D.data_ptr(), Dp.data_ptr(), stream),
                "redux_mma_group_probe")
     return D, Dp
