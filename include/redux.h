@@ -151,6 +151,40 @@ int redux_mma_group_probe(const void *x, size_t count, int dtype, void *D, void 
  */
 int redux_calibration_copy(void *dst, const void *src, size_t nbytes, void *stream);
 
+/*
+ * Launch plans -- what the library would launch for a given problem, computed on the host with no HIP
+ * call (so it works, and is tested, on a machine without a GPU).  `compute_units` stands for the device's
+ * compute-unit count (256 on an MI355X); `x_address` is the address the input would have (only its low
+ * four bits matter: alignment decides head/tail elements and whether the short-segment kernel applies).
+ * The current redux_set_param settings apply.
+ */
+typedef enum {
+    REDUX_KERNEL_FLAT   = 0, /* redux_sum */
+    REDUX_KERNEL_ROWS   = 1, /* redux_sum_segmented, sixteen short segments per wavefront */
+    REDUX_KERNEL_WAVE   = 2, /* redux_sum_segmented, one wavefront per segment */
+    REDUX_KERNEL_PIECES = 3  /* redux_sum_segmented, long segments cut into pieces + per-segment finish */
+} redux_kernel;
+
+typedef struct {
+    int      kernel;   /* a redux_kernel */
+    int      unroll;   /* 16-byte loads in flight per lane (ROWS: per row group) */
+    unsigned grid;     /* 256-thread blocks of the main kernel */
+    int      finish;   /* FLAT: 1 = in the same kernel, 2 = second kernel; PIECES: 2; else 0 */
+    uint64_t parts;    /* pieces per segment (1 unless PIECES) */
+    uint64_t part_len; /* elements per piece */
+    unsigned head;     /* FLAT: elements before the first 16-byte aligned vector */
+    unsigned tail;     /* FLAT: elements after the last whole vector */
+    uint64_t vectors;  /* FLAT: whole 16-byte vectors; ROWS: vectors per segment */
+} redux_plan;
+
+int redux_plan_sum(size_t n, int dtype, uintptr_t x_address, int compute_units, redux_plan *plan);
+int redux_plan_sum_segmented(size_t nseg, size_t seglen, int dtype, uintptr_t x_address, int compute_units,
+                             redux_plan *plan); /* nseg, seglen >= 1 */
+/* The slabs (block-sized runs of unroll x 4 KiB) that block `block` of `grid` reads under `layout`:
+ * start, start + stride, ... (count of them).  Over all blocks they cover 0 .. nslab-1 exactly once. */
+int redux_plan_block_slabs(int layout, uint64_t nslab, uint64_t grid, uint64_t block,
+                           uint64_t *start, uint64_t *stride, uint64_t *count);
+
 /* Select the kernel family for subsequent calls (process-wide). Also read once from the
  * environment variable REDUX_VARIANT = auto | mfma | classic. */
 int redux_set_variant(int variant);

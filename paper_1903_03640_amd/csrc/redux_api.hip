@@ -274,6 +274,91 @@ long *param_slot(const char *name, long *lo, long *hi)
     return nullptr;
 }
 
+// ---- launch plans: pure host arithmetic, shared by the entry points and by redux_plan_* ---------------------
+struct FlatPlan { int unroll; unsigned grid; int finish; };
+
+// Launch shape of the flat sum.  Measured on MI355X: read bandwidth peaks with about 8 MiB in flight
+// (one 256-thread block per compute unit, eight 16-byte loads per lane) and drops by several percent
+// when more blocks are resident.  Small inputs keep the deep unroll as long as that leaves 64 blocks.
+FlatPlan plan_flat(u64 nvec, int cus)
+{
+    FlatPlan p;
+    u64 gmax = (u64)cus * (u64)g_set.blocks_per_cu;
+    if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+    if (gmax < 1) gmax = 1;
+    p.unroll = (int)g_set.unroll;
+    if (p.unroll == 0) {
+        const u64 want = gmax < 64 ? gmax : 64;
+        p.unroll = 8;
+        while (p.unroll > 1 && nvec / ((u64)kBlock * p.unroll) < want) p.unroll >>= 1;
+    }
+    const u64 nslab = nvec / ((u64)kBlock * p.unroll);
+    p.grid = (unsigned)(nslab < 1 ? 1 : (nslab < gmax ? nslab : gmax));
+    // Measured: finishing inside the kernel (a device-wide release per block) costs about 7 us more than a
+    // second one-block kernel (4.5 us) once the input is 128 MiB or more, and 1-3 us less up to 32 MiB,
+    // where the second launch is what shows.
+    p.finish = (int)g_set.finish;
+    if (p.finish < 0) p.finish = nvec > ((u64)32 << 20) / 16 ? 2 : 1;
+    return p;
+}
+
+struct SegPlan {
+    int kernel;          // REDUX_KERNEL_ROWS, _WAVE or _PIECES
+    int unroll;          // rows: loads per row group per iteration; otherwise 16-byte loads in flight per lane
+    unsigned grid;
+    u64 parts, part_len; // pieces per segment and elements per piece (parts == 1: the whole segment)
+    unsigned nvec;       // rows: 16-byte vectors per segment
+};
+
+SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_addr, int cus)
+{
+    SegPlan p;
+    p.parts = 1;
+    p.part_len = seglen;
+    p.nvec = 0;
+    const u64 seg_bytes = seglen * es;
+    // short segments: sixteen per wavefront, one per row of the A operand
+    if ((dtype == REDUX_F16 || dtype == REDUX_I8) && g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 && x_addr % 16 == 0 &&
+        seg_bytes / 16 <= (u64)g_set.rows_max_vec) {
+        p.kernel = REDUX_KERNEL_ROWS;
+        p.nvec = (unsigned)(seg_bytes / 16);
+        const unsigned steps = (p.nvec + 3) / 4;
+        p.unroll = steps <= 1 ? 1 : steps <= 2 ? 2 : steps <= 4 ? 4 : 8;
+        const u64 groups_per_iter = 8 / p.unroll;
+        const u64 nsuper = ((nseg + 15) / 16 + groups_per_iter - 1) / groups_per_iter;
+        u64 blocks = (nsuper + kWaves - 1) / kWaves;
+        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 2);   // measured best
+        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        if (gmax < 1) gmax = 1;
+        p.grid = (unsigned)(blocks < gmax ? blocks : gmax);
+        return p;
+    }
+    // A few long segments would leave most of the chip idle: cut each into a power-of-two number of
+    // pieces (whole 512-element tiles, at least 8 tiles each) until there are about 8 wavefronts per
+    // compute unit, as far as the workspace allows.
+    const u64 want_waves = (u64)cus * 8;
+    u64 parts = 1;
+    if (g_set.seg_parts > 0) parts = (u64)g_set.seg_parts;
+    else while (nseg * parts < want_waves && nseg * parts * 2 <= (u64)kMaxGrid && seglen / (parts * 2) >= 8 * 512) parts *= 2;
+    p.kernel = REDUX_KERNEL_WAVE;
+    if (parts > 1 && nseg <= (u64)kMaxGrid / parts) {
+        p.kernel = REDUX_KERNEL_PIECES;
+        p.parts = parts;
+        p.part_len = ((seglen + parts - 1) / parts + 511) / 512 * 512;
+    }
+    // loads in flight per lane x resident blocks per compute unit = 8
+    const u64 vec_per_piece = p.part_len * es / 16;
+    p.unroll = (int)g_set.unroll;
+    if (p.unroll == 0) p.unroll = vec_per_piece >= 256 ? 4 : vec_per_piece >= 128 ? 2 : 1;
+    const long bpc = g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 8 / p.unroll;
+    u64 blocks_needed = (nseg * p.parts + kWaves - 1) / kWaves;
+    u64 gmax = (u64)cus * (u64)bpc;
+    if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+    if (gmax < 1) gmax = 1;
+    p.grid = (unsigned)(blocks_needed < gmax ? blocks_needed : gmax);
+    return p;
+}
+
 } // namespace
 
 // =====================================================================================================
@@ -312,24 +397,10 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
     a.layout = (int)g_set.layout;
     a.finish = (int)g_set.finish;
 
-    // Launch shape.  Measured on MI355X: read bandwidth peaks with about 8 MiB in flight
-    // (one 256-thread block per compute unit, eight 16-byte loads per lane) and drops by
-    // several percent when more blocks are resident.  Small inputs keep the deep unroll as long
-    // as that leaves 64 blocks, so that they finish in one kernel (see `finish` below).
-    u64 gmax = (u64)cus * (u64)g_set.blocks_per_cu;
-    if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
-    int unroll = (int)g_set.unroll;
-    if (unroll == 0) {
-        const u64 want = gmax < 64 ? gmax : 64;
-        unroll = 8;
-        while (unroll > 1 && a.run.nvec / ((u64)kBlock * unroll) < want) unroll >>= 1;
-    }
-    u64 nslab = a.run.nvec / ((u64)kBlock * unroll);
-    unsigned grid = (unsigned)(nslab < 1 ? 1 : (nslab < gmax ? nslab : gmax));
-    // Measured: finishing inside the kernel (a device-wide release per block) costs about 7 us more than a
-    // second one-block kernel (4.5 us) once the input is 128 MiB or more, and 1-3 us less up to 32 MiB,
-    // where the second launch is what shows.
-    if (a.finish < 0) a.finish = a.run.nvec > ((u64)32 << 20) / 16 ? 2 : 1;
+    const FlatPlan plan = plan_flat(a.run.nvec, cus);
+    const int unroll = plan.unroll;
+    const unsigned grid = plan.grid;
+    a.finish = plan.finish;
 
     const bool nt = g_set.nontemporal != 0;
     const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
@@ -375,23 +446,17 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
 
     const bool nt = g_set.nontemporal != 0;
     const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
-    const u64 seg_bytes = (u64)seglen * es;
+    const SegPlan plan = plan_segmented(nseg, seglen, dtype, es, (uintptr_t)x, cus);
+    const unsigned grid = plan.grid;
 
     // ---- short segments: sixteen per wavefront, one per row of the A operand -------------------------
-    if ((dtype == REDUX_F16 || dtype == REDUX_I8) && g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 && (uintptr_t)x % 16 == 0 &&
-        seg_bytes / 16 <= (u64)g_set.rows_max_vec) {
+    if (plan.kernel == REDUX_KERNEL_ROWS) {
         RowArgs r;
         r.x = (const u32x4 *)x;
         r.nseg = nseg;
-        r.nvec = (unsigned)(seg_bytes / 16);
+        r.nvec = plan.nvec;
         r.out = out;
-        const unsigned steps = (r.nvec + 3) / 4;
-        const int tc = steps <= 1 ? 1 : steps <= 2 ? 2 : steps <= 4 ? 4 : 8;
-        const u64 nsuper = ((nseg + 15) / 16 + (8 / tc) - 1) / (8 / tc);
-        u64 blocks = (nsuper + kWaves - 1) / kWaves;
-        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 2);   // measured best
-        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
-        const unsigned grid = (unsigned)(blocks < gmax ? blocks : gmax);
+        const int tc = plan.unroll;
 #define REDUX_ROWS(R, TC) do { if (nt) hipLaunchKernelGGL((sum_rows_kernel<R, TC, true>), dim3(grid), dim3(kBlock), 0, st, r); \
                                else    hipLaunchKernelGGL((sum_rows_kernel<R, TC, false>), dim3(grid), dim3(kBlock), 0, st, r); } while (0)
 #define REDUX_ROWS_TC(R) do { if (tc == 1) REDUX_ROWS(R, 1); else if (tc == 2) REDUX_ROWS(R, 2); \
@@ -411,35 +476,15 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     a.seglen = seglen;
     a.out = out;
     a.max_chain = (unsigned)g_set.max_chain;
-    a.parts = 1;
-    a.part_len = seglen;
+    a.parts = plan.parts;
+    a.part_len = plan.part_len;
     a.partials = nullptr;
-
-    // A few long segments would leave most of the chip idle: cut each into a power-of-two number of
-    // pieces (whole 512-element tiles, at least 8 tiles each) until there are about 8 wavefronts per
-    // compute unit, as far as the workspace allows.
-    const u64 want_waves = (u64)cus * 8;
-    u64 parts = 1;
-    if (g_set.seg_parts > 0) parts = (u64)g_set.seg_parts;
-    else while (nseg * parts < want_waves && nseg * parts * 2 <= (u64)kMaxGrid && seglen / (parts * 2) >= 8 * 512) parts *= 2;
-    if (parts > 1 && nseg <= (u64)kMaxGrid / parts) {
+    if (plan.kernel == REDUX_KERNEL_PIECES) {
         Workspace ws;
         if ((rc = get_workspace(dev, st, &ws)) != REDUX_OK) return rc;
-        a.parts = parts;
-        a.part_len = ((seglen + parts - 1) / parts + 511) / 512 * 512;
         a.partials = ws.partials;
     }
-
-    // loads in flight per lane x resident blocks per compute unit = 8
-    const u64 vec_per_piece = (u64)a.part_len * es / 16;
-    int unroll = (int)g_set.unroll;
-    if (unroll == 0) unroll = vec_per_piece >= 256 ? 4 : vec_per_piece >= 128 ? 2 : 1;
-    long bpc = g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 8 / unroll;
-
-    u64 blocks_needed = (nseg * a.parts + kWaves - 1) / kWaves;
-    u64 gmax = (u64)cus * (u64)bpc;
-    if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
-    unsigned grid = (unsigned)(blocks_needed < gmax ? blocks_needed : gmax);
+    const int unroll = plan.unroll;
 
     with_seg_family(dtype, mfma, [&](auto family) { launch_seg<decltype(family)>(unroll, nt, grid, st, a); });
     e = hipGetLastError();
@@ -569,6 +614,63 @@ int redux_calibration_copy(void *dst, const void *src, size_t nbytes, void *stre
                        (u32x4 *)dst, (const u32x4 *)src, (u64)(nbytes / 16));
     e = hipGetLastError();
     return e == hipSuccess ? REDUX_OK : hip_fail(e);
+}
+
+int redux_plan_sum(size_t n, int dtype, uintptr_t x_address, int compute_units, redux_plan *plan)
+{
+    if (!plan) return REDUX_ERR_NULL;
+    const size_t es = elem_size_of(dtype);
+    if (es == 0) return REDUX_ERR_DTYPE;
+    if (n > ((size_t)1 << 62) / es) return REDUX_ERR_SIZE;
+    if (compute_units < 1) return REDUX_ERR_PARAM;
+    std::lock_guard<std::mutex> lock(g_mu);
+    const void *x = (const void *)x_address;
+    const Run run = es == 4 ? make_run<4>(x, n) : es == 2 ? make_run<2>(x, n) : make_run<1>(x, n);
+    const FlatPlan p = plan_flat(run.nvec, compute_units);
+    plan->kernel = REDUX_KERNEL_FLAT;
+    plan->unroll = p.unroll;
+    plan->grid = p.grid;
+    plan->finish = p.finish;
+    plan->parts = 1;
+    plan->part_len = n;
+    plan->head = (unsigned)run.nhead;
+    plan->tail = (unsigned)run.ntail;
+    plan->vectors = run.nvec;
+    return REDUX_OK;
+}
+
+int redux_plan_sum_segmented(size_t nseg, size_t seglen, int dtype, uintptr_t x_address, int compute_units, redux_plan *plan)
+{
+    if (!plan) return REDUX_ERR_NULL;
+    const size_t es = elem_size_of(dtype);
+    if (es == 0) return REDUX_ERR_DTYPE;
+    if (seglen && nseg > ((size_t)1 << 62) / seglen / es) return REDUX_ERR_SIZE;
+    if (nseg > ((size_t)1 << 59)) return REDUX_ERR_SIZE;
+    if (compute_units < 1 || nseg == 0 || seglen == 0) return REDUX_ERR_PARAM;
+    std::lock_guard<std::mutex> lock(g_mu);
+    const SegPlan p = plan_segmented(nseg, seglen, dtype, es, x_address, compute_units);
+    plan->kernel = p.kernel;
+    plan->unroll = p.unroll;
+    plan->grid = p.grid;
+    plan->finish = p.kernel == REDUX_KERNEL_PIECES ? 2 : 0;
+    plan->parts = p.parts;
+    plan->part_len = p.part_len;
+    plan->head = 0;
+    plan->tail = 0;
+    plan->vectors = p.nvec;
+    return REDUX_OK;
+}
+
+int redux_plan_block_slabs(int layout, uint64_t nslab, uint64_t grid, uint64_t block, uint64_t *start, uint64_t *stride, uint64_t *count)
+{
+    if (!start || !stride || !count) return REDUX_ERR_NULL;
+    if (layout < 0 || layout > 2 || grid < 1 || block >= grid) return REDUX_ERR_PARAM;
+    u64 s = 0, st = 0, c = 0;
+    slab_schedule(layout, nslab, grid, block, &s, &st, &c);
+    *start = s;
+    *stride = st;
+    *count = c;
+    return REDUX_OK;
 }
 
 int redux_set_variant(int variant)

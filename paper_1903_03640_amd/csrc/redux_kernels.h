@@ -451,7 +451,7 @@ constexpr int kXcds = 8;  // workgroup b is dispatched to accelerator die b % 8
 //   layout 0  interleaved: at any time the grid reads one contiguous moving window
 //   layout 1  blocked: every block streams its own contiguous share of the array
 //   layout 2  die-blocked: every accelerator die owns a contiguous eighth, interleaved among its blocks
-__device__ __forceinline__ void slab_schedule(int layout, u64 nslab, u64 G, u64 b, u64 *start, u64 *stride, u64 *count)
+__host__ __device__ __forceinline__ void slab_schedule(int layout, u64 nslab, u64 G, u64 b, u64 *start, u64 *stride, u64 *count)
 {
     if (layout == 1) {
         const u64 q = nslab / G, r = nslab % G;

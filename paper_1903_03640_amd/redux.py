@@ -19,11 +19,22 @@ VARIANTS = {"auto": 0, "mfma": 1, "classic": 2}
 # every symbol include/redux.h declares
 SYMBOLS = (
     "redux_sum", "redux_sum_segmented", "redux_sum_multipass", "redux_mma_group_probe", "redux_calibration_copy",
+    "redux_plan_sum", "redux_plan_sum_segmented", "redux_plan_block_slabs",
     "redux_set_variant", "redux_get_variant", "redux_set_param", "redux_get_param",
     "redux_strerror", "redux_last_hip_error", "redux_shutdown", "redux_version",
 )
 
 _lib = None
+
+
+class Plan(ctypes.Structure):
+    """Mirror of redux_plan."""
+    _fields_ = [("kernel", ctypes.c_int), ("unroll", ctypes.c_int), ("grid", ctypes.c_uint), ("finish", ctypes.c_int),
+                ("parts", ctypes.c_uint64), ("part_len", ctypes.c_uint64), ("head", ctypes.c_uint), ("tail", ctypes.c_uint),
+                ("vectors", ctypes.c_uint64)]
+
+
+KERNEL_FLAT, KERNEL_ROWS, KERNEL_WAVE, KERNEL_PIECES = 0, 1, 2, 3
 
 
 class ReduxError(RuntimeError):
@@ -52,6 +63,13 @@ def load():
         lib.redux_mma_group_probe.argtypes = [vp, sz, ci, vp, vp, vp]
         lib.redux_calibration_copy.restype = ci
         lib.redux_calibration_copy.argtypes = [vp, vp, sz, vp]
+        u64p = ctypes.POINTER(ctypes.c_uint64)
+        lib.redux_plan_sum.restype = ci
+        lib.redux_plan_sum.argtypes = [sz, ci, ctypes.c_size_t, ci, ctypes.POINTER(Plan)]
+        lib.redux_plan_sum_segmented.restype = ci
+        lib.redux_plan_sum_segmented.argtypes = [sz, sz, ci, ctypes.c_size_t, ci, ctypes.POINTER(Plan)]
+        lib.redux_plan_block_slabs.restype = ci
+        lib.redux_plan_block_slabs.argtypes = [ci, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, u64p, u64p, u64p]
         lib.redux_set_variant.restype = ci
         lib.redux_set_variant.argtypes = [ci]
         lib.redux_get_variant.restype = ci
@@ -129,6 +147,27 @@ def mma_group_probe_raw(x_ptr: int, count: int, dtype: int, d_ptr: int, dp_ptr: 
 
 def calibration_copy_raw(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> int:
     return load().redux_calibration_copy(dst_ptr, src_ptr, nbytes, stream)
+
+
+def plan_sum(n: int, dtype: int, x_address: int = 0, compute_units: int = 256) -> Plan:
+    p = Plan()
+    _check(load().redux_plan_sum(n, dtype, x_address, compute_units, ctypes.byref(p)), "redux_plan_sum")
+    return p
+
+
+def plan_sum_segmented(nseg: int, seglen: int, dtype: int, x_address: int = 0, compute_units: int = 256) -> Plan:
+    p = Plan()
+    _check(load().redux_plan_sum_segmented(nseg, seglen, dtype, x_address, compute_units, ctypes.byref(p)),
+           "redux_plan_sum_segmented")
+    return p
+
+
+def plan_block_slabs(layout: int, nslab: int, grid: int, block: int):
+    """(start, stride, count) of the slabs one block reads."""
+    a, b, c = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64()
+    _check(load().redux_plan_block_slabs(layout, nslab, grid, block, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)),
+           "redux_plan_block_slabs")
+    return a.value, b.value, c.value
 
 
 # ---- torch conveniences: allocate the output, pass the current stream --------------------------------

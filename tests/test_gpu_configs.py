@@ -90,3 +90,28 @@ def test_multipass_configs(name):
         assert abs(float(out.item()) - want[0]) <= TOL * want[1]
         assert levels == mr.expected_levels(cfg.n, 256)
         print("%s multipass: levels %d err/sum|x| %.3g" % (name, levels, abs(float(out.item()) - want[0]) / want[1]))
+
+
+@pytest.mark.parametrize("variant", ["mfma", "classic"])
+def test_more_than_2_to_32_elements(variant):
+    """64-bit indexing: closed forms on arrays longer than 2^32 elements (int8) and 2^32 bytes (binary16)."""
+    _cache.clear()
+    redux.set_variant(variant)
+    n = (1 << 32) + 12345
+    x = torch.ones(n, dtype=torch.int8, device="cuda:0")
+    x[n - 1] = -100
+    x[1 << 32] = 7
+    got = redux.sum(x)
+    nseg = 3
+    seg = redux.sum_segmented(x[: nseg * ((1 << 30) + 5)], nseg, (1 << 30) + 5)      # three segments of 2^30 + 5
+    torch.cuda.synchronize()
+    assert int(got.item()) == n - 2 + 7 - 100
+    assert seg.cpu().tolist() == [(1 << 30) + 5] * 3
+    del x
+    h = torch.full(((1 << 31) + 7,), 0.5, dtype=torch.float16, device="cuda:0")       # 4 GiB + 14 B
+    h[-1] = 1024.0
+    got = redux.sum(h)
+    torch.cuda.synchronize()
+    want = 0.5 * ((1 << 31) + 6) + 1024.0
+    assert abs(float(got.item()) - want) <= 1e-4 * want
+    del h

@@ -1,0 +1,145 @@
+"""Host logic without a GPU: the launch plans the library computes (grid, unroll, finish, pieces) and
+the slab schedule of the flat kernel.  These are the numbers the kernels index memory with, so their
+invariants are checked here over many shapes before anything runs on a device."""
+import os
+
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from paper_1903_03640_amd import redux
+
+pytestmark = pytest.mark.skipif(not os.path.exists(redux.LIB_PATH), reason="libredux.so not built")
+
+ES = {redux.F16: 2, redux.I8: 1, redux.BF16: 2, redux.F32: 4, redux.F8E4M3: 1, redux.F8E5M2: 1}
+DTYPES = sorted(ES)
+PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "layout")
+
+
+@pytest.fixture(autouse=True)
+def restore_params():
+    keep = {k: redux.get_param(k) for k in PARAMS}
+    yield
+    for k, v in keep.items():
+        redux.set_param(k, v)
+
+
+@settings(max_examples=400, deadline=None)
+@given(n=st.one_of(st.integers(0, 5000), st.integers(0, 1 << 40)), dtype=st.sampled_from(DTYPES),
+       mis=st.integers(0, 15), cus=st.sampled_from([1, 8, 104, 256, 304]),
+       bpc=st.integers(1, 16), max_grid=st.sampled_from([1, 7, 256, 16384]), unroll=st.sampled_from([0, 1, 2, 4, 8]))
+def test_flat_plan_invariants(n, dtype, mis, cus, bpc, max_grid, unroll):
+    es = ES[dtype]
+    addr = 4096 + (mis // es) * es                       # aligned to the element size, any 16-byte phase
+    redux.set_param("blocks_per_cu", bpc)
+    redux.set_param("max_grid", max_grid)
+    redux.set_param("unroll", unroll)
+    p = redux.plan_sum(n, dtype, addr, cus)
+    per_vec = 16 // es
+    # geometry: head + vectors + tail tile the array exactly; head ends on a 16-byte boundary
+    assert p.head + p.vectors * per_vec + p.tail == n
+    assert p.head < per_vec and p.tail < per_vec
+    if p.vectors or p.tail:
+        assert (addr + p.head * es) % 16 == 0
+    assert p.unroll in (1, 2, 4, 8) and (unroll == 0 or p.unroll == unroll)
+    nslab = p.vectors // (256 * p.unroll)
+    assert 1 <= p.grid <= min(cus * bpc, max_grid, 16384)
+    assert p.grid <= max(nslab, 1)
+    assert p.finish in (1, 2)
+    assert p.kernel == redux.KERNEL_FLAT
+
+
+def test_flat_plan_defaults_on_mi355x():
+    c3 = redux.plan_sum((1 << 30) + 12345, redux.F16, 0, 256)
+    assert (c3.unroll, c3.grid, c3.finish) == (8, 256, 2)           # one block per CU, 8 loads per lane, second kernel
+    assert (c3.head, c3.tail, c3.vectors) == (0, 1, 134219271)      # the last 16-byte vector holds one element
+    c1 = redux.plan_sum(1 << 20, redux.F16, 0, 256)
+    assert (c1.unroll, c1.grid, c1.finish) == (8, 64, 1)            # small: few blocks, finishes in the same kernel
+    assert redux.plan_sum(0, redux.I8, 0, 256).grid == 1
+
+
+@settings(max_examples=300, deadline=None)
+@given(layout=st.integers(0, 2), nslab=st.integers(0, 5000), grid=st.integers(1, 600))
+def test_slab_schedule_covers_every_slab_once(layout, nslab, grid):
+    seen = bytearray(nslab)
+    for b in range(grid):
+        start, stride, count = redux.plan_block_slabs(layout, nslab, grid, b)
+        assert count == 0 or stride >= 1
+        for k in range(count):
+            s = start + k * stride
+            assert s < nslab and not seen[s]
+            seen[s] = 1
+    assert all(seen)
+
+
+def test_slab_schedule_is_balanced_and_die_blocked():
+    nslab, grid = 65537, 256
+    for layout in (0, 1, 2):
+        counts = [redux.plan_block_slabs(layout, nslab, grid, b)[2] for b in range(grid)]
+        assert sum(counts) == nslab and max(counts) - min(counts) <= 2
+    # layout 2: the blocks of die d (block % 8 == d) stay inside the d-th eighth of the array
+    for b in range(grid):
+        start, stride, count = redux.plan_block_slabs(2, nslab, grid, b)
+        d = b % 8
+        lo, hi = nslab * d // 8, nslab * (d + 1) // 8
+        assert lo <= start and start + (count - 1) * stride < hi
+
+
+@settings(max_examples=500, deadline=None)
+@given(nseg=st.one_of(st.integers(1, 300), st.integers(1, 1 << 24)), seglen=st.one_of(st.integers(1, 3000), st.integers(1, 1 << 26)),
+       dtype=st.sampled_from(DTYPES), aligned=st.booleans(), cus=st.sampled_from([1, 104, 256]),
+       seg_parts=st.sampled_from([0, 0, 0, 2, 8, 64, 4096]), rows_max=st.sampled_from([64, 64, 0, 5]),
+       seg_bpc=st.integers(0, 16), unroll=st.sampled_from([0, 1, 2, 4, 8]))
+def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll):
+    es = ES[dtype]
+    addr = 4096 if aligned else 4096 + es
+    redux.set_param("seg_parts", seg_parts)
+    redux.set_param("rows_max_vec", rows_max)
+    redux.set_param("seg_blocks_per_cu", seg_bpc)
+    redux.set_param("unroll", unroll)
+    p = redux.plan_sum_segmented(nseg, seglen, dtype, addr, cus)
+    assert 1 <= p.grid <= 16 * cus
+    if p.kernel == redux.KERNEL_ROWS:
+        assert dtype in (redux.F16, redux.I8) and aligned and (seglen * es) % 16 == 0
+        assert p.vectors == seglen * es // 16 and 1 <= p.vectors <= rows_max
+        assert p.unroll in (1, 2, 4, 8) and (p.vectors <= 4 * p.unroll or p.unroll == 8)
+        waves = p.grid * 4
+        super_groups = -(-(-(-nseg // 16)) // (8 // p.unroll))
+        assert p.grid <= max(1, -(-super_groups // 4)) and waves >= 1
+    else:
+        assert p.unroll in (1, 2, 4, 8)
+        if p.kernel == redux.KERNEL_PIECES:
+            assert p.parts > 1 and p.parts & (p.parts - 1) == 0
+            assert nseg * p.parts <= 16384                      # piece totals fit the workspace
+            assert p.part_len % 512 == 0 and p.parts * p.part_len >= seglen
+            assert p.finish == 2
+        else:
+            assert p.kernel == redux.KERNEL_WAVE and p.parts == 1 and p.part_len == seglen
+        assert p.grid <= max(1, -(-(nseg * p.parts) // 4))
+
+
+def test_segmented_plan_defaults_on_mi355x():
+    c5 = redux.plan_sum_segmented(65536, 4096, redux.F16, 0, 256)
+    assert (c5.kernel, c5.unroll, c5.grid, c5.parts) == (redux.KERNEL_WAVE, 4, 512, 1)
+    short = redux.plan_sum_segmented(1 << 22, 64, redux.F16, 0, 256)
+    assert (short.kernel, short.vectors, short.unroll) == (redux.KERNEL_ROWS, 8, 2)
+    assert redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256).kernel == redux.KERNEL_WAVE      # misaligned base
+    assert redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256).kernel == redux.KERNEL_WAVE     # other dtypes
+    long_ = redux.plan_sum_segmented(256, 1 << 20, redux.F16, 0, 256)
+    assert (long_.kernel, long_.parts, long_.part_len) == (redux.KERNEL_PIECES, 8, 131072)
+    assert redux.plan_sum_segmented(1, 100, redux.I8, 0, 256).kernel == redux.KERNEL_WAVE
+
+
+def test_plan_argument_errors():
+    import ctypes
+    lib = redux.load()
+    p = redux.Plan()
+    assert lib.redux_plan_sum(8, 9, 0, 256, ctypes.byref(p)) == -2
+    assert lib.redux_plan_sum(8, redux.F16, 0, 0, ctypes.byref(p)) == -8
+    assert lib.redux_plan_sum(8, redux.F16, 0, 256, None) == -1
+    assert lib.redux_plan_sum(1 << 63, redux.F32, 0, 256, ctypes.byref(p)) == -3
+    assert lib.redux_plan_sum_segmented(0, 8, redux.F16, 0, 256, ctypes.byref(p)) == -8
+    assert lib.redux_plan_sum_segmented(1 << 40, 1 << 40, redux.F16, 0, 256, ctypes.byref(p)) == -3
+    with pytest.raises(redux.ReduxError):
+        redux.plan_block_slabs(3, 10, 4, 0)
+    with pytest.raises(redux.ReduxError):
+        redux.plan_block_slabs(0, 10, 4, 4)
