@@ -101,10 +101,11 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
  *   out     device pointer to nseg results (float for F16, int64_t for I8).
  *   nseg == 0 is a no-op; seglen == 0 writes nseg zeros.
  *
- * Three shapes of kernel, chosen from (nseg, seglen): short 16-byte-aligned segments (up to 1 KiB)
- * go sixteen to a wavefront, one per row of the A operand, and need only the first MMA; otherwise one
- * wavefront takes one segment (first MMA chained over its tiles, second MMA to fold the rows); a few
- * long segments are cut into pieces whose totals (in the workspace) a second kernel adds per segment.
+ * The kernel is chosen from (nseg, seglen): short 16-byte-aligned segments (up to 1 KiB) go sixteen to
+ * a wavefront, one per row of the A operand, and need only the first MMA; otherwise one wavefront takes
+ * one segment (first MMA chained over its tiles, second MMA to fold the rows), with a pipelined form for
+ * aligned segments of exactly 1, 2, 4 or 8 KiB; a few long segments are cut into pieces whose totals (in
+ * the workspace) a second kernel adds per segment.
  */
 int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, void *out, void *stream);
 
@@ -162,7 +163,9 @@ typedef enum {
     REDUX_KERNEL_FLAT   = 0, /* redux_sum */
     REDUX_KERNEL_ROWS   = 1, /* redux_sum_segmented, sixteen short segments per wavefront */
     REDUX_KERNEL_WAVE   = 2, /* redux_sum_segmented, one wavefront per segment */
-    REDUX_KERNEL_PIECES = 3  /* redux_sum_segmented, long segments cut into pieces + per-segment finish */
+    REDUX_KERNEL_PIECES = 3, /* redux_sum_segmented, long segments cut into pieces + per-segment finish */
+    REDUX_KERNEL_TILES  = 4  /* redux_sum_segmented, segments of exactly 1, 2, 4 or 8 KiB: one wavefront per
+                                segment with the next segment's loads issued ahead */
 } redux_kernel;
 
 typedef struct {
@@ -199,6 +202,8 @@ int redux_get_variant(void);
  *   "nontemporal"       0/1     use non-temporal (streaming) loads (default 1)
  *   "rows_max_vec"      0..64   segmented sum: segments of at most this many 16-byte vectors (and 16-byte
  *                               aligned) take the sixteen-segments-per-wavefront kernel; 0 = never (default 64)
+ *   "seg_tiles"         0/1     segmented sum: 16-byte aligned segments of exactly 1, 2, 4 or 8 KiB, at least
+ *                               four per compute unit, take the pipelined one-wavefront-per-segment kernel (default 1)
  *   "seg_parts"         0,1,2,4,...,4096  segmented sum: pieces a long segment is cut into; 0 = from the
  *                               shape (default 0); ignored if nseg * pieces exceeds the workspace (16384)
  *   "lit_m"             4,16,32 redux_sum_multipass, binary16: linear size m of the MMA matrices (default 16)

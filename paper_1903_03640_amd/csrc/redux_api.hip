@@ -27,6 +27,7 @@ struct Settings {
     long layout = 2;
     long rows_max_vec = 64;       // short-segment kernel up to this many 16-byte vectors per segment (0 = off)
     long seg_parts = 0;           // 0 = pieces per long segment chosen from the shape
+    long seg_tiles = 1;           // use the pipelined kernel for segments of 1, 2, 4 or 8 whole tiles
     long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
     long lit_blocks_per_cu = 0;
     long lit_m = 16;              // linear size m of the MMA matrices of the level-by-level form
@@ -265,6 +266,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "max_chain")) { *lo = 1; *hi = 65536; return &g_set.max_chain; }
     if (!std::strcmp(name, "max_grid")) { *lo = 1; *hi = kMaxGrid; return &g_set.max_grid; }
     if (!std::strcmp(name, "rows_max_vec")) { *lo = 0; *hi = 64; return &g_set.rows_max_vec; }
+    if (!std::strcmp(name, "seg_tiles")) { *lo = 0; *hi = 1; return &g_set.seg_tiles; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
     if (!std::strcmp(name, "lit_m")) { *lo = 4; *hi = 32; return &g_set.lit_m; }
     if (!std::strcmp(name, "lit_unroll")) { *lo = 0; *hi = 16; return &g_set.lit_unroll; }
@@ -328,6 +330,19 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         const u64 nsuper = ((nseg + 15) / 16 + groups_per_iter - 1) / groups_per_iter;
         u64 blocks = (nsuper + kWaves - 1) / kWaves;
         u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 2);   // measured best
+        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        if (gmax < 1) gmax = 1;
+        p.grid = (unsigned)(blocks < gmax ? blocks : gmax);
+        return p;
+    }
+    // segments of exactly 1, 2, 4 or 8 whole tiles, enough of them to fill the chip: the pipelined kernel
+    if (g_set.seg_tiles && x_addr % 16 == 0 && seg_bytes % 1024 == 0 && seg_bytes <= 8192 &&
+        ((seg_bytes / 1024) & (seg_bytes / 1024 - 1)) == 0 && nseg >= (u64)cus * kWaves) {
+        p.kernel = REDUX_KERNEL_TILES;
+        p.unroll = (int)(seg_bytes / 1024);
+        u64 blocks = (nseg + kWaves - 1) / kWaves;
+        const long best_bpc = p.unroll == 8 ? 1 : p.unroll == 4 ? 2 : p.unroll == 2 ? 3 : 8;   // measured on MI355X
+        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : best_bpc);
         if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
         if (gmax < 1) gmax = 1;
         p.grid = (unsigned)(blocks < gmax ? blocks : gmax);
@@ -485,6 +500,18 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
         a.partials = ws.partials;
     }
     const int unroll = plan.unroll;
+
+    if (plan.kernel == REDUX_KERNEL_TILES) {
+        with_seg_family(dtype, mfma, [&](auto family) {
+            typedef decltype(family) F;
+#define REDUX_TILES(UU) do { if (nt) hipLaunchKernelGGL((sum_segments_tiles_kernel<F, UU, true>), dim3(grid), dim3(kBlock), 0, st, a); \
+                             else    hipLaunchKernelGGL((sum_segments_tiles_kernel<F, UU, false>), dim3(grid), dim3(kBlock), 0, st, a); } while (0)
+            if (unroll == 8) REDUX_TILES(8); else if (unroll == 4) REDUX_TILES(4); else if (unroll == 2) REDUX_TILES(2); else REDUX_TILES(1);
+#undef REDUX_TILES
+        });
+        e = hipGetLastError();
+        return e == hipSuccess ? REDUX_OK : hip_fail(e);
+    }
 
     with_seg_family(dtype, mfma, [&](auto family) { launch_seg<decltype(family)>(unroll, nt, grid, st, a); });
     e = hipGetLastError();

@@ -154,7 +154,7 @@ def test_special_values(dev, variant):
 def test_segmented(dev, kind, variant):
     redux.set_variant(variant)
     for nseg, seglen, parts in ((1, 1, 0), (5, 8, 0), (64, 33, 0), (257, 512, 0), (100, 4099, 0), (3, (1 << 20) + 3, 0),
-                                (7, 100003, 8), (2000, 64, 0)):
+                                (7, 100003, 8), (2000, 64, 0), (1500, 2048, 0)):
         redux.set_param("seg_parts", parts)
         pats = make(kind, nseg + seglen, nseg * seglen)
         got = redux.sum_segmented(to_dev(pats, kind, dev), nseg, seglen)

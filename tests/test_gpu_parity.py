@@ -45,7 +45,7 @@ def default_params():
     for name, val in (("unroll", 0), ("nontemporal", 1), ("max_chain", 256),
                       ("max_grid", 16384), ("blocks_per_cu", DEFAULTS["blocks_per_cu"]),
                       ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
-                      ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("lit_unroll", 0),
+                      ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("seg_tiles", 1), ("lit_unroll", 0),
                       ("lit_blocks_per_cu", 0), ("lit_m", 16)):
         redux.set_param(name, val)
     redux.set_variant("auto")
@@ -518,3 +518,30 @@ def test_graph_replay_matches_eager(dev):
             assert torch.equal(got, want), rep
     check_f16(eager[0].item(), x.cpu().numpy())
     assert eager[2].item() == oracle.sum_i8(xi.cpu().numpy())[0]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("tiles", [1, 2, 4, 8])
+def test_segmented_whole_tile_segments(dev, variant, tiles):
+    """Segments of exactly 1, 2, 4 or 8 KiB: the pipelined kernel, against the oracle and against the general kernel."""
+    redux.set_variant(variant)
+    for nseg, max_grid in ((1024, 16384), (1025, 16384), (4099, 16384), (3000, 5), (70001 // tiles + 1024, 16384)):
+        redux.set_param("max_grid", max_grid)
+        seglen = 512 * tiles
+        x = workloads.normal_f16(tiles + nseg, nseg * seglen)
+        xd = to_dev(x, dev)
+        want, want_abs = oracle.sum_segmented_f16(x, nseg, seglen)
+        want_kernel = redux.KERNEL_ROWS if tiles == 1 else redux.KERNEL_TILES     # 1 KiB: the short-segment kernel comes first
+        assert redux.plan_sum_segmented(nseg, seglen, redux.F16, xd.data_ptr(), 256).kernel == want_kernel
+        got = redux.sum_segmented(xd, nseg, seglen)
+        redux.set_param("seg_tiles", 0)
+        ref = redux.sum_segmented(xd, nseg, seglen)
+        redux.set_param("seg_tiles", 1)
+        torch.cuda.synchronize()
+        assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
+        assert np.all(np.abs(ref.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
+        seglen8 = 1024 * tiles
+        xi = workloads.uniform_i8(tiles + nseg, nseg * seglen8)
+        goti = redux.sum_segmented(to_dev(xi, dev), nseg, seglen8)
+        torch.cuda.synchronize()
+        assert np.array_equal(goti.cpu().numpy(), oracle.sum_segmented_i8(xi, nseg, seglen8)[0])

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(redux.LIB_PATH), reason="libr
 
 ES = {redux.F16: 2, redux.I8: 1, redux.BF16: 2, redux.F32: 4, redux.F8E4M3: 1, redux.F8E5M2: 1}
 DTYPES = sorted(ES)
-PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "layout")
+PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "layout")
 
 
 @pytest.fixture(autouse=True)
@@ -105,6 +105,9 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
         waves = p.grid * 4
         super_groups = -(-(-(-nseg // 16)) // (8 // p.unroll))
         assert p.grid <= max(1, -(-super_groups // 4)) and waves >= 1
+    elif p.kernel == redux.KERNEL_TILES:
+        assert aligned and seglen * es == 1024 * p.unroll and p.unroll in (1, 2, 4, 8) and nseg >= 4 * cus
+        assert p.parts == 1 and p.grid <= -(-nseg // 4)
     else:
         assert p.unroll in (1, 2, 4, 8)
         if p.kernel == redux.KERNEL_PIECES:
@@ -119,7 +122,15 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
 
 def test_segmented_plan_defaults_on_mi355x():
     c5 = redux.plan_sum_segmented(65536, 4096, redux.F16, 0, 256)
+    assert (c5.kernel, c5.unroll, c5.grid, c5.parts) == (redux.KERNEL_TILES, 8, 256, 1)      # 8 KiB segments: pipelined
+    assert redux.plan_sum_segmented(65536, 1024, redux.F16, 0, 256).grid == 768                 # 2 KiB: three blocks per CU
+    redux.set_param("seg_tiles", 0)
+    c5 = redux.plan_sum_segmented(65536, 4096, redux.F16, 0, 256)
     assert (c5.kernel, c5.unroll, c5.grid, c5.parts) == (redux.KERNEL_WAVE, 4, 512, 1)
+    redux.set_param("seg_tiles", 1)
+    assert redux.plan_sum_segmented(1023, 4096, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE    # too few segments
+    assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE
+    assert redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE  # 3 tiles: not a power of two
     short = redux.plan_sum_segmented(1 << 22, 64, redux.F16, 0, 256)
     assert (short.kernel, short.vectors, short.unroll) == (redux.KERNEL_ROWS, 8, 2)
     assert redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256).kernel == redux.KERNEL_WAVE      # misaligned base
