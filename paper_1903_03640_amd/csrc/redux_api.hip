@@ -31,7 +31,7 @@ struct Settings {
     long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
     long lit_blocks_per_cu = 0;
     long lit_m = 16;              // linear size m of the MMA matrices of the level-by-level form
-    long finish = -1;             // -1 = from the grid size
+    long finish = -1;             // -1 = from the input size
 };
 Settings g_set;
 std::once_flag g_env_once;

@@ -545,3 +545,42 @@ def test_segmented_whole_tile_segments(dev, variant, tiles):
         goti = redux.sum_segmented(to_dev(xi, dev), nseg, seglen8)
         torch.cuda.synchronize()
         assert np.array_equal(goti.cpu().numpy(), oracle.sum_segmented_i8(xi, nseg, seglen8)[0])
+
+
+def test_shutdown_and_reuse_and_host_threads(dev):
+    """redux_shutdown frees the workspaces and the library keeps working; host threads on their own streams
+    can call concurrently."""
+    import threading
+    x = to_dev(workloads.uniform_f16(71, (1 << 22) + 3), dev)
+    want, want_abs = oracle.sum_f16(x.cpu().numpy())
+    a = redux.sum(x).item()
+    torch.cuda.synchronize()
+    redux.shutdown()
+    b = redux.sum(x).item()
+    out_mp, _ = redux.sum_multipass(x)
+    torch.cuda.synchronize()
+    assert a == b and abs(a - want) <= TOL * want_abs and abs(out_mp.item() - want) <= TOL * want_abs
+
+    results, errors = {}, []
+
+    def worker(k):
+        try:
+            torch.cuda.set_device(0)
+            s = torch.cuda.Stream()
+            outs = torch.empty(40, dtype=torch.float32, device=dev)
+            with torch.cuda.stream(s):
+                for i in range(40):
+                    redux.sum(x, out=outs[i:i + 1])
+            s.synchronize()
+            results[k] = outs.cpu().numpy()
+        except Exception as e:                               # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for k in range(4):
+        assert np.all(results[k] == np.float32(a))
