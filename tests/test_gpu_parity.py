@@ -584,3 +584,54 @@ def test_shutdown_and_reuse_and_host_threads(dev):
     assert not errors, errors
     for k in range(4):
         assert np.all(results[k] == np.float32(a))
+
+
+def test_randomised_shapes_and_settings(dev):
+    """300 random (entry point, dtype, size, base offset, family, launch parameters) cases against the oracle.
+    Every case stays inside what the host checks allow; the seed is fixed so a failure names its case."""
+    rng = np.random.default_rng(20240)
+    for case in range(300):
+        kind = ("flat", "seg", "multipass")[int(rng.integers(0, 3))]
+        is_f16 = bool(rng.integers(0, 2))
+        variant = ("mfma", "classic", "auto")[int(rng.integers(0, 3))]
+        redux.set_variant(variant)
+        redux.set_param("unroll", int(rng.choice([0, 1, 2, 4, 8])))
+        redux.set_param("max_grid", int(rng.choice([1, 3, 64, 16384])))
+        redux.set_param("max_chain", int(rng.choice([1, 7, 256])))
+        redux.set_param("layout", int(rng.integers(0, 3)))
+        redux.set_param("finish", int(rng.integers(-1, 3)))
+        redux.set_param("nontemporal", int(rng.integers(0, 2)))
+        off = int(rng.integers(0, 8 if is_f16 else 16))
+        if kind == "seg":
+            nseg = int(rng.choice([1, 2, 17, 300, 5000]))
+            seglen = int(rng.choice([1, 7, 8, 64, 100, 512, 1024, 2048, 4099, 30000]))
+            if nseg * seglen > (1 << 23):
+                nseg = max(1, (1 << 23) // seglen)
+            redux.set_param("seg_parts", int(rng.choice([0, 0, 2, 16])))
+            redux.set_param("seg_tiles", int(rng.integers(0, 2)))
+            n = nseg * seglen
+        else:
+            n = int(rng.choice([0, 1, 100, 4097, 70001, (1 << 20) + 5, (1 << 22) + 77]))
+            redux.set_param("lit_m", int(rng.choice([4, 16, 32])))
+        tag = (case, kind, is_f16, variant, n, off)
+        if is_f16:
+            x = workloads.normal_f16(case, n)
+        else:
+            x = workloads.uniform_i8(case, n)
+        xd = to_dev(x, dev, off) if n else torch.empty(0, dtype=torch.float16 if is_f16 else torch.int8, device=dev)
+        if kind == "seg":
+            got = redux.sum_segmented(xd, nseg, seglen)
+            torch.cuda.synchronize()
+            if is_f16:
+                want, want_abs = oracle.sum_segmented_f16(x, nseg, seglen)
+                assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs), tag
+            else:
+                assert np.array_equal(got.cpu().numpy(), oracle.sum_segmented_i8(x, nseg, seglen)[0]), tag
+        else:
+            got = redux.sum(xd) if kind == "flat" else redux.sum_multipass(xd)[0]
+            torch.cuda.synchronize()
+            if is_f16:
+                want, want_abs = oracle.sum_f16(x)
+                assert abs(got.item() - want) <= TOL * want_abs, tag
+            else:
+                assert got.item() == oracle.sum_i8(x)[0], tag
