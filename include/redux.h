@@ -104,8 +104,8 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
  * The kernel is chosen from (nseg, seglen): short 16-byte-aligned segments (up to 1 KiB) go sixteen to
  * a wavefront, one per row of the A operand, and need only the first MMA; otherwise one wavefront takes
  * one segment (first MMA chained over its tiles, second MMA to fold the rows), with a pipelined form for
- * aligned segments of exactly 1, 2, 4 or 8 KiB; a few long segments are cut into pieces whose totals (in
- * the workspace) a second kernel adds per segment.
+ * aligned segments of exactly 2, 4 or 8 KiB; segments of 32 KiB and more take a whole block each; a few
+ * long segments are cut into pieces whose totals (in the workspace) a second kernel adds per segment.
  */
 int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, void *out, void *stream);
 
@@ -164,16 +164,18 @@ typedef enum {
     REDUX_KERNEL_ROWS   = 1, /* redux_sum_segmented, sixteen short segments per wavefront */
     REDUX_KERNEL_WAVE   = 2, /* redux_sum_segmented, one wavefront per segment */
     REDUX_KERNEL_PIECES = 3, /* redux_sum_segmented, long segments cut into pieces + per-segment finish */
-    REDUX_KERNEL_TILES  = 4  /* redux_sum_segmented, segments of exactly 1, 2, 4 or 8 KiB: one wavefront per
+    REDUX_KERNEL_TILES  = 4, /* redux_sum_segmented, segments of exactly 1, 2, 4 or 8 KiB: one wavefront per
                                 segment with the next segment's loads issued ahead */
+    REDUX_KERNEL_BLOCK  = 5  /* redux_sum_segmented, long segments: one block per segment or per piece of one
+                                (parts > 1: a per-segment finish kernel follows) */
 } redux_kernel;
 
 typedef struct {
     int      kernel;   /* a redux_kernel */
     int      unroll;   /* 16-byte loads in flight per lane (ROWS: per row group) */
     unsigned grid;     /* 256-thread blocks of the main kernel */
-    int      finish;   /* FLAT: 1 = in the same kernel, 2 = second kernel; PIECES: 2; else 0 */
-    uint64_t parts;    /* pieces per segment (1 unless PIECES) */
+    int      finish;   /* FLAT: 1 = in the same kernel, 2 = second kernel; segmented: 2 if parts > 1, else 0 */
+    uint64_t parts;    /* pieces per segment (above 1 only for PIECES and BLOCK) */
     uint64_t part_len; /* elements per piece */
     unsigned head;     /* FLAT: elements before the first 16-byte aligned vector */
     unsigned tail;     /* FLAT: elements after the last whole vector */
@@ -202,6 +204,8 @@ int redux_get_variant(void);
  *   "nontemporal"       0/1     use non-temporal (streaming) loads (default 1)
  *   "rows_max_vec"      0..64   segmented sum: segments of at most this many 16-byte vectors (and 16-byte
  *                               aligned) take the sixteen-segments-per-wavefront kernel; 0 = never (default 64)
+ *   "seg_block_bytes"   0..2^40 segmented sum: segments of at least this many bytes take one 256-thread block
+ *                               each (or one per piece) and are streamed like the flat sum; 0 = never (default 32768)
  *   "seg_tiles"         0/1     segmented sum: 16-byte aligned segments of exactly 1, 2, 4 or 8 KiB, at least
  *                               four per compute unit, take the pipelined one-wavefront-per-segment kernel (default 1)
  *   "seg_parts"         0,1,2,4,...,4096  segmented sum: pieces a long segment is cut into; 0 = from the

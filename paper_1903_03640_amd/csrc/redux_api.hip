@@ -28,6 +28,7 @@ struct Settings {
     long rows_max_vec = 64;       // short-segment kernel up to this many 16-byte vectors per segment (0 = off)
     long seg_parts = 0;           // 0 = pieces per long segment chosen from the shape
     long seg_tiles = 1;           // use the pipelined kernel for segments of 1, 2, 4 or 8 whole tiles
+    long seg_block_bytes = 32768; // segments of at least this many bytes take one block each (0 = never)
     long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
     long lit_blocks_per_cu = 0;
     long lit_m = 16;              // linear size m of the MMA matrices of the level-by-level form
@@ -266,6 +267,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "max_chain")) { *lo = 1; *hi = 65536; return &g_set.max_chain; }
     if (!std::strcmp(name, "max_grid")) { *lo = 1; *hi = kMaxGrid; return &g_set.max_grid; }
     if (!std::strcmp(name, "rows_max_vec")) { *lo = 0; *hi = 64; return &g_set.rows_max_vec; }
+    if (!std::strcmp(name, "seg_block_bytes")) { *lo = 0; *hi = (long)1 << 40; return &g_set.seg_block_bytes; }
     if (!std::strcmp(name, "seg_tiles")) { *lo = 0; *hi = 1; return &g_set.seg_tiles; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
     if (!std::strcmp(name, "lit_m")) { *lo = 4; *hi = 32; return &g_set.lit_m; }
@@ -348,8 +350,31 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         p.grid = (unsigned)(blocks < gmax ? blocks : gmax);
         return p;
     }
-    // A few long segments would leave most of the chip idle: cut each into a power-of-two number of
-    // pieces (whole 512-element tiles, at least 8 tiles each) until there are about 8 wavefronts per
+    // long segments (32 KiB and up): one block per segment, cut into pieces of at least 32 KiB while there are
+    // fewer than two pieces per compute unit, as far as the workspace allows
+    if (g_set.seg_block_bytes > 0 && seg_bytes >= (u64)g_set.seg_block_bytes) {
+        const u64 want_blocks = (u64)cus * 2;
+        u64 parts = 1;
+        if (g_set.seg_parts > 0) parts = (u64)g_set.seg_parts;
+        else while (nseg * parts < want_blocks && nseg * parts * 2 <= (u64)kMaxGrid && seg_bytes / (parts * 2) >= 32768) parts *= 2;
+        if (parts > 1 && nseg <= (u64)kMaxGrid / parts) {
+            p.parts = parts;
+            p.part_len = ((seglen + parts - 1) / parts + 511) / 512 * 512;
+        }
+        p.kernel = REDUX_KERNEL_BLOCK;
+        p.unroll = (int)g_set.unroll;
+        if (p.unroll == 0) p.unroll = 8;
+        // measured: two blocks per compute unit hide the per-piece fold for pieces below 512 KiB
+        const long bpc = g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : (p.part_len * es >= ((u64)512 << 10) ? 1 : 2);
+        const u64 blocks_needed = nseg * p.parts;
+        u64 gmax = (u64)cus * (u64)bpc;
+        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        if (gmax < 1) gmax = 1;
+        p.grid = (unsigned)(blocks_needed < gmax ? blocks_needed : gmax);
+        return p;
+    }
+    // A few segments below that size would leave most of the chip idle: cut each into a power-of-two number
+    // of pieces (whole 512-element tiles, at least 8 tiles each) until there are about 8 wavefronts per
     // compute unit, as far as the workspace allows.
     const u64 want_waves = (u64)cus * 8;
     u64 parts = 1;
@@ -494,7 +519,7 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     a.parts = plan.parts;
     a.part_len = plan.part_len;
     a.partials = nullptr;
-    if (plan.kernel == REDUX_KERNEL_PIECES) {
+    if (plan.parts > 1) {
         Workspace ws;
         if ((rc = get_workspace(dev, st, &ws)) != REDUX_OK) return rc;
         a.partials = ws.partials;
@@ -513,7 +538,17 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
         return e == hipSuccess ? REDUX_OK : hip_fail(e);
     }
 
-    with_seg_family(dtype, mfma, [&](auto family) { launch_seg<decltype(family)>(unroll, nt, grid, st, a); });
+    if (plan.kernel == REDUX_KERNEL_BLOCK) {
+        with_flat_family(dtype, mfma, [&](auto family) {      // four accumulator chains, as in the flat sum
+            typedef decltype(family) F;
+#define REDUX_BLOCK(UU) do { if (nt) hipLaunchKernelGGL((sum_segments_block_kernel<F, UU, true>), dim3(grid), dim3(kBlock), 0, st, a); \
+                             else    hipLaunchKernelGGL((sum_segments_block_kernel<F, UU, false>), dim3(grid), dim3(kBlock), 0, st, a); } while (0)
+            if (unroll == 8) REDUX_BLOCK(8); else if (unroll == 4) REDUX_BLOCK(4); else if (unroll == 2) REDUX_BLOCK(2); else REDUX_BLOCK(1);
+#undef REDUX_BLOCK
+        });
+    } else {
+        with_seg_family(dtype, mfma, [&](auto family) { launch_seg<decltype(family)>(unroll, nt, grid, st, a); });
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     if (a.parts > 1) {
@@ -679,7 +714,7 @@ int redux_plan_sum_segmented(size_t nseg, size_t seglen, int dtype, uintptr_t x_
     plan->kernel = p.kernel;
     plan->unroll = p.unroll;
     plan->grid = p.grid;
-    plan->finish = p.kernel == REDUX_KERNEL_PIECES ? 2 : 0;
+    plan->finish = p.parts > 1 ? 2 : 0;
     plan->parts = p.parts;
     plan->part_len = p.part_len;
     plan->head = 0;

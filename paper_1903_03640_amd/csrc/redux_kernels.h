@@ -659,6 +659,60 @@ __global__ void __launch_bounds__(kBlock) sum_segments_tiles_kernel(SegArgs a)
     }
 }
 
+// Long segments: one block per segment (or per piece of one).  The block streams its piece exactly like the
+// flat kernel streams the array -- slabs of U x 4 KiB, each load instruction of the block contiguous -- so a
+// handful of long segments reads HBM as a few hundred wide streams instead of thousands of narrow ones.
+template <class F, int U, bool NT>
+__global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
+{
+    typedef typename F::Total Total;
+    const unsigned tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    constexpr u64 kSlab = (u64)kBlock * U;
+    const u64 npieces = a.nseg * a.parts;
+    __shared__ Total lds[kWaves];
+
+    for (u64 piece = blockIdx.x; piece < npieces; piece += gridDim.x) {
+        const u64 seg = piece / a.parts, part = piece % a.parts;
+        const u64 first = part * a.part_len;
+        const u64 len = first < a.seglen ? (a.seglen - first < a.part_len ? a.seglen - first : a.part_len) : 0;
+        const Run run = make_run<F::kElemSize>(a.x + (seg * a.seglen + first) * F::kElemSize, len);
+        typename F::Acc acc;
+        F::clear(acc);
+        Total wave_total = 0;
+        unsigned chain = 0;
+        const u64 nslab = run.nvec / kSlab;
+        const u32x4 *p = run.body + tid;
+        for (u64 k = 0; k < nslab; ++k, p += kSlab) {
+            u32x4 cur[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) cur[u] = load16<NT>(p + u * kBlock);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
+            if (++chain >= a.max_chain) { wave_total += F::fold(acc); chain = 0; }
+        }
+        if (nslab * kSlab < run.nvec) {                    // the rest of the piece, lanes past its end add zeros
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const u64 idx = nslab * kSlab + (u64)u * kBlock + tid;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (idx < run.nvec) v = load16<NT>(run.body + idx);
+                F::consume(acc, u, v);
+            }
+        }
+        if (wave == 0 && (run.nhead | run.ntail)) F::consume(acc, 0, edge_vector<F>(run, (int)lane));
+        wave_total += F::fold(acc);
+        if (lane == 0) lds[wave] = wave_total;
+        __syncthreads();
+        if (tid == 0) {
+            const Total total = (lds[0] + lds[1]) + (lds[2] + lds[3]);
+            if (a.parts == 1) ((typename F::Out *)a.out)[seg] = F::to_out(total);
+            else a.partials[piece] = __builtin_bit_cast(u64, total);
+        }
+        __syncthreads();                                   // lds is reused by the next piece
+    }
+}
+
 // One block per segment adds that segment's piece totals in a fixed order.
 template <class F>
 __global__ void __launch_bounds__(kBlock) finish_segments_kernel(const u64 *partials, unsigned parts, void *out)

@@ -34,7 +34,7 @@ class Plan(ctypes.Structure):
                 ("vectors", ctypes.c_uint64)]
 
 
-KERNEL_FLAT, KERNEL_ROWS, KERNEL_WAVE, KERNEL_PIECES, KERNEL_TILES = 0, 1, 2, 3, 4
+KERNEL_FLAT, KERNEL_ROWS, KERNEL_WAVE, KERNEL_PIECES, KERNEL_TILES, KERNEL_BLOCK = 0, 1, 2, 3, 4, 5
 
 
 class ReduxError(RuntimeError):

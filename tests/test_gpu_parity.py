@@ -45,7 +45,7 @@ def default_params():
     for name, val in (("unroll", 0), ("nontemporal", 1), ("max_chain", 256),
                       ("max_grid", 16384), ("blocks_per_cu", DEFAULTS["blocks_per_cu"]),
                       ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
-                      ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("seg_tiles", 1), ("lit_unroll", 0),
+                      ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("seg_tiles", 1), ("seg_block_bytes", 32768), ("lit_unroll", 0),
                       ("lit_blocks_per_cu", 0), ("lit_m", 16)):
         redux.set_param(name, val)
     redux.set_variant("auto")
@@ -393,9 +393,11 @@ def test_segmented_short_rows_i8(dev, variant, seglen):
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("nseg,seglen,parts", [(3, (1 << 20) + 3, 0), (2, 1 << 22, 0), (256, 65536, 0), (5, 100003, 8),
                                                (1, (1 << 23) + 17, 0), (7, 5000, 4), (16, 1 << 16, 64), (3, 40, 2)])
-def test_segmented_long_pieces(dev, variant, nseg, seglen, parts):
+@pytest.mark.parametrize("block_bytes", [32768, 0, 4096])
+def test_segmented_long_pieces(dev, variant, nseg, seglen, parts, block_bytes):
     redux.set_variant(variant)
     redux.set_param("seg_parts", parts)
+    redux.set_param("seg_block_bytes", block_bytes)           # one block per piece, or (0) one wavefront per piece
     x = workloads.normal_f16(nseg + parts, nseg * seglen)
     want, want_abs = oracle.sum_segmented_f16(x, nseg, seglen)
     got = redux.sum_segmented(to_dev(x, dev, 1), nseg, seglen)
@@ -609,6 +611,7 @@ def test_randomised_shapes_and_settings(dev):
                 nseg = max(1, (1 << 23) // seglen)
             redux.set_param("seg_parts", int(rng.choice([0, 0, 2, 16])))
             redux.set_param("seg_tiles", int(rng.integers(0, 2)))
+            redux.set_param("seg_block_bytes", int(rng.choice([65536, 0, 2048])))
             n = nseg * seglen
         else:
             n = int(rng.choice([0, 1, 100, 4097, 70001, (1 << 20) + 5, (1 << 22) + 77]))

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(redux.LIB_PATH), reason="libr
 
 ES = {redux.F16: 2, redux.I8: 1, redux.BF16: 2, redux.F32: 4, redux.F8E4M3: 1, redux.F8E5M2: 1}
 DTYPES = sorted(ES)
-PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "layout")
+PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout")
 
 
 @pytest.fixture(autouse=True)
@@ -88,14 +88,15 @@ def test_slab_schedule_is_balanced_and_die_blocked():
 @given(nseg=st.one_of(st.integers(1, 300), st.integers(1, 1 << 24)), seglen=st.one_of(st.integers(1, 3000), st.integers(1, 1 << 26)),
        dtype=st.sampled_from(DTYPES), aligned=st.booleans(), cus=st.sampled_from([1, 104, 256]),
        seg_parts=st.sampled_from([0, 0, 0, 2, 8, 64, 4096]), rows_max=st.sampled_from([64, 64, 0, 5]),
-       seg_bpc=st.integers(0, 16), unroll=st.sampled_from([0, 1, 2, 4, 8]))
-def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll):
+       seg_bpc=st.integers(0, 16), unroll=st.sampled_from([0, 1, 2, 4, 8]), block_bytes=st.sampled_from([32768, 32768, 0, 1000]))
+def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll, block_bytes):
     es = ES[dtype]
     addr = 4096 if aligned else 4096 + es
     redux.set_param("seg_parts", seg_parts)
     redux.set_param("rows_max_vec", rows_max)
     redux.set_param("seg_blocks_per_cu", seg_bpc)
     redux.set_param("unroll", unroll)
+    redux.set_param("seg_block_bytes", block_bytes)
     p = redux.plan_sum_segmented(nseg, seglen, dtype, addr, cus)
     assert 1 <= p.grid <= 16 * cus
     if p.kernel == redux.KERNEL_ROWS:
@@ -108,6 +109,14 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
     elif p.kernel == redux.KERNEL_TILES:
         assert aligned and seglen * es == 1024 * p.unroll and p.unroll in (1, 2, 4, 8) and nseg >= 4 * cus
         assert p.parts == 1 and p.grid <= -(-nseg // 4)
+    elif p.kernel == redux.KERNEL_BLOCK:
+        assert block_bytes and seglen * es >= block_bytes and p.unroll in (1, 2, 4, 8)
+        assert p.parts & (p.parts - 1) == 0 and p.parts * p.part_len >= seglen
+        if p.parts > 1:
+            assert nseg * p.parts <= 16384 and p.part_len % 512 == 0 and p.finish == 2
+        else:
+            assert p.part_len == seglen and p.finish == 0
+        assert p.grid <= nseg * p.parts
     else:
         assert p.unroll in (1, 2, 4, 8)
         if p.kernel == redux.KERNEL_PIECES:
@@ -136,7 +145,12 @@ def test_segmented_plan_defaults_on_mi355x():
     assert redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256).kernel == redux.KERNEL_WAVE      # misaligned base
     assert redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256).kernel == redux.KERNEL_WAVE     # other dtypes
     long_ = redux.plan_sum_segmented(256, 1 << 20, redux.F16, 0, 256)
+    assert (long_.kernel, long_.parts, long_.part_len, long_.unroll, long_.grid) == (redux.KERNEL_BLOCK, 2, 524288, 8, 256)
+    assert redux.plan_sum_segmented(4096, 65536, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK      # 128 KiB each, no pieces
+    redux.set_param("seg_block_bytes", 0)
+    long_ = redux.plan_sum_segmented(256, 1 << 20, redux.F16, 0, 256)
     assert (long_.kernel, long_.parts, long_.part_len) == (redux.KERNEL_PIECES, 8, 131072)
+    redux.set_param("seg_block_bytes", 32768)
     assert redux.plan_sum_segmented(1, 100, redux.I8, 0, 256).kernel == redux.KERNEL_WAVE
 
 
