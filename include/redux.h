@@ -98,7 +98,7 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
  * already yields independent row sums).
  *
  *   x       device pointer, row-major [nseg][seglen], read only; may be NULL iff nseg*seglen == 0.
- *   out     device pointer to nseg results (float for F16, int64_t for I8).
+ *   out     device pointer to nseg results (int64_t for I8, float for every floating-point dtype).
  *   nseg == 0 is a no-op; seglen == 0 writes nseg zeros.
  *
  * The kernel is chosen from (nseg, seglen): short 16-byte-aligned segments (up to 1 KiB) go sixteen to
