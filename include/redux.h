@@ -166,8 +166,11 @@ typedef enum {
     REDUX_KERNEL_PIECES = 3, /* redux_sum_segmented, long segments cut into pieces + per-segment finish */
     REDUX_KERNEL_TILES  = 4, /* redux_sum_segmented, segments of exactly 1, 2, 4 or 8 KiB: one wavefront per
                                 segment with the next segment's loads issued ahead */
-    REDUX_KERNEL_BLOCK  = 5  /* redux_sum_segmented, long segments: one block per segment or per piece of one
+    REDUX_KERNEL_BLOCK  = 5, /* redux_sum_segmented, long segments: one block per segment or per piece of one
                                 (parts > 1: a per-segment finish kernel follows) */
+    REDUX_KERNEL_SHORT  = 6  /* redux_sum_segmented, 16-byte aligned segments of 16, 32, ... 1024 bytes: the array is
+                                read as one contiguous stream and 0/1 selection matrices in the two MMAs (or a
+                                shortened lane butterfly) yield every segment's sum */
 } redux_kernel;
 
 typedef struct {
@@ -206,6 +209,10 @@ int redux_get_variant(void);
  *                               aligned) take the sixteen-segments-per-wavefront kernel; 0 = never (default 64)
  *   "seg_block_bytes"   0..2^40 segmented sum: segments of at least this many bytes take one 256-thread block
  *                               each (or one per piece) and are streamed like the flat sum; 0 = never (default 32768)
+ *   "seg_short"         0/1     segmented sum: 16-byte aligned segments of a power-of-two size from 16 to 1024
+ *                               bytes take the contiguous-stream kernel (default 1)
+ *   "seg_short_pipe"    -1,0,1  that kernel: 1 = every register is reloaded from the block's next 32 KiB as soon as it has
+ *                               been consumed, 0 = plain load-then-work loop, -1 = the measured best for the shape (default -1)
  *   "seg_tiles"         0/1     segmented sum: 16-byte aligned segments of exactly 1, 2, 4 or 8 KiB, at least
  *                               four per compute unit, take the pipelined one-wavefront-per-segment kernel (default 1)
  *   "seg_parts"         0,1,2,4,...,4096  segmented sum: pieces a long segment is cut into; 0 = from the

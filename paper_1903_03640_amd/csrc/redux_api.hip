@@ -3,6 +3,7 @@
 #include "../../include/redux.h"
 #include "redux_kernels.h"
 #include "redux_literal.h"
+#include "redux_short.h"
 
 #include <climits>
 #include <cstdlib>
@@ -27,6 +28,8 @@ struct Settings {
     long layout = 2;
     long rows_max_vec = 64;       // short-segment kernel up to this many 16-byte vectors per segment (0 = off)
     long seg_parts = 0;           // 0 = pieces per long segment chosen from the shape
+    long seg_short_pipe = -1;     // that kernel: 1 = refill each register as soon as it is consumed, 0 = plain loop, -1 = measured best
+    long seg_short = 1;           // use the contiguous-stream kernel for aligned power-of-two segments of 16 B .. 1 KiB
     long seg_tiles = 1;           // use the pipelined kernel for segments of 1, 2, 4 or 8 whole tiles
     long seg_block_bytes = 32768; // segments of at least this many bytes take one block each (0 = never)
     long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
@@ -246,6 +249,19 @@ void with_seg_family(int dtype, bool mfma, Fn &&fn)
     }
 }
 
+template <class Fn>
+void with_short_family(int dtype, Fn &&fn)
+{
+    switch (dtype) {
+    case REDUX_F16:    fn(ShortFloat<kF16>());  break;
+    case REDUX_BF16:   fn(ShortFloat<kBF16>()); break;
+    case REDUX_F32:    fn(ShortFloat<kF32>());  break;
+    case REDUX_F8E4M3: fn(ShortFloat<kE4M3>()); break;
+    case REDUX_F8E5M2: fn(ShortFloat<kE5M2>()); break;
+    default:           fn(ShortI8());           break;
+    }
+}
+
 int effective_variant(int dtype)
 {
     int v = g_set.variant;
@@ -268,6 +284,8 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "max_grid")) { *lo = 1; *hi = kMaxGrid; return &g_set.max_grid; }
     if (!std::strcmp(name, "rows_max_vec")) { *lo = 0; *hi = 64; return &g_set.rows_max_vec; }
     if (!std::strcmp(name, "seg_block_bytes")) { *lo = 0; *hi = (long)1 << 40; return &g_set.seg_block_bytes; }
+    if (!std::strcmp(name, "seg_short_pipe")) { *lo = -1; *hi = 1; return &g_set.seg_short_pipe; }
+    if (!std::strcmp(name, "seg_short")) { *lo = 0; *hi = 1; return &g_set.seg_short; }
     if (!std::strcmp(name, "seg_tiles")) { *lo = 0; *hi = 1; return &g_set.seg_tiles; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
     if (!std::strcmp(name, "lit_m")) { *lo = 4; *hi = 32; return &g_set.lit_m; }
@@ -307,11 +325,11 @@ FlatPlan plan_flat(u64 nvec, int cus)
 }
 
 struct SegPlan {
-    int kernel;          // REDUX_KERNEL_ROWS, _WAVE or _PIECES
+    int kernel;          // REDUX_KERNEL_SHORT, _ROWS, _TILES, _BLOCK, _WAVE or _PIECES
     int unroll;          // rows: loads per row group per iteration; otherwise 16-byte loads in flight per lane
     unsigned grid;
     u64 parts, part_len; // pieces per segment and elements per piece (parts == 1: the whole segment)
-    unsigned nvec;       // rows: 16-byte vectors per segment
+    unsigned nvec;       // short, rows: 16-byte vectors per segment
 };
 
 SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_addr, int cus)
@@ -321,6 +339,20 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
     p.part_len = seglen;
     p.nvec = 0;
     const u64 seg_bytes = seglen * es;
+    // aligned power-of-two segments of 16 B .. 1 KiB: read as one contiguous stream, 0/1 selection matrices in the MMAs
+    if (g_set.seg_short && x_addr % 16 == 0 && seg_bytes >= 16 && seg_bytes <= 1024 && (seg_bytes & (seg_bytes - 1)) == 0) {
+        p.kernel = REDUX_KERNEL_SHORT;
+        p.nvec = (unsigned)(seg_bytes / 16);
+        p.unroll = kShortLoads;
+        const u64 nslab = (nseg * p.nvec + kShortSlab - 1) / kShortSlab;
+        // measured: one block per compute unit for the MMA family, two for the classic one (its conversions are longer)
+        const long best_bpc = effective_variant(dtype) == REDUX_VARIANT_MFMA ? 1 : 2;
+        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : best_bpc);
+        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        if (gmax < 1) gmax = 1;
+        p.grid = (unsigned)(nslab < gmax ? nslab : gmax);
+        return p;
+    }
     // short segments: sixteen per wavefront, one per row of the A operand
     if ((dtype == REDUX_F16 || dtype == REDUX_I8) && g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 && x_addr % 16 == 0 &&
         seg_bytes / 16 <= (u64)g_set.rows_max_vec) {
@@ -489,6 +521,37 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     const SegPlan plan = plan_segmented(nseg, seglen, dtype, es, (uintptr_t)x, cus);
     const unsigned grid = plan.grid;
 
+    // ---- short power-of-two segments: one contiguous stream ---------------------------------------------
+    if (plan.kernel == REDUX_KERNEL_SHORT) {
+        ShortArgs s;
+        s.x = (const u32x4 *)x;
+        s.nseg = nseg;
+        s.nvec = (u64)nseg * plan.nvec;
+        s.lg = 0;
+        while ((1u << s.lg) < plan.nvec) ++s.lg;
+        s.out = out;
+        s.layout = (int)g_set.layout;
+        // measured: refilling registers one by one hides the second MMA and the stores of segments up to
+        // 256 B (and the classic family's conversions); longer segments run fastest as a plain loop
+        // (binary32 excepted: it needs four MMAs per load)
+        s.pipe = g_set.seg_short_pipe >= 0 ? (int)g_set.seg_short_pipe : (mfma && s.lg >= 5 && dtype != REDUX_F32 ? 0 : 1);
+        const bool wide = s.lg >= 5;       // 32 or 64 vectors per segment: eight loads share an accumulator
+        with_short_family(dtype, [&](auto elem) {
+            typedef decltype(elem) E;
+            if (mfma) {
+                if (wide) { if (nt) hipLaunchKernelGGL((sum_short_mfma_kernel<E, 8, true>), dim3(grid), dim3(kBlock), 0, st, s);
+                            else    hipLaunchKernelGGL((sum_short_mfma_kernel<E, 8, false>), dim3(grid), dim3(kBlock), 0, st, s); }
+                else      { if (nt) hipLaunchKernelGGL((sum_short_mfma_kernel<E, 4, true>), dim3(grid), dim3(kBlock), 0, st, s);
+                            else    hipLaunchKernelGGL((sum_short_mfma_kernel<E, 4, false>), dim3(grid), dim3(kBlock), 0, st, s); }
+            } else {
+                if (nt) hipLaunchKernelGGL((sum_short_classic_kernel<E, true>), dim3(grid), dim3(kBlock), 0, st, s);
+                else    hipLaunchKernelGGL((sum_short_classic_kernel<E, false>), dim3(grid), dim3(kBlock), 0, st, s);
+            }
+        });
+        e = hipGetLastError();
+        return e == hipSuccess ? REDUX_OK : hip_fail(e);
+    }
+
     // ---- short segments: sixteen per wavefront, one per row of the A operand -------------------------
     if (plan.kernel == REDUX_KERNEL_ROWS) {
         RowArgs r;
@@ -529,10 +592,14 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     if (plan.kernel == REDUX_KERNEL_TILES) {
         with_seg_family(dtype, mfma, [&](auto family) {
             typedef decltype(family) F;
-#define REDUX_TILES(UU) do { if (nt) hipLaunchKernelGGL((sum_segments_tiles_kernel<F, UU, true>), dim3(grid), dim3(kBlock), 0, st, a); \
-                             else    hipLaunchKernelGGL((sum_segments_tiles_kernel<F, UU, false>), dim3(grid), dim3(kBlock), 0, st, a); } while (0)
+            // measured on 8 KiB segments: issuing the next segment's loads ahead gains 1 % with the MMA family and loses
+            // as much with the classic one
+#define REDUX_TILES_P(UU, PP) do { if (nt) hipLaunchKernelGGL((sum_segments_tiles_kernel<F, UU, true, PP>), dim3(grid), dim3(kBlock), 0, st, a); \
+                                   else    hipLaunchKernelGGL((sum_segments_tiles_kernel<F, UU, false, PP>), dim3(grid), dim3(kBlock), 0, st, a); } while (0)
+#define REDUX_TILES(UU) do { if (mfma) REDUX_TILES_P(UU, 1); else REDUX_TILES_P(UU, 0); } while (0)
             if (unroll == 8) REDUX_TILES(8); else if (unroll == 4) REDUX_TILES(4); else if (unroll == 2) REDUX_TILES(2); else REDUX_TILES(1);
 #undef REDUX_TILES
+#undef REDUX_TILES_P
         });
         e = hipGetLastError();
         return e == hipSuccess ? REDUX_OK : hip_fail(e);

@@ -621,41 +621,57 @@ __global__ void __launch_bounds__(kBlock) sum_segmented_kernel(SegArgs a)
     }
 }
 
-// Segments that are exactly U whole tiles (1, 2, 4 or 8 KiB, 16-byte aligned): one wavefront per segment,
-// the whole segment in flight at once, and the next segment's loads issued before the current one is
-// pushed through the MMAs and folded, so that the fold never leaves the memory pipe idle.
-template <class F, int U, bool NT>
+// Segments that are exactly U whole tiles (1, 2, 4 or 8 KiB, 16-byte aligned): one wavefront per segment, the
+// whole segment in flight at once, nothing but the MMAs, the fold and one store per segment.
+// PIPE 0: plain loop.  PIPE 1: the next segment's loads are issued before the current one is worked on
+// (the wait in front of the MMAs still covers both segments, because the loads ahead are conditional).
+template <class F, int U, bool NT, int PIPE>
 __global__ void __launch_bounds__(kBlock) sum_segments_tiles_kernel(SegArgs a)
 {
     typedef typename F::Total Total;
     const unsigned lane = threadIdx.x & 63u;
     const u64 wave_global = (u64)blockIdx.x * kWaves + (threadIdx.x >> 6);
     const u64 nwaves = (u64)gridDim.x * kWaves;
-    const u32x4 *base = (const u32x4 *)a.x;
-    u64 seg = wave_global;
-    if (seg >= a.nseg) return;
-
-    u32x4 cur[U];
+    const u32x4 *base = (const u32x4 *)a.x + lane;
+    typename F::Out *out = (typename F::Out *)a.out;
+    if (PIPE == 0) {
+        for (u64 seg = wave_global; seg < a.nseg; seg += nwaves) {
+            u32x4 cur[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) cur[u] = load16<NT>(base + seg * (64ull * U) + (u64)u * 64 + lane);
-    while (true) {
-        const u64 next = seg + nwaves;
-        const bool more = next < a.nseg;                   // the same for every lane of the wavefront
-        u32x4 nxt[U];
-        if (more) {
+            for (int u = 0; u < U; ++u) cur[u] = load16<NT>(base + seg * (64ull * U) + (u64)u * 64);
+            __builtin_amdgcn_sched_barrier(0);
+            typename F::Acc acc;
+            F::clear(acc);
 #pragma unroll
-            for (int u = 0; u < U; ++u) nxt[u] = load16<NT>(base + next * (64ull * U) + (u64)u * 64 + lane);
+            for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
+            const Total total = F::fold(acc);
+            if (lane == 0) out[seg] = F::to_out(total);
         }
-        __builtin_amdgcn_sched_barrier(0);
-        typename F::Acc acc;
-        F::clear(acc);
+    } else {
+        u64 seg = wave_global;
+        if (seg >= a.nseg) return;
+        u32x4 cur[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
-        const Total total = F::fold(acc);
-        if (lane == 0) ((typename F::Out *)a.out)[seg] = F::to_out(total);
-        if (!more) break;
-        for (int u = 0; u < U; ++u) cur[u] = nxt[u];      // constant trip count: becomes register renaming
-        seg = next;
+        for (int u = 0; u < U; ++u) cur[u] = load16<NT>(base + seg * (64ull * U) + (u64)u * 64);
+        while (true) {
+            const u64 next = seg + nwaves;
+            const bool more = next < a.nseg;                   // the same for every lane of the wavefront
+            u32x4 nxt[U];
+            if (more) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) nxt[u] = load16<NT>(base + next * (64ull * U) + (u64)u * 64);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            typename F::Acc acc;
+            F::clear(acc);
+#pragma unroll
+            for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
+            const Total total = F::fold(acc);
+            if (lane == 0) out[seg] = F::to_out(total);
+            if (!more) break;
+            for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+            seg = next;
+        }
     }
 }
 

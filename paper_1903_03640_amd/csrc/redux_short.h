@@ -1,0 +1,298 @@
+// redux_short.h -- segmented sum of short power-of-two segments (16 B .. 1 KiB each), read as one
+// contiguous stream.
+//
+// A segment here is 2^lg whole 16-byte vectors (lg = 0 .. 6) and the array starts on a 16-byte
+// boundary, so every wavefront-wide load (64 vectors, 1 KiB) holds whole segments and the grid can read
+// the array exactly like the flat sum does.  What changes is the constant operand of the two MMAs of
+// Section IV-A: instead of all ones they are 0/1 *selection* matrices, so one MMA pair yields many
+// independent sums instead of one.
+//
+//   first MMA   D <- A x B_t + D.  Lane l of a load holds vector l, which the matrix unit reads as
+//               A[l % 16][k-group l / 16].  B_t has ones only where k-group g meets column c(t, g), so
+//               D[i][c(t, g)] is the sum of the elements of vector 16 g + i of load t: up to four
+//               loads (sixteen k-groups) share one accumulator and fill its sixteen columns with 256
+//               per-vector sums.  For segments of 32 or 64 vectors two or four k-groups share a column.
+//   second MMA  D' <- S x D with S[m][i] = 1 where row i belongs to sub-segment m of its column
+//               (i >> lg == m): D'[m][c] is the sum of segment m of column c.  For segments of sixteen
+//               vectors or more S is all ones, the second MMA of the paper.
+//
+// The classic family adds each vector inside its lane and stops the lane butterfly of Section III
+// after lg steps.
+#pragma once
+#include "redux_kernels.h"
+
+namespace redux {
+
+constexpr int kShortLoads = 8;                                   // 16-byte loads per lane per slab
+constexpr u64 kShortSlab = (u64)kBlock * kShortLoads;            // vectors per slab (32 KiB)
+
+struct ShortArgs {
+    const u32x4 *x;     // 16-byte aligned
+    u64 nseg;
+    u64 nvec;           // nseg << lg
+    unsigned lg;        // log2(vectors per segment), 0 .. 6
+    void *out;
+    int layout;         // see slab_schedule
+    int pipe;           // 0 = plain loop, 1 = refill each register as soon as it is consumed
+};
+
+// vector index, inside its slab, of the vector that load u of thread tid reads: every load of the block
+// covers 4 KiB contiguous, every wavefront 1 KiB of it
+__device__ __forceinline__ unsigned short_index(int u, unsigned tid)
+{
+    return (unsigned)u * kBlock + tid;
+}
+
+// `count` (1, 2 or 4) consecutive results of one lane, as one store where alignment allows
+template <class Out>
+__device__ __forceinline__ void short_store(Out *p, const Out *v, unsigned count, u64 room)
+{
+    typedef Out Out4 __attribute__((ext_vector_type(4)));
+    typedef Out Out2 __attribute__((ext_vector_type(2)));
+    if (count == 4 && room >= 4 && ((uintptr_t)p & (4 * sizeof(Out) - 1)) == 0) {
+        *(Out4 *)p = Out4{v[0], v[1], v[2], v[3]};
+    } else if (count == 2 && room >= 2 && ((uintptr_t)p & (2 * sizeof(Out) - 1)) == 0) {
+        *(Out2 *)p = Out2{v[0], v[1]};
+    } else {
+#pragma unroll
+        for (unsigned r = 0; r < 4; ++r)
+            if (r < count && r < room) p[r] = v[r];
+    }
+}
+
+// first MMA with a 0/1 column selector as the constant operand: `sel` says whether this lane's slice of
+// B is ones (its k-group feeds the column the lane holds) or zeros
+template <int KIND>
+__device__ __forceinline__ f32x4 mma1_select(u32x4 v, bool sel, f32x4 d)
+{
+    if (KIND == kF16) {
+        const unsigned w = sel ? 0x3C003C00u : 0u;
+        const u32x4 b = {w, w, w, w};
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, v), __builtin_bit_cast(f16x8, b), d, 0, 0, 0);
+    } else if (KIND == kBF16) {
+        const unsigned w = sel ? 0x3F803F80u : 0u;
+        const u32x4 b = {w, w, w, w};
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v), __builtin_bit_cast(bf16x8, b), d, 0, 0, 0);
+    } else if (KIND == kF32) {
+        const f32x4 f = __builtin_bit_cast(f32x4, v);
+        const float b = sel ? 1.0f : 0.0f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) d = __builtin_amdgcn_mfma_f32_16x16x4f32(f[k], b, d, 0, 0, 0);
+        return d;
+    } else {
+        const long lo = (long)(((u64)v[1] << 32) | v[0]), hi = (long)(((u64)v[3] << 32) | v[2]);
+        if (KIND == kE4M3) {
+            const long b = sel ? 0x3838383838383838L : 0L;
+            d = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(lo, b, d, 0, 0, 0);
+            return __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(hi, b, d, 0, 0, 0);
+        } else {
+            const long b = sel ? 0x3C3C3C3C3C3C3C3CL : 0L;
+            d = __builtin_amdgcn_mfma_f32_16x16x32_bf8_bf8(lo, b, d, 0, 0, 0);
+            return __builtin_amdgcn_mfma_f32_16x16x32_bf8_bf8(hi, b, d, 0, 0, 0);
+        }
+    }
+}
+
+// Element policies: how one vector enters the first MMA (or is added inside a lane), and how a
+// per-segment result leaves.
+template <int KIND>
+struct ShortFloat {
+    typedef float Out;
+    typedef f32x4 Acc;
+    typedef float Lane;
+    static __device__ __forceinline__ Acc zero() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+    static __device__ __forceinline__ Acc mma1(u32x4 v, bool sel, Acc d) { return mma1_select<KIND>(v, sel, d); }
+    static __device__ __forceinline__ float fold_in(const Acc &d, int r) { return d[r]; }
+    static __device__ __forceinline__ Out fold_out(float f) { return f; }
+    static __device__ __forceinline__ Lane lane_sum(u32x4 v)
+    {
+        float s[4] = {0.f, 0.f, 0.f, 0.f};
+        add_vector<KIND>(s, v);
+        return (s[0] + s[1]) + (s[2] + s[3]);
+    }
+    static __device__ __forceinline__ Out lane_out(Lane v) { return v; }
+};
+
+// int8: a vector sums to at most 16 x 128 and a segment to at most 64 times that, so the binary32
+// second MMA (and the int32 lane butterfly) are exact.
+struct ShortI8 {
+    typedef i64 Out;
+    typedef i32x4 Acc;
+    typedef int Lane;
+    static __device__ __forceinline__ Acc zero() { return i32x4{0, 0, 0, 0}; }
+    static __device__ __forceinline__ Acc mma1(u32x4 v, bool sel, Acc d)
+    {
+        const int w = sel ? 0x01010101 : 0;
+        const i32x4 b = {w, w, w, w};
+        return __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, v), b, d, 0, 0, 0);
+    }
+    static __device__ __forceinline__ float fold_in(const Acc &d, int r) { return (float)d[r]; }
+    static __device__ __forceinline__ Out fold_out(float f) { return (i64)f; }
+    static __device__ __forceinline__ Lane lane_sum(u32x4 v)
+    {
+        int s = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s = __builtin_amdgcn_sdot4((int)v[k], 0x01010101, s, false);
+        return s;
+    }
+    static __device__ __forceinline__ Out lane_out(Lane v) { return (i64)v; }
+};
+
+// One whole slab into registers.
+template <bool NT>
+__device__ __forceinline__ void short_load(u32x4 *dst, const ShortArgs &a, u64 slab, unsigned tid)
+{
+    const u32x4 *p = a.x + slab * kShortSlab;
+#pragma unroll
+    for (int u = 0; u < kShortLoads; ++u) dst[u] = load16<NT>(p + short_index(u, tid));
+}
+
+// The slab that holds the end of the array; lanes past the end read zeros.
+template <bool NT>
+__device__ __forceinline__ void short_load_partial(u32x4 *dst, const ShortArgs &a, u64 slab, unsigned tid)
+{
+#pragma unroll
+    for (int u = 0; u < kShortLoads; ++u) {
+        const u64 idx = slab * kShortSlab + short_index(u, tid);
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (idx < a.nvec) v = load16<NT>(a.x + idx);
+        dst[u] = v;
+    }
+}
+
+// `work(cur, slab, refill)` does everything for one slab held in `cur` and calls refill(u) as soon as it has
+// consumed cur[u]: the register is then reloaded with the same block's next slab, so eight loads per lane stay
+// in flight while the MMAs (or the butterfly) and the stores run.  The block's last slab is peeled off, so that
+// no load in the loop is conditional and the wait in front of each use leaves exactly the seven newer loads
+// outstanding.  The slab that holds the ragged end of the array is done by one block afterwards.
+template <bool NT, class Work>
+__device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, Work &&work)
+{
+    const u64 nfull = a.nvec / kShortSlab;
+    u64 s0, stride, count;
+    slab_schedule(a.layout, nfull, gridDim.x, blockIdx.x, &s0, &stride, &count);
+    if (count && a.pipe == 0) {
+        for (u64 k = 0; k < count; ++k) {
+            u32x4 cur[kShortLoads];
+            short_load<NT>(cur, a, s0 + k * stride, tid);
+            __builtin_amdgcn_sched_barrier(0);
+            work(cur, s0 + k * stride, [](int) {});
+        }
+    } else if (count) {
+        u32x4 cur[kShortLoads];
+        {   // issued strictly in the order they are consumed in: the waits in the loop count on it
+            const u32x4 *first = a.x + s0 * kShortSlab;
+#pragma unroll
+            for (int u = 0; u < kShortLoads; ++u) {
+                cur[u] = load16<NT>(first + short_index(u, tid));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        u64 slab = s0;
+        for (u64 k = 1; k < count; ++k, slab += stride) {
+            const u32x4 *next = a.x + (slab + stride) * kShortSlab;
+            __builtin_amdgcn_sched_barrier(0);
+            work(cur, slab, [&](int u) {
+                cur[u] = load16<NT>(next + short_index(u, tid));
+                __builtin_amdgcn_sched_barrier(0);                   // keep the refill right behind the use
+            });
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        work(cur, slab, [](int) {});
+    }
+    if (nfull * kShortSlab < a.nvec && blockIdx.x == (unsigned)(nfull % gridDim.x)) {
+        u32x4 last[kShortLoads];
+        short_load_partial<NT>(last, a, nfull, tid);
+        work(last, nfull, [](int) {});
+    }
+}
+
+// LPA = loads that share one accumulator: 4 for segments up to sixteen vectors (four columns per load),
+// 8 for segments of 32 or 64 vectors (two columns or one column per load).
+template <class E, int LPA, bool NT>
+__global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
+{
+    constexpr int U = kShortLoads;
+    constexpr int NACC = U / LPA;
+    const unsigned tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const unsigned g = lane >> 4, n = lane & 15u;
+    const unsigned lg = a.lg;
+    const unsigned cpl = LPA == 4 ? 4u : (lg == 5 ? 2u : 1u);      // columns per load
+    const unsigned lgc = lg < 4 ? lg : 4u;
+    const unsigned mask = (16u >> lgc) - 1u;                       // segments per column - 1
+
+    // first MMA: k-group g of load t feeds column t * cpl + g * cpl / 4
+    bool sel[LPA];
+#pragma unroll
+    for (int t = 0; t < LPA; ++t) sel[t] = (n == (unsigned)t * cpl + (g * cpl) / 4u);
+    // second MMA, step r: the A operand of this lane is S[m = n][i = 4 g + r]
+    float srow[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) srow[r] = (((4u * g + (unsigned)r) >> lgc) == (n & mask)) ? 1.0f : 0.0f;
+    // after the second MMA this lane holds rows m = 4 g + r' of column n: the sums of segments m of
+    // the 64 / cpl vectors that start at vector col_off of load col_load
+    const bool col_used = n < (unsigned)LPA * cpl && 4u * g <= mask;
+    const unsigned col_load = n / cpl;
+    const unsigned col_off = (n % cpl) * (64u / cpl);
+    const unsigned per_lane = mask >= 3u ? 4u : mask + 1u;        // results this lane writes per accumulator: 4, 2 or 1
+    typename E::Out *out = (typename E::Out *)a.out;
+
+    short_stream<NT>(a, tid, [&](const u32x4 *cur, u64 slab, auto refill) {
+#pragma unroll
+        for (int q = 0; q < NACC; ++q) {
+            typename E::Acc d = E::zero();
+#pragma unroll
+            for (int t = 0; t < LPA; ++t) {
+                d = E::mma1(cur[q * LPA + t], sel[t], d);
+                refill(q * LPA + t);
+            }
+            f32x4 dp = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dp = __builtin_amdgcn_mfma_f32_16x16x4f32(srow[r], E::fold_in(d, r), dp, 0, 0, 0);
+            if (col_used) {
+                const u64 vb = slab * kShortSlab + short_index(q * LPA + (int)col_load, wave * 64u) + col_off;
+                const u64 seg0 = (vb >> lg) + 4u * g;
+                if (seg0 < a.nseg) {
+                    const typename E::Out res[4] = {E::fold_out(dp[0]), E::fold_out(dp[1]), E::fold_out(dp[2]), E::fold_out(dp[3])};
+                    short_store(out + seg0, res, per_lane, a.nseg - seg0);
+                }
+            }
+        }
+    });
+}
+
+template <class T, int CTRL>
+__device__ __forceinline__ T dpp_add(T v)
+{
+    return v + __builtin_bit_cast(T, dpp_i32<CTRL>(__builtin_bit_cast(int, v)));
+}
+
+template <class E, bool NT>
+__global__ void __launch_bounds__(kBlock) sum_short_classic_kernel(ShortArgs a)
+{
+    typedef typename E::Lane Lane;
+    const unsigned tid = threadIdx.x, lane = tid & 63u;
+    const unsigned lg = a.lg;
+    const bool writer = (lane & ((1u << lg) - 1u)) == 0;
+    typename E::Out *out = (typename E::Out *)a.out;
+
+    short_stream<NT>(a, tid, [&](const u32x4 *cur, u64 slab, auto refill) {
+#pragma unroll
+        for (int u = 0; u < kShortLoads; ++u) {
+            Lane s = E::lane_sum(cur[u]);
+            refill(u);
+            // butterfly over the 2^lg lanes of a segment; lg is the same for every lane
+            if (lg >= 1) s = dpp_add<Lane, kQuadXor1>(s);
+            if (lg >= 2) s = dpp_add<Lane, kQuadXor2>(s);
+            if (lg >= 3) s = dpp_add<Lane, kRowHalfMirror>(s);
+            if (lg >= 4) s = dpp_add<Lane, kRowMirror>(s);
+            if (lg >= 5) s = s + __builtin_bit_cast(Lane, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, s), kSwizzleXor16));
+            if (lg >= 6) s = __builtin_bit_cast(Lane, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 0)) +
+                             __builtin_bit_cast(Lane, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 32));
+            const u64 seg = (slab * kShortSlab + short_index(u, tid)) >> lg;
+            if (writer && seg < a.nseg) out[seg] = E::lane_out(s);
+        }
+    });
+}
+
+} // namespace redux

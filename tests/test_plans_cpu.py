@@ -12,7 +12,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(redux.LIB_PATH), reason="libr
 
 ES = {redux.F16: 2, redux.I8: 1, redux.BF16: 2, redux.F32: 4, redux.F8E4M3: 1, redux.F8E5M2: 1}
 DTYPES = sorted(ES)
-PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout")
+PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short")
 
 
 @pytest.fixture(autouse=True)
@@ -85,11 +85,12 @@ def test_slab_schedule_is_balanced_and_die_blocked():
 
 
 @settings(max_examples=500, deadline=None)
-@given(nseg=st.one_of(st.integers(1, 300), st.integers(1, 1 << 24)), seglen=st.one_of(st.integers(1, 3000), st.integers(1, 1 << 26)),
+@given(nseg=st.one_of(st.integers(1, 300), st.integers(1, 1 << 24)), seglen=st.one_of(st.integers(1, 3000), st.integers(1, 1 << 26), st.sampled_from([4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048])),
        dtype=st.sampled_from(DTYPES), aligned=st.booleans(), cus=st.sampled_from([1, 104, 256]),
        seg_parts=st.sampled_from([0, 0, 0, 2, 8, 64, 4096]), rows_max=st.sampled_from([64, 64, 0, 5]),
-       seg_bpc=st.integers(0, 16), unroll=st.sampled_from([0, 1, 2, 4, 8]), block_bytes=st.sampled_from([32768, 32768, 0, 1000]))
-def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll, block_bytes):
+       seg_bpc=st.integers(0, 16), unroll=st.sampled_from([0, 1, 2, 4, 8]), block_bytes=st.sampled_from([32768, 32768, 0, 1000]),
+       seg_short=st.sampled_from([1, 1, 0]))
+def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll, block_bytes, seg_short):
     es = ES[dtype]
     addr = 4096 if aligned else 4096 + es
     redux.set_param("seg_parts", seg_parts)
@@ -97,9 +98,15 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
     redux.set_param("seg_blocks_per_cu", seg_bpc)
     redux.set_param("unroll", unroll)
     redux.set_param("seg_block_bytes", block_bytes)
+    redux.set_param("seg_short", seg_short)
     p = redux.plan_sum_segmented(nseg, seglen, dtype, addr, cus)
     assert 1 <= p.grid <= 16 * cus
-    if p.kernel == redux.KERNEL_ROWS:
+    pow2_short = aligned and 16 <= seglen * es <= 1024 and (seglen * es) & (seglen * es - 1) == 0
+    assert (p.kernel == redux.KERNEL_SHORT) == bool(seg_short and pow2_short)
+    if p.kernel == redux.KERNEL_SHORT:
+        assert p.vectors == seglen * es // 16 and p.unroll == 8 and p.parts == 1
+        assert p.grid <= max(1, -(-(nseg * p.vectors) // 2048))            # never more blocks than 32 KiB slabs
+    elif p.kernel == redux.KERNEL_ROWS:
         assert dtype in (redux.F16, redux.I8) and aligned and (seglen * es) % 16 == 0
         assert p.vectors == seglen * es // 16 and 1 <= p.vectors <= rows_max
         assert p.unroll in (1, 2, 4, 8) and (p.vectors <= 4 * p.unroll or p.unroll == 8)
@@ -141,9 +148,17 @@ def test_segmented_plan_defaults_on_mi355x():
     assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE
     assert redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE  # 3 tiles: not a power of two
     short = redux.plan_sum_segmented(1 << 22, 64, redux.F16, 0, 256)
+    assert (short.kernel, short.vectors, short.unroll, short.grid) == (redux.KERNEL_SHORT, 8, 8, 256)   # 128 B: contiguous stream
+    assert redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256).kernel == redux.KERNEL_SHORT     # every dtype
+    assert redux.plan_sum_segmented(100, 64, redux.F16, 0, 256).grid == 1                             # 12.5 KiB: one slab
+    rows = redux.plan_sum_segmented(1 << 22, 72, redux.F16, 0, 256)
+    assert (rows.kernel, rows.vectors, rows.unroll) == (redux.KERNEL_ROWS, 9, 4)                      # 144 B: not a power of two
+    redux.set_param("seg_short", 0)
+    short = redux.plan_sum_segmented(1 << 22, 64, redux.F16, 0, 256)
     assert (short.kernel, short.vectors, short.unroll) == (redux.KERNEL_ROWS, 8, 2)
+    assert redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256).kernel == redux.KERNEL_WAVE     # rows: binary16 and int8 only
+    redux.set_param("seg_short", 1)
     assert redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256).kernel == redux.KERNEL_WAVE      # misaligned base
-    assert redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256).kernel == redux.KERNEL_WAVE     # other dtypes
     long_ = redux.plan_sum_segmented(256, 1 << 20, redux.F16, 0, 256)
     assert (long_.kernel, long_.parts, long_.part_len, long_.unroll, long_.grid) == (redux.KERNEL_BLOCK, 2, 524288, 8, 256)
     assert redux.plan_sum_segmented(4096, 65536, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK      # 128 KiB each, no pieces
