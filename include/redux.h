@@ -168,9 +168,11 @@ typedef enum {
                                 segment with the next segment's loads issued ahead */
     REDUX_KERNEL_BLOCK  = 5, /* redux_sum_segmented, long segments: one block per segment or per piece of one
                                 (parts > 1: a per-segment finish kernel follows) */
-    REDUX_KERNEL_SHORT  = 6  /* redux_sum_segmented, 16-byte aligned segments of 16, 32, ... 1024 bytes: the array is
+    REDUX_KERNEL_SHORT  = 6, /* redux_sum_segmented, 16-byte aligned segments of 16, 32, ... 1024 bytes: the array is
                                 read as one contiguous stream and 0/1 selection matrices in the two MMAs (or a
                                 shortened lane butterfly) yield every segment's sum */
+    REDUX_KERNEL_RAGGED = 7  /* redux_sum_segmented, any other segment of up to 1008 bytes: the same kernel, each group
+                                of `vectors` lanes reading the aligned vectors that overlap its segment */
 } redux_kernel;
 
 typedef struct {
@@ -211,6 +213,8 @@ int redux_get_variant(void);
  *                               each (or one per piece) and are streamed like the flat sum; 0 = never (default 32768)
  *   "seg_short"         0/1     segmented sum: 16-byte aligned segments of a power-of-two size from 16 to 1024
  *                               bytes take the contiguous-stream kernel (default 1)
+ *   "seg_ragged"        0/1     segmented sum: every other segment of up to 1008 bytes takes that kernel's ragged form
+ *                               (after "rows_max_vec" has had its pick) (default 1)
  *   "seg_short_pipe"    -1,0,1  that kernel: 1 = every register is reloaded from the block's next 32 KiB as soon as it has
  *                               been consumed, 0 = plain load-then-work loop, -1 = the measured best for the shape (default -1)
  *   "seg_tiles"         0/1     segmented sum: 16-byte aligned segments of exactly 1, 2, 4 or 8 KiB, at least

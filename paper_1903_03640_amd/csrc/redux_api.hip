@@ -29,6 +29,7 @@ struct Settings {
     long rows_max_vec = 64;       // short-segment kernel up to this many 16-byte vectors per segment (0 = off)
     long seg_parts = 0;           // 0 = pieces per long segment chosen from the shape
     long seg_short_pipe = -1;     // that kernel: 1 = refill each register as soon as it is consumed, 0 = plain loop, -1 = measured best
+    long seg_ragged = 1;          // use that kernel's ragged form for all other segments of up to 1008 bytes
     long seg_short = 1;           // use the contiguous-stream kernel for aligned power-of-two segments of 16 B .. 1 KiB
     long seg_tiles = 1;           // use the pipelined kernel for segments of 1, 2, 4 or 8 whole tiles
     long seg_block_bytes = 32768; // segments of at least this many bytes take one block each (0 = never)
@@ -285,6 +286,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "rows_max_vec")) { *lo = 0; *hi = 64; return &g_set.rows_max_vec; }
     if (!std::strcmp(name, "seg_block_bytes")) { *lo = 0; *hi = (long)1 << 40; return &g_set.seg_block_bytes; }
     if (!std::strcmp(name, "seg_short_pipe")) { *lo = -1; *hi = 1; return &g_set.seg_short_pipe; }
+    if (!std::strcmp(name, "seg_ragged")) { *lo = 0; *hi = 1; return &g_set.seg_ragged; }
     if (!std::strcmp(name, "seg_short")) { *lo = 0; *hi = 1; return &g_set.seg_short; }
     if (!std::strcmp(name, "seg_tiles")) { *lo = 0; *hi = 1; return &g_set.seg_tiles; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
@@ -325,11 +327,11 @@ FlatPlan plan_flat(u64 nvec, int cus)
 }
 
 struct SegPlan {
-    int kernel;          // REDUX_KERNEL_SHORT, _ROWS, _TILES, _BLOCK, _WAVE or _PIECES
+    int kernel;          // REDUX_KERNEL_SHORT, _ROWS, _RAGGED, _TILES, _BLOCK, _WAVE or _PIECES
     int unroll;          // rows: loads per row group per iteration; otherwise 16-byte loads in flight per lane
     unsigned grid;
     u64 parts, part_len; // pieces per segment and elements per piece (parts == 1: the whole segment)
-    unsigned nvec;       // short, rows: 16-byte vectors per segment
+    unsigned nvec;       // short, rows: 16-byte vectors per segment; ragged: lanes per segment
 };
 
 SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_addr, int cus)
@@ -367,6 +369,25 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
         if (gmax < 1) gmax = 1;
         p.grid = (unsigned)(blocks < gmax ? blocks : gmax);
+        return p;
+    }
+    // any other segment of up to 1008 bytes: the same contiguous stream, each group of 2^lg lanes reading the aligned
+    // vectors that overlap its segment and clearing the bytes outside it
+    if (g_set.seg_ragged && seg_bytes <= 1008 && nseg <= ((u64)1 << 56)) {
+        // most vectors a segment can touch: its first byte sits at most 16 - es bytes into a vector (at exactly
+        // x mod 16 if segments are whole vectors long)
+        const u64 max_off = seg_bytes % 16 == 0 ? (u64)(x_addr % 16) : (u64)(16 - es);
+        const u64 cover = (max_off + seg_bytes + 15) / 16;
+        unsigned lg = 0;
+        while ((1ull << lg) < cover) ++lg;
+        p.kernel = REDUX_KERNEL_RAGGED;
+        p.nvec = 1u << lg;
+        p.unroll = kShortLoads;
+        const u64 nslab = ((nseg << lg) + kShortSlab - 1) / kShortSlab;
+        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 2);
+        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        if (gmax < 1) gmax = 1;
+        p.grid = (unsigned)(nslab < gmax ? nslab : gmax);
         return p;
     }
     // segments of exactly 1, 2, 4 or 8 whole tiles, enough of them to fill the chip: the pipelined kernel
@@ -521,32 +542,34 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     const SegPlan plan = plan_segmented(nseg, seglen, dtype, es, (uintptr_t)x, cus);
     const unsigned grid = plan.grid;
 
-    // ---- short power-of-two segments: one contiguous stream ---------------------------------------------
-    if (plan.kernel == REDUX_KERNEL_SHORT) {
+    // ---- short segments read as one contiguous stream: aligned powers of two, or ragged ----------------------
+    if (plan.kernel == REDUX_KERNEL_SHORT || plan.kernel == REDUX_KERNEL_RAGGED) {
+        const bool ragged = plan.kernel == REDUX_KERNEL_RAGGED;
         ShortArgs s;
-        s.x = (const u32x4 *)x;
+        s.x = (const unsigned char *)x;
         s.nseg = nseg;
-        s.nvec = (u64)nseg * plan.nvec;
         s.lg = 0;
         while ((1u << s.lg) < plan.nvec) ++s.lg;
+        s.nvec = (u64)nseg << s.lg;
+        s.seg_bytes = (u64)seglen * es;
         s.out = out;
         s.layout = (int)g_set.layout;
         // measured: refilling registers one by one hides the second MMA and the stores of segments up to
         // 256 B (and the classic family's conversions); longer segments run fastest as a plain loop
         // (binary32 excepted: it needs four MMAs per load)
         s.pipe = g_set.seg_short_pipe >= 0 ? (int)g_set.seg_short_pipe : (mfma && s.lg >= 5 && dtype != REDUX_F32 ? 0 : 1);
-        const bool wide = s.lg >= 5;       // 32 or 64 vectors per segment: eight loads share an accumulator
+        const bool wide = s.lg >= 5;       // 32 or 64 lanes per segment: eight loads share an accumulator
         with_short_family(dtype, [&](auto elem) {
             typedef decltype(elem) E;
-            if (mfma) {
-                if (wide) { if (nt) hipLaunchKernelGGL((sum_short_mfma_kernel<E, 8, true>), dim3(grid), dim3(kBlock), 0, st, s);
-                            else    hipLaunchKernelGGL((sum_short_mfma_kernel<E, 8, false>), dim3(grid), dim3(kBlock), 0, st, s); }
-                else      { if (nt) hipLaunchKernelGGL((sum_short_mfma_kernel<E, 4, true>), dim3(grid), dim3(kBlock), 0, st, s);
-                            else    hipLaunchKernelGGL((sum_short_mfma_kernel<E, 4, false>), dim3(grid), dim3(kBlock), 0, st, s); }
-            } else {
-                if (nt) hipLaunchKernelGGL((sum_short_classic_kernel<E, true>), dim3(grid), dim3(kBlock), 0, st, s);
-                else    hipLaunchKernelGGL((sum_short_classic_kernel<E, false>), dim3(grid), dim3(kBlock), 0, st, s);
-            }
+#define REDUX_SHORT_NT(KERNEL, ...) do { if (nt) hipLaunchKernelGGL((KERNEL<E, __VA_ARGS__ true, RR>), dim3(grid), dim3(kBlock), 0, st, s); \
+                                         else    hipLaunchKernelGGL((KERNEL<E, __VA_ARGS__ false, RR>), dim3(grid), dim3(kBlock), 0, st, s); } while (0)
+#define REDUX_SHORT_ALL() do { if (!mfma) REDUX_SHORT_NT(sum_short_classic_kernel, ); \
+                               else if (wide) REDUX_SHORT_NT(sum_short_mfma_kernel, 8, ); \
+                               else REDUX_SHORT_NT(sum_short_mfma_kernel, 4, ); } while (0)
+            if (ragged) { constexpr bool RR = true; REDUX_SHORT_ALL(); }
+            else        { constexpr bool RR = false; REDUX_SHORT_ALL(); }
+#undef REDUX_SHORT_ALL
+#undef REDUX_SHORT_NT
         });
         e = hipGetLastError();
         return e == hipSuccess ? REDUX_OK : hip_fail(e);

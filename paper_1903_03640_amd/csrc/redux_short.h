@@ -1,7 +1,6 @@
-// redux_short.h -- segmented sum of short power-of-two segments (16 B .. 1 KiB each), read as one
-// contiguous stream.
+// redux_short.h -- segmented sum of short segments (up to 1 KiB each), read as one contiguous stream.
 //
-// A segment here is 2^lg whole 16-byte vectors (lg = 0 .. 6) and the array starts on a 16-byte
+// Aligned form: a segment is 2^lg whole 16-byte vectors (lg = 0 .. 6) and the array starts on a 16-byte
 // boundary, so every wavefront-wide load (64 vectors, 1 KiB) holds whole segments and the grid can read
 // the array exactly like the flat sum does.  What changes is the constant operand of the two MMAs of
 // Section IV-A: instead of all ones they are 0/1 *selection* matrices, so one MMA pair yields many
@@ -18,29 +17,73 @@
 //
 // The classic family adds each vector inside its lane and stops the lane butterfly of Section III
 // after lg steps.
+//
+// Ragged form: any segment length up to 1008 bytes at any element alignment.  A group of 2^lg lanes still
+// owns one segment, but lane j of the group loads the j-th 16-byte aligned vector that overlaps the segment
+// and clears the bytes outside it (the zero padding of Section IV-A, applied per segment); vectors that do
+// not overlap it are not loaded.  Everything after the load is the aligned form.
+//
+// A zero in a selection matrix still multiplies its data: an infinity or NaN in one segment would turn
+// the other segments of its accumulator into NaN (0 x inf).  So whenever an accumulator yields a
+// non-finite result -- which every non-finite input forces in its own segment -- its loads are read again
+// and summed with the lane butterfly, which never mixes segments.
 #pragma once
 #include "redux_kernels.h"
 
 namespace redux {
 
 constexpr int kShortLoads = 8;                                   // 16-byte loads per lane per slab
-constexpr u64 kShortSlab = (u64)kBlock * kShortLoads;            // vectors per slab (32 KiB)
+constexpr u64 kShortSlab = (u64)kBlock * kShortLoads;            // (virtual) vectors per slab: 32 KiB when aligned
 
 struct ShortArgs {
-    const u32x4 *x;     // 16-byte aligned
+    const unsigned char *x;  // first element; aligned form: on a 16-byte boundary
     u64 nseg;
-    u64 nvec;           // nseg << lg
-    unsigned lg;        // log2(vectors per segment), 0 .. 6
+    u64 nvec;           // nseg << lg: lane slots, one 16-byte vector each
+    u64 seg_bytes;      // ragged form: bytes per segment
+    unsigned lg;        // log2(lanes per segment), 0 .. 6
     void *out;
     int layout;         // see slab_schedule
     int pipe;           // 0 = plain loop, 1 = refill each register as soon as it is consumed
 };
 
-// vector index, inside its slab, of the vector that load u of thread tid reads: every load of the block
-// covers 4 KiB contiguous, every wavefront 1 KiB of it
+// slot index, inside its slab, that load u of thread tid fills: every load of the block covers 256
+// consecutive slots (4 KiB contiguous when aligned), every wavefront 64 of them
 __device__ __forceinline__ unsigned short_index(int u, unsigned tid)
 {
     return (unsigned)u * kBlock + tid;
+}
+
+// all-ones in the low b bytes of a 128-bit word (b = 0 .. 16), as two 64-bit halves
+__device__ __forceinline__ void bytes_below(unsigned b, u64 *lo, u64 *hi)
+{
+    *lo = b >= 8u ? ~0ull : (1ull << (8u * b)) - 1ull;
+    *hi = b <= 8u ? 0ull : (b >= 16u ? ~0ull : (1ull << (8u * (b - 8u))) - 1ull);
+}
+
+// The vector of slot V (V < a.nvec).  Aligned form: vector V of the array.  Ragged form: slot V is lane
+// j = V mod 2^lg of segment V >> lg; it reads the j-th aligned vector overlapping that segment and keeps the
+// segment's bytes only.  An aligned vector that holds at least one byte of the array lies in the array's
+// pages, so the bytes read beyond either end of the array are mapped; they are cleared like all others.
+template <bool NT, bool RAGGED>
+__device__ __forceinline__ u32x4 short_fetch(const ShortArgs &a, u64 V)
+{
+    if (!RAGGED) return load16<NT>((const u32x4 *)a.x + V);
+    const u64 seg = V >> a.lg;
+    const unsigned j = (unsigned)V & ((1u << a.lg) - 1u);
+    const u64 first = (u64)(uintptr_t)a.x + seg * a.seg_bytes;       // address of the segment's first byte
+    const unsigned off = (unsigned)first & 15u;
+    const u64 va = (first - off) + 16ull * j;                        // this slot's aligned vector
+    // bytes [lo, hi) of the vector belong to the segment
+    const unsigned lo = j == 0 ? off : 0u;
+    const u64 end = (u64)off + a.seg_bytes;                          // segment end, in bytes from the first aligned vector
+    if (end <= 16ull * j) return u32x4{0u, 0u, 0u, 0u};              // the segment ends before this vector
+    const unsigned hi = end - 16ull * j >= 16ull ? 16u : (unsigned)(end - 16ull * j);
+    const u32x4 v = load16<NT>((const u32x4 *)va);
+    u64 hl, hh, ll, lh;
+    bytes_below(hi, &hl, &hh);
+    bytes_below(lo, &ll, &lh);
+    const u64 ml = hl & ~ll, mh = hh & ~lh;
+    return u32x4{v[0] & (unsigned)ml, v[1] & (unsigned)(ml >> 32), v[2] & (unsigned)mh, v[3] & (unsigned)(mh >> 32)};
 }
 
 // `count` (1, 2 or 4) consecutive results of one lane, as one store where alignment allows
@@ -97,6 +140,7 @@ __device__ __forceinline__ f32x4 mma1_select(u32x4 v, bool sel, f32x4 d)
 // per-segment result leaves.
 template <int KIND>
 struct ShortFloat {
+    static constexpr bool kCanBeNonFinite = true;
     typedef float Out;
     typedef f32x4 Acc;
     typedef float Lane;
@@ -116,6 +160,7 @@ struct ShortFloat {
 // int8: a vector sums to at most 16 x 128 and a segment to at most 64 times that, so the binary32
 // second MMA (and the int32 lane butterfly) are exact.
 struct ShortI8 {
+    static constexpr bool kCanBeNonFinite = false;
     typedef i64 Out;
     typedef i32x4 Acc;
     typedef int Lane;
@@ -139,23 +184,22 @@ struct ShortI8 {
 };
 
 // One whole slab into registers.
-template <bool NT>
+template <bool NT, bool RAGGED>
 __device__ __forceinline__ void short_load(u32x4 *dst, const ShortArgs &a, u64 slab, unsigned tid)
 {
-    const u32x4 *p = a.x + slab * kShortSlab;
 #pragma unroll
-    for (int u = 0; u < kShortLoads; ++u) dst[u] = load16<NT>(p + short_index(u, tid));
+    for (int u = 0; u < kShortLoads; ++u) dst[u] = short_fetch<NT, RAGGED>(a, slab * kShortSlab + short_index(u, tid));
 }
 
-// The slab that holds the end of the array; lanes past the end read zeros.
-template <bool NT>
+// The slab that holds the end of the array; slots past the end read zeros.
+template <bool NT, bool RAGGED>
 __device__ __forceinline__ void short_load_partial(u32x4 *dst, const ShortArgs &a, u64 slab, unsigned tid)
 {
 #pragma unroll
     for (int u = 0; u < kShortLoads; ++u) {
-        const u64 idx = slab * kShortSlab + short_index(u, tid);
+        const u64 V = slab * kShortSlab + short_index(u, tid);
         u32x4 v = {0u, 0u, 0u, 0u};
-        if (idx < a.nvec) v = load16<NT>(a.x + idx);
+        if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V);
         dst[u] = v;
     }
 }
@@ -165,35 +209,33 @@ __device__ __forceinline__ void short_load_partial(u32x4 *dst, const ShortArgs &
 // in flight while the MMAs (or the butterfly) and the stores run.  The block's last slab is peeled off, so that
 // no load in the loop is conditional and the wait in front of each use leaves exactly the seven newer loads
 // outstanding.  The slab that holds the ragged end of the array is done by one block afterwards.
-template <bool NT, class Work>
+template <bool NT, bool RAGGED, class Work>
 __device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, Work &&work)
 {
     const u64 nfull = a.nvec / kShortSlab;
     u64 s0, stride, count;
     slab_schedule(a.layout, nfull, gridDim.x, blockIdx.x, &s0, &stride, &count);
-    if (count && a.pipe == 0) {
+    if (count && (a.pipe == 0 || RAGGED)) {
+        // (ragged form: a load may be skipped, so the wait in front of a use cannot be counted out anyway)
         for (u64 k = 0; k < count; ++k) {
             u32x4 cur[kShortLoads];
-            short_load<NT>(cur, a, s0 + k * stride, tid);
+            short_load<NT, RAGGED>(cur, a, s0 + k * stride, tid);
             __builtin_amdgcn_sched_barrier(0);
             work(cur, s0 + k * stride, [](int) {});
         }
     } else if (count) {
         u32x4 cur[kShortLoads];
-        {   // issued strictly in the order they are consumed in: the waits in the loop count on it
-            const u32x4 *first = a.x + s0 * kShortSlab;
 #pragma unroll
-            for (int u = 0; u < kShortLoads; ++u) {
-                cur[u] = load16<NT>(first + short_index(u, tid));
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        for (int u = 0; u < kShortLoads; ++u) {      // issued strictly in the order they are consumed in: the waits count on it
+            cur[u] = short_fetch<NT, RAGGED>(a, s0 * kShortSlab + short_index(u, tid));
+            __builtin_amdgcn_sched_barrier(0);
         }
         u64 slab = s0;
         for (u64 k = 1; k < count; ++k, slab += stride) {
-            const u32x4 *next = a.x + (slab + stride) * kShortSlab;
+            const u64 next = (slab + stride) * kShortSlab;
             __builtin_amdgcn_sched_barrier(0);
             work(cur, slab, [&](int u) {
-                cur[u] = load16<NT>(next + short_index(u, tid));
+                cur[u] = short_fetch<NT, RAGGED>(a, next + short_index(u, tid));
                 __builtin_amdgcn_sched_barrier(0);                   // keep the refill right behind the use
             });
         }
@@ -202,14 +244,44 @@ __device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, W
     }
     if (nfull * kShortSlab < a.nvec && blockIdx.x == (unsigned)(nfull % gridDim.x)) {
         u32x4 last[kShortLoads];
-        short_load_partial<NT>(last, a, nfull, tid);
+        short_load_partial<NT, RAGGED>(last, a, nfull, tid);
         work(last, nfull, [](int) {});
     }
 }
 
+template <class T, int CTRL>
+__device__ __forceinline__ T dpp_add(T v)
+{
+    return v + __builtin_bit_cast(T, dpp_i32<CTRL>(__builtin_bit_cast(int, v)));
+}
+
+// The lane butterfly of Section III over the 2^lg lanes of a segment (lg is the same for every lane):
+// afterwards every lane of a segment holds the segment's sum.
+template <class Lane>
+__device__ __forceinline__ Lane short_butterfly(Lane s, unsigned lg)
+{
+    if (lg >= 1) s = dpp_add<Lane, kQuadXor1>(s);
+    if (lg >= 2) s = dpp_add<Lane, kQuadXor2>(s);
+    if (lg >= 3) s = dpp_add<Lane, kRowHalfMirror>(s);
+    if (lg >= 4) s = dpp_add<Lane, kRowMirror>(s);
+    if (lg >= 5) s = s + __builtin_bit_cast(Lane, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, s), kSwizzleXor16));
+    if (lg >= 6) s = __builtin_bit_cast(Lane, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 0)) +
+                     __builtin_bit_cast(Lane, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 32));
+    return s;
+}
+
+// one load of the classic family: the vector in v fills slot V
+template <class E>
+__device__ __forceinline__ void short_classic_one(const ShortArgs &a, u32x4 v, u64 V, unsigned lane)
+{
+    const typename E::Lane s = short_butterfly(E::lane_sum(v), a.lg);
+    const u64 seg = V >> a.lg;
+    if ((lane & ((1u << a.lg) - 1u)) == 0 && seg < a.nseg) ((typename E::Out *)a.out)[seg] = E::lane_out(s);
+}
+
 // LPA = loads that share one accumulator: 4 for segments up to sixteen vectors (four columns per load),
 // 8 for segments of 32 or 64 vectors (two columns or one column per load).
-template <class E, int LPA, bool NT>
+template <class E, int LPA, bool NT, bool RAGGED>
 __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
 {
     constexpr int U = kShortLoads;
@@ -230,14 +302,14 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
 #pragma unroll
     for (int r = 0; r < 4; ++r) srow[r] = (((4u * g + (unsigned)r) >> lgc) == (n & mask)) ? 1.0f : 0.0f;
     // after the second MMA this lane holds rows m = 4 g + r' of column n: the sums of segments m of
-    // the 64 / cpl vectors that start at vector col_off of load col_load
+    // the 64 / cpl slots that start at slot col_off of load col_load
     const bool col_used = n < (unsigned)LPA * cpl && 4u * g <= mask;
     const unsigned col_load = n / cpl;
     const unsigned col_off = (n % cpl) * (64u / cpl);
     const unsigned per_lane = mask >= 3u ? 4u : mask + 1u;        // results this lane writes per accumulator: 4, 2 or 1
     typename E::Out *out = (typename E::Out *)a.out;
 
-    short_stream<NT>(a, tid, [&](const u32x4 *cur, u64 slab, auto refill) {
+    short_stream<NT, RAGGED>(a, tid, [&](const u32x4 *cur, u64 slab, auto refill) {
 #pragma unroll
         for (int q = 0; q < NACC; ++q) {
             typename E::Acc d = E::zero();
@@ -249,6 +321,21 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
             f32x4 dp = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int r = 0; r < 4; ++r) dp = __builtin_amdgcn_mfma_f32_16x16x4f32(srow[r], E::fold_in(d, r), dp, 0, 0, 0);
+            if (E::kCanBeNonFinite) {
+                // finite - finite is 0; infinities and NaNs give NaN, which differs from itself
+                const f32x4 z = dp - dp;
+                const bool bad = (z[0] != 0.f) | (z[1] != 0.f) | (z[2] != 0.f) | (z[3] != 0.f);
+                if (__builtin_amdgcn_ballot_w64(bad) != 0) {       // the same for the whole wavefront
+#pragma unroll
+                    for (int t = 0; t < LPA; ++t) {
+                        const u64 V = slab * kShortSlab + short_index(q * LPA + t, tid);
+                        u32x4 v = {0u, 0u, 0u, 0u};
+                        if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V);
+                        short_classic_one<E>(a, v, V, lane);
+                    }
+                    continue;
+                }
+            }
             if (col_used) {
                 const u64 vb = slab * kShortSlab + short_index(q * LPA + (int)col_load, wave * 64u) + col_off;
                 const u64 seg0 = (vb >> lg) + 4u * g;
@@ -261,36 +348,16 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
     });
 }
 
-template <class T, int CTRL>
-__device__ __forceinline__ T dpp_add(T v)
-{
-    return v + __builtin_bit_cast(T, dpp_i32<CTRL>(__builtin_bit_cast(int, v)));
-}
-
-template <class E, bool NT>
+template <class E, bool NT, bool RAGGED>
 __global__ void __launch_bounds__(kBlock) sum_short_classic_kernel(ShortArgs a)
 {
-    typedef typename E::Lane Lane;
     const unsigned tid = threadIdx.x, lane = tid & 63u;
-    const unsigned lg = a.lg;
-    const bool writer = (lane & ((1u << lg) - 1u)) == 0;
-    typename E::Out *out = (typename E::Out *)a.out;
-
-    short_stream<NT>(a, tid, [&](const u32x4 *cur, u64 slab, auto refill) {
+    short_stream<NT, RAGGED>(a, tid, [&](const u32x4 *cur, u64 slab, auto refill) {
 #pragma unroll
         for (int u = 0; u < kShortLoads; ++u) {
-            Lane s = E::lane_sum(cur[u]);
+            const u32x4 v = cur[u];
             refill(u);
-            // butterfly over the 2^lg lanes of a segment; lg is the same for every lane
-            if (lg >= 1) s = dpp_add<Lane, kQuadXor1>(s);
-            if (lg >= 2) s = dpp_add<Lane, kQuadXor2>(s);
-            if (lg >= 3) s = dpp_add<Lane, kRowHalfMirror>(s);
-            if (lg >= 4) s = dpp_add<Lane, kRowMirror>(s);
-            if (lg >= 5) s = s + __builtin_bit_cast(Lane, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, s), kSwizzleXor16));
-            if (lg >= 6) s = __builtin_bit_cast(Lane, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 0)) +
-                             __builtin_bit_cast(Lane, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 32));
-            const u64 seg = (slab * kShortSlab + short_index(u, tid)) >> lg;
-            if (writer && seg < a.nseg) out[seg] = E::lane_out(s);
+            short_classic_one<E>(a, v, slab * kShortSlab + short_index(u, tid), lane);
         }
     });
 }

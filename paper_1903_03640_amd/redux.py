@@ -34,7 +34,7 @@ class Plan(ctypes.Structure):
                 ("vectors", ctypes.c_uint64)]
 
 
-KERNEL_FLAT, KERNEL_ROWS, KERNEL_WAVE, KERNEL_PIECES, KERNEL_TILES, KERNEL_BLOCK, KERNEL_SHORT = 0, 1, 2, 3, 4, 5, 6
+KERNEL_FLAT, KERNEL_ROWS, KERNEL_WAVE, KERNEL_PIECES, KERNEL_TILES, KERNEL_BLOCK, KERNEL_SHORT, KERNEL_RAGGED = 0, 1, 2, 3, 4, 5, 6, 7
 
 
 class ReduxError(RuntimeError):

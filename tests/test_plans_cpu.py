@@ -12,7 +12,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(redux.LIB_PATH), reason="libr
 
 ES = {redux.F16: 2, redux.I8: 1, redux.BF16: 2, redux.F32: 4, redux.F8E4M3: 1, redux.F8E5M2: 1}
 DTYPES = sorted(ES)
-PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short")
+PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short", "seg_ragged")
 
 
 @pytest.fixture(autouse=True)
@@ -89,8 +89,8 @@ def test_slab_schedule_is_balanced_and_die_blocked():
        dtype=st.sampled_from(DTYPES), aligned=st.booleans(), cus=st.sampled_from([1, 104, 256]),
        seg_parts=st.sampled_from([0, 0, 0, 2, 8, 64, 4096]), rows_max=st.sampled_from([64, 64, 0, 5]),
        seg_bpc=st.integers(0, 16), unroll=st.sampled_from([0, 1, 2, 4, 8]), block_bytes=st.sampled_from([32768, 32768, 0, 1000]),
-       seg_short=st.sampled_from([1, 1, 0]))
-def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll, block_bytes, seg_short):
+       seg_short=st.sampled_from([1, 1, 0]), seg_ragged=st.sampled_from([1, 1, 0]))
+def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll, block_bytes, seg_short, seg_ragged):
     es = ES[dtype]
     addr = 4096 if aligned else 4096 + es
     redux.set_param("seg_parts", seg_parts)
@@ -99,6 +99,7 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
     redux.set_param("unroll", unroll)
     redux.set_param("seg_block_bytes", block_bytes)
     redux.set_param("seg_short", seg_short)
+    redux.set_param("seg_ragged", seg_ragged)
     p = redux.plan_sum_segmented(nseg, seglen, dtype, addr, cus)
     assert 1 <= p.grid <= 16 * cus
     pow2_short = aligned and 16 <= seglen * es <= 1024 and (seglen * es) & (seglen * es - 1) == 0
@@ -106,6 +107,15 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
     if p.kernel == redux.KERNEL_SHORT:
         assert p.vectors == seglen * es // 16 and p.unroll == 8 and p.parts == 1
         assert p.grid <= max(1, -(-(nseg * p.vectors) // 2048))            # never more blocks than 32 KiB slabs
+    elif p.kernel == redux.KERNEL_RAGGED:
+        sb = seglen * es
+        assert seg_ragged and sb <= 1008 and p.unroll == 8 and p.parts == 1
+        lanes = p.vectors
+        assert lanes in (1, 2, 4, 8, 16, 32, 64)
+        # every placement of a segment fits its lane group: first byte at most 16 - es bytes into a vector
+        worst = (addr % 16 if sb % 16 == 0 else 16 - es)
+        assert lanes * 16 >= worst + sb and (lanes == 1 or (lanes // 2) * 16 < worst + sb)
+        assert p.grid <= max(1, -(-(nseg * lanes) // 2048))
     elif p.kernel == redux.KERNEL_ROWS:
         assert dtype in (redux.F16, redux.I8) and aligned and (seglen * es) % 16 == 0
         assert p.vectors == seglen * es // 16 and 1 <= p.vectors <= rows_max
@@ -126,6 +136,7 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
         assert p.grid <= nseg * p.parts
     else:
         assert p.unroll in (1, 2, 4, 8)
+        assert not (seg_ragged and seglen * es <= 1008)
         if p.kernel == redux.KERNEL_PIECES:
             assert p.parts > 1 and p.parts & (p.parts - 1) == 0
             assert nseg * p.parts <= 16384                      # piece totals fit the workspace
@@ -156,9 +167,19 @@ def test_segmented_plan_defaults_on_mi355x():
     redux.set_param("seg_short", 0)
     short = redux.plan_sum_segmented(1 << 22, 64, redux.F16, 0, 256)
     assert (short.kernel, short.vectors, short.unroll) == (redux.KERNEL_ROWS, 8, 2)
-    assert redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256).kernel == redux.KERNEL_WAVE     # rows: binary16 and int8 only
+    ragged = redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256)                                # rows: binary16 and int8 only
+    assert (ragged.kernel, ragged.vectors) == (redux.KERNEL_RAGGED, 8)
     redux.set_param("seg_short", 1)
-    assert redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256).kernel == redux.KERNEL_WAVE      # misaligned base
+    ragged = redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256)                                 # misaligned base: 9 vectors
+    assert (ragged.kernel, ragged.vectors, ragged.grid) == (redux.KERNEL_RAGGED, 16, 512)
+    ragged = redux.plan_sum_segmented(1 << 20, 100, redux.BF16, 0, 256)                               # 200 B anywhere: 14 vectors
+    assert (ragged.kernel, ragged.vectors) == (redux.KERNEL_RAGGED, 16)
+    assert redux.plan_sum_segmented(1 << 20, 3, redux.F8E4M3, 0, 256).vectors == 2                    # 3 B can straddle two vectors
+    assert redux.plan_sum_segmented(1 << 20, 252, redux.F32, 0, 256).vectors == 64                    # 1008 B: the longest
+    assert redux.plan_sum_segmented(1 << 20, 253, redux.F32, 0, 256).kernel == redux.KERNEL_WAVE
+    redux.set_param("seg_ragged", 0)
+    assert redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256).kernel == redux.KERNEL_WAVE
+    redux.set_param("seg_ragged", 1)
     long_ = redux.plan_sum_segmented(256, 1 << 20, redux.F16, 0, 256)
     assert (long_.kernel, long_.parts, long_.part_len, long_.unroll, long_.grid) == (redux.KERNEL_BLOCK, 2, 524288, 8, 256)
     assert redux.plan_sum_segmented(4096, 65536, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK      # 128 KiB each, no pieces
@@ -166,7 +187,8 @@ def test_segmented_plan_defaults_on_mi355x():
     long_ = redux.plan_sum_segmented(256, 1 << 20, redux.F16, 0, 256)
     assert (long_.kernel, long_.parts, long_.part_len) == (redux.KERNEL_PIECES, 8, 131072)
     redux.set_param("seg_block_bytes", 32768)
-    assert redux.plan_sum_segmented(1, 100, redux.I8, 0, 256).kernel == redux.KERNEL_WAVE
+    assert redux.plan_sum_segmented(1, 100, redux.I8, 0, 256).kernel == redux.KERNEL_RAGGED
+    assert redux.plan_sum_segmented(1, 2000, redux.I8, 0, 256).kernel == redux.KERNEL_WAVE
 
 
 def test_plan_argument_errors():
