@@ -356,8 +356,11 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         return p;
     }
     // short segments: sixteen per wavefront, one per row of the A operand
-    if ((dtype == REDUX_F16 || dtype == REDUX_I8) && g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 && x_addr % 16 == 0 &&
-        seg_bytes / 16 <= (u64)g_set.rows_max_vec) {
+    // (measured: where the lane groups of the ragged form below would be at least 25/32 full, that form is faster)
+    const auto ragged_lanes = [](u64 cover) { u64 l = 1; while (l < cover) l *= 2; return l; };
+    const bool rows_fit = (dtype == REDUX_F16 || dtype == REDUX_I8) && g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 &&
+                          x_addr % 16 == 0 && seg_bytes / 16 <= (u64)g_set.rows_max_vec;
+    if (rows_fit && !(g_set.seg_ragged && seg_bytes <= 1008 && seg_bytes / 16 * 32 >= 25 * ragged_lanes(seg_bytes / 16))) {
         p.kernel = REDUX_KERNEL_ROWS;
         p.nvec = (unsigned)(seg_bytes / 16);
         const unsigned steps = (p.nvec + 3) / 4;
@@ -378,13 +381,13 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         // x mod 16 if segments are whole vectors long)
         const u64 max_off = seg_bytes % 16 == 0 ? (u64)(x_addr % 16) : (u64)(16 - es);
         const u64 cover = (max_off + seg_bytes + 15) / 16;
-        unsigned lg = 0;
-        while ((1ull << lg) < cover) ++lg;
         p.kernel = REDUX_KERNEL_RAGGED;
-        p.nvec = 1u << lg;
+        p.nvec = (unsigned)ragged_lanes(cover);
         p.unroll = kShortLoads;
-        const u64 nslab = ((nseg << lg) + kShortSlab - 1) / kShortSlab;
-        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 2);
+        const u64 nslab = (nseg * p.nvec + kShortSlab - 1) / kShortSlab;
+        // measured: the address and mask arithmetic per load wants more wavefronts per compute unit than the aligned form
+        const long best_bpc = effective_variant(dtype) == REDUX_VARIANT_MFMA ? 6 : 8;
+        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : best_bpc);
         if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
         if (gmax < 1) gmax = 1;
         p.grid = (unsigned)(nslab < gmax ? nslab : gmax);
@@ -557,7 +560,9 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
         // measured: refilling registers one by one hides the second MMA and the stores of segments up to
         // 256 B (and the classic family's conversions); longer segments run fastest as a plain loop
         // (binary32 excepted: it needs four MMAs per load)
-        s.pipe = g_set.seg_short_pipe >= 0 ? (int)g_set.seg_short_pipe : (mfma && s.lg >= 5 && dtype != REDUX_F32 ? 0 : 1);
+        // The ragged form: refill with the MMA family, plain loop with the classic one.
+        const int best_pipe = ragged ? (mfma ? 1 : 0) : (mfma && s.lg >= 5 && dtype != REDUX_F32 ? 0 : 1);
+        s.pipe = g_set.seg_short_pipe >= 0 ? (int)g_set.seg_short_pipe : best_pipe;
         const bool wide = s.lg >= 5;       // 32 or 64 lanes per segment: eight loads share an accumulator
         with_short_family(dtype, [&](auto elem) {
             typedef decltype(elem) E;

@@ -20,8 +20,8 @@
 //
 // Ragged form: any segment length up to 1008 bytes at any element alignment.  A group of 2^lg lanes still
 // owns one segment, but lane j of the group loads the j-th 16-byte aligned vector that overlaps the segment
-// and clears the bytes outside it (the zero padding of Section IV-A, applied per segment); vectors that do
-// not overlap it are not loaded.  Everything after the load is the aligned form.
+// and clears the bytes outside it (the zero padding of Section IV-A, applied per segment).  Everything after
+// the load is the aligned form.
 //
 // A zero in a selection matrix still multiplies its data: an infinity or NaN in one segment would turn
 // the other segments of its accumulator into NaN (0 x inf).  So whenever an accumulator yields a
@@ -72,13 +72,15 @@ __device__ __forceinline__ u32x4 short_fetch(const ShortArgs &a, u64 V)
     const unsigned j = (unsigned)V & ((1u << a.lg) - 1u);
     const u64 first = (u64)(uintptr_t)a.x + seg * a.seg_bytes;       // address of the segment's first byte
     const unsigned off = (unsigned)first & 15u;
-    const u64 va = (first - off) + 16ull * j;                        // this slot's aligned vector
+    const unsigned end = off + (unsigned)a.seg_bytes;                // segment end, in bytes from its first aligned vector
+    const unsigned cover = (end + 15u) >> 4;                         // aligned vectors that overlap the segment (at least 1)
+    // Lanes past the last overlapping vector read that vector again (the same cache line as their neighbour: no
+    // extra traffic) and keep nothing of it, so that every lane issues its load and waits can be counted.
+    const unsigned jj = j < cover ? j : cover - 1u;
+    const u32x4 v = load16<NT>((const u32x4 *)((first - off) + 16ull * jj));
     // bytes [lo, hi) of the vector belong to the segment
     const unsigned lo = j == 0 ? off : 0u;
-    const u64 end = (u64)off + a.seg_bytes;                          // segment end, in bytes from the first aligned vector
-    if (end <= 16ull * j) return u32x4{0u, 0u, 0u, 0u};              // the segment ends before this vector
-    const unsigned hi = end - 16ull * j >= 16ull ? 16u : (unsigned)(end - 16ull * j);
-    const u32x4 v = load16<NT>((const u32x4 *)va);
+    const unsigned hi = j >= cover ? 0u : (end - 16u * j >= 16u ? 16u : end - 16u * j);
     u64 hl, hh, ll, lh;
     bytes_below(hi, &hl, &hh);
     bytes_below(lo, &ll, &lh);
@@ -215,8 +217,7 @@ __device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, W
     const u64 nfull = a.nvec / kShortSlab;
     u64 s0, stride, count;
     slab_schedule(a.layout, nfull, gridDim.x, blockIdx.x, &s0, &stride, &count);
-    if (count && (a.pipe == 0 || RAGGED)) {
-        // (ragged form: a load may be skipped, so the wait in front of a use cannot be counted out anyway)
+    if (count && a.pipe == 0) {
         for (u64 k = 0; k < count; ++k) {
             u32x4 cur[kShortLoads];
             short_load<NT, RAGGED>(cur, a, s0 + k * stride, tid);

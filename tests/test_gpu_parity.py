@@ -45,7 +45,7 @@ def default_params():
     for name, val in (("unroll", 0), ("nontemporal", 1), ("max_chain", 256),
                       ("max_grid", 16384), ("blocks_per_cu", DEFAULTS["blocks_per_cu"]),
                       ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
-                      ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("seg_tiles", 1), ("seg_short", 1), ("seg_block_bytes", 32768), ("lit_unroll", 0),
+                      ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("seg_tiles", 1), ("seg_short", 1), ("seg_ragged", 1), ("seg_short_pipe", -1), ("seg_block_bytes", 32768), ("lit_unroll", 0),
                       ("lit_blocks_per_cu", 0), ("lit_m", 16)):
         redux.set_param(name, val)
     redux.set_variant("auto")
@@ -359,7 +359,8 @@ def test_segmented_params(dev, variant):
 @pytest.mark.parametrize("seglen", [8, 16, 24, 32, 40, 64, 72, 128, 248, 256, 504, 512])
 def test_segmented_short_rows_f16(dev, variant, seglen):
     redux.set_variant(variant)
-    redux.set_param("seg_short", 0)         # power-of-two sizes too through the row-per-segment kernel
+    redux.set_param("seg_short", 0)         # every size through the row-per-segment kernel
+    redux.set_param("seg_ragged", 0)
     for nseg in (1, 15, 16, 17, 100, 4097, 70000):
         x = workloads.normal_f16(seglen + nseg, nseg * seglen)
         xd = to_dev(x, dev)
@@ -378,6 +379,7 @@ def test_segmented_short_rows_f16(dev, variant, seglen):
 def test_segmented_short_rows_i8(dev, variant, seglen):
     redux.set_variant(variant)
     redux.set_param("seg_short", 0)
+    redux.set_param("seg_ragged", 0)
     for nseg in (1, 15, 16, 17, 100, 4097, 70000):
         x = workloads.uniform_i8(seglen + nseg, nseg * seglen)
         want, _ = oracle.sum_segmented_i8(x, nseg, seglen)
