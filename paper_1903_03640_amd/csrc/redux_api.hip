@@ -442,11 +442,23 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         p.parts = parts;
         p.part_len = ((seglen + parts - 1) / parts + 511) / 512 * 512;
     }
-    // loads in flight per lane x resident blocks per compute unit = 8
-    const u64 vec_per_piece = p.part_len * es / 16;
+    // Measured on MI355X by piece size (aligned vectors a piece can overlap): up to 2 KiB two loads per lane take the
+    // whole piece at once; up to 5 KiB one load per lane and as many wavefronts as fit hide the per-segment fold
+    // best; longer pieces stream with two, then four loads in flight per lane.
+    const u64 piece_bytes = p.part_len * es;
+    const u64 cover = (piece_bytes + ((x_addr % 16 == 0 && seg_bytes % 16 == 0) ? 0 : 16 - es) + 15) / 16;
     p.unroll = (int)g_set.unroll;
-    if (p.unroll == 0) p.unroll = vec_per_piece >= 256 ? 4 : vec_per_piece >= 128 ? 2 : 1;
-    const long bpc = g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 8 / p.unroll;
+    long best_bpc = 0;
+    if (p.unroll == 0) {
+        if (cover <= 64)       { p.unroll = 1; best_bpc = 16; }
+        else if (cover <= 128) { p.unroll = 2; best_bpc = 8; }
+        else if (cover <= 320) { p.unroll = 1; best_bpc = 16; }
+        else if (cover <= 640) { p.unroll = 2; best_bpc = 4; }
+        else                   { p.unroll = 4; best_bpc = 2; }
+    } else {
+        best_bpc = 8 / p.unroll;
+    }
+    const long bpc = g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : best_bpc;
     u64 blocks_needed = (nseg * p.parts + kWaves - 1) / kWaves;
     u64 gmax = (u64)cus * (u64)bpc;
     if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;

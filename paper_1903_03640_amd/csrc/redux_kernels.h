@@ -574,6 +574,28 @@ struct SegArgs {
     u64 *partials;
 };
 
+// all-ones in the low b bytes of a 128-bit word (b = 0 .. 16), as two 64-bit halves
+__device__ __forceinline__ void bytes_below(unsigned b, u64 *lo, u64 *hi)
+{
+    *lo = b >= 8u ? ~0ull : (1ull << (8u * b)) - 1ull;
+    *hi = b <= 8u ? 0ull : (b >= 16u ? ~0ull : (1ull << (8u * (b - 8u))) - 1ull);
+}
+
+// bytes [lo, hi) of a vector, zeros elsewhere (0 <= lo, hi <= 16; nothing is kept if hi <= lo)
+__device__ __forceinline__ u32x4 keep_bytes(u32x4 v, unsigned lo, unsigned hi)
+{
+    u64 hl, hh, ll, lh;
+    bytes_below(hi, &hl, &hh);
+    bytes_below(lo, &ll, &lh);
+    const u64 ml = hl & ~ll, mh = hh & ~lh;
+    return u32x4{v[0] & (unsigned)ml, v[1] & (unsigned)(ml >> 32), v[2] & (unsigned)mh, v[3] & (unsigned)(mh >> 32)};
+}
+
+// The wavefront reads the 16-byte aligned vectors that overlap its segment (or piece), 64 x U at a time, and clears
+// the bytes of the first and the last one that lie outside it: the zero padding of Section IV-A.  Lanes past the
+// last vector read that vector again (one cache line for all of them) and keep nothing: a load under a branch would
+// make the wait in front of the MMAs cover every load in flight.  An aligned vector that holds a byte of the array
+// lies in the array's pages, so what is read beyond either end is mapped memory; it is cleared like the rest.
 template <class F, int U, bool NT>
 __global__ void __launch_bounds__(kBlock) sum_segmented_kernel(SegArgs a)
 {
@@ -585,34 +607,46 @@ __global__ void __launch_bounds__(kBlock) sum_segmented_kernel(SegArgs a)
     const u64 npieces = a.nseg * a.parts;
 
     for (u64 piece = wave_global; piece < npieces; piece += nwaves) {
-        const u64 seg = piece / a.parts, part = piece % a.parts;
+        // (a 64-bit division costs more than the rest of a short segment: only cut segments pay for it)
+        const u64 seg = a.parts == 1 ? piece : piece / a.parts, part = a.parts == 1 ? 0 : piece % a.parts;
         const u64 first = part * a.part_len;
         const u64 len = first < a.seglen ? (a.seglen - first < a.part_len ? a.seglen - first : a.part_len) : 0;
-        const Run run = make_run<F::kElemSize>(a.x + (seg * a.seglen + first) * F::kElemSize, len);
         typename F::Acc acc;
         F::clear(acc);
         Total total = 0;
-        unsigned chain = 0;
-        u64 v0 = 0;
-        for (; v0 + kChunk <= run.nvec; v0 += kChunk) {
-            u32x4 cur[U];
+        if (len) {
+            const u64 addr = (u64)(uintptr_t)a.x + (seg * a.seglen + first) * F::kElemSize;
+            const unsigned off = (unsigned)addr & 15u;
+            const u32x4 *base = (const u32x4 *)(addr - off);
+            const u64 end = off + len * F::kElemSize;          // end of the piece, in bytes from its first aligned vector
+            const u64 cover = (end + 15) >> 4;                 // aligned vectors that overlap the piece
+            unsigned chain = 0;
+            for (u64 v0 = 0; v0 < cover; v0 += kChunk) {
+                u32x4 cur[U];
+                if (v0 != 0 && v0 + kChunk < cover) {          // neither end is in this chunk (the same for every lane)
 #pragma unroll
-            for (int u = 0; u < U; ++u) cur[u] = load16<NT>(run.body + v0 + (u64)u * 64 + lane);
-            __builtin_amdgcn_sched_barrier(0);     // all loads of the chunk in flight before the first MMA waits
+                    for (int u = 0; u < U; ++u) cur[u] = load16<NT>(base + v0 + (u64)u * 64 + lane);
+                    __builtin_amdgcn_sched_barrier(0);         // all loads of the chunk in flight before the first MMA waits
+                } else {
 #pragma unroll
-            for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
-            if (++chain >= a.max_chain) { total += F::fold(acc); chain = 0; }
-        }
-        if (v0 < run.nvec) {
+                    for (int u = 0; u < U; ++u) {
+                        const u64 idx = v0 + (u64)u * 64 + lane;
+                        cur[u] = load16<NT>(base + (idx < cover ? idx : cover - 1));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                u64 idx = v0 + (u64)u * 64 + lane;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (idx < run.nvec) v = load16<NT>(run.body + idx);
-                F::consume(acc, u, v);
+                    for (int u = 0; u < U; ++u) {
+                        const u64 idx = v0 + (u64)u * 64 + lane;
+                        const unsigned lo = idx == 0 ? off : 0u;
+                        const unsigned hi = idx >= cover ? 0u : (end - 16 * idx >= 16 ? 16u : (unsigned)(end - 16 * idx));
+                        cur[u] = keep_bytes(cur[u], lo, hi);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
+                if (++chain >= a.max_chain) { total += F::fold(acc); chain = 0; }
             }
         }
-        if (run.nhead | run.ntail) F::consume(acc, 0, edge_vector<F>(run, (int)lane));
         total += F::fold(acc);
         if (lane == 0) {
             if (a.parts == 1) ((typename F::Out *)a.out)[seg] = F::to_out(total);

@@ -53,13 +53,6 @@ __device__ __forceinline__ unsigned short_index(int u, unsigned tid)
     return (unsigned)u * kBlock + tid;
 }
 
-// all-ones in the low b bytes of a 128-bit word (b = 0 .. 16), as two 64-bit halves
-__device__ __forceinline__ void bytes_below(unsigned b, u64 *lo, u64 *hi)
-{
-    *lo = b >= 8u ? ~0ull : (1ull << (8u * b)) - 1ull;
-    *hi = b <= 8u ? 0ull : (b >= 16u ? ~0ull : (1ull << (8u * (b - 8u))) - 1ull);
-}
-
 // The vector of slot V (V < a.nvec).  Aligned form: vector V of the array.  Ragged form: slot V is lane
 // j = V mod 2^lg of segment V >> lg; it reads the j-th aligned vector overlapping that segment and keeps the
 // segment's bytes only.  An aligned vector that holds at least one byte of the array lies in the array's
@@ -81,11 +74,7 @@ __device__ __forceinline__ u32x4 short_fetch(const ShortArgs &a, u64 V)
     // bytes [lo, hi) of the vector belong to the segment
     const unsigned lo = j == 0 ? off : 0u;
     const unsigned hi = j >= cover ? 0u : (end - 16u * j >= 16u ? 16u : end - 16u * j);
-    u64 hl, hh, ll, lh;
-    bytes_below(hi, &hl, &hh);
-    bytes_below(lo, &ll, &lh);
-    const u64 ml = hl & ~ll, mh = hh & ~lh;
-    return u32x4{v[0] & (unsigned)ml, v[1] & (unsigned)(ml >> 32), v[2] & (unsigned)mh, v[3] & (unsigned)(mh >> 32)};
+    return keep_bytes(v, lo, hi);
 }
 
 // `count` (1, 2 or 4) consecutive results of one lane, as one store where alignment allows

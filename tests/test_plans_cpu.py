@@ -156,7 +156,7 @@ def test_segmented_plan_defaults_on_mi355x():
     assert redux.plan_sum_segmented(65536, 1024, redux.F16, 0, 256).grid == 768                 # 2 KiB: three blocks per CU
     redux.set_param("seg_tiles", 0)
     c5 = redux.plan_sum_segmented(65536, 4096, redux.F16, 0, 256)
-    assert (c5.kernel, c5.unroll, c5.grid, c5.parts) == (redux.KERNEL_WAVE, 4, 512, 1)
+    assert (c5.kernel, c5.unroll, c5.grid, c5.parts) == (redux.KERNEL_WAVE, 2, 1024, 1)           # 512 vectors: two loads per lane, four blocks per CU
     redux.set_param("seg_tiles", 1)
     assert redux.plan_sum_segmented(1023, 4096, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE    # too few segments
     assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE
