@@ -207,14 +207,15 @@ int redux_get_variant(void);
  *   "max_grid"          1..16384 upper limit on the number of blocks (default 16384)
  *   "unroll"            0,1,2,4,8   16-byte loads in flight per lane; 0 = chosen from the size (default 0)
  *   "nontemporal"       0/1     use non-temporal (streaming) loads (default 1)
- *   "rows_max_vec"      0..64   segmented sum: segments of at most this many 16-byte vectors (and 16-byte
- *                               aligned) take the sixteen-segments-per-wavefront kernel; 0 = never (default 64)
+ *   "rows_max_vec"      0..64   segmented sum, binary16 and int8, only where "seg_short" / "seg_ragged" do not apply:
+ *                               segments of at most this many 16-byte vectors (and 16-byte aligned) take the
+ *                               sixteen-segments-per-wavefront kernel; 0 = never (default 64)
  *   "seg_block_bytes"   0..2^40 segmented sum: segments of at least this many bytes take one 256-thread block
  *                               each (or one per piece) and are streamed like the flat sum; 0 = never (default 32768)
  *   "seg_short"         0/1     segmented sum: 16-byte aligned segments of a power-of-two size from 16 to 1024
  *                               bytes take the contiguous-stream kernel (default 1)
  *   "seg_ragged"        0/1     segmented sum: every other segment of up to 1008 bytes takes that kernel's ragged form
- *                               (after "rows_max_vec" has had its pick) (default 1)
+ *                               (default 1)
  *   "seg_short_pipe"    -1,0,1  that kernel: 1 = every register is reloaded from the block's next 32 KiB as soon as it has
  *                               been consumed, 0 = plain load-then-work loop, -1 = the measured best for the shape (default -1)
  *   "seg_tiles"         0/1     segmented sum: 16-byte aligned segments of exactly 1, 2, 4 or 8 KiB, at least

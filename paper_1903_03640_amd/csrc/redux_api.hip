@@ -356,11 +356,11 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         return p;
     }
     // short segments: sixteen per wavefront, one per row of the A operand
-    // (measured: where the lane groups of the ragged form below would be at least 25/32 full, that form is faster)
+    // (only when the ragged form below is switched off: measured, that form is as fast or faster at every size)
     const auto ragged_lanes = [](u64 cover) { u64 l = 1; while (l < cover) l *= 2; return l; };
-    const bool rows_fit = (dtype == REDUX_F16 || dtype == REDUX_I8) && g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 &&
-                          x_addr % 16 == 0 && seg_bytes / 16 <= (u64)g_set.rows_max_vec;
-    if (rows_fit && !(g_set.seg_ragged && seg_bytes <= 1008 && seg_bytes / 16 * 32 >= 25 * ragged_lanes(seg_bytes / 16))) {
+    const bool ragged_fit = g_set.seg_ragged && seg_bytes <= 1008 && nseg <= ((u64)1 << 56);
+    if (!ragged_fit && (dtype == REDUX_F16 || dtype == REDUX_I8) && g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 &&
+        x_addr % 16 == 0 && seg_bytes / 16 <= (u64)g_set.rows_max_vec) {
         p.kernel = REDUX_KERNEL_ROWS;
         p.nvec = (unsigned)(seg_bytes / 16);
         const unsigned steps = (p.nvec + 3) / 4;
@@ -376,7 +376,7 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
     }
     // any other segment of up to 1008 bytes: the same contiguous stream, each group of 2^lg lanes reading the aligned
     // vectors that overlap its segment and clearing the bytes outside it
-    if (g_set.seg_ragged && seg_bytes <= 1008 && nseg <= ((u64)1 << 56)) {
+    if (ragged_fit) {
         // most vectors a segment can touch: its first byte sits at most 16 - es bytes into a vector (at exactly
         // x mod 16 if segments are whole vectors long)
         const u64 max_off = seg_bytes % 16 == 0 ? (u64)(x_addr % 16) : (u64)(16 - es);
@@ -572,8 +572,8 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
         // measured: refilling registers one by one hides the second MMA and the stores of segments up to
         // 256 B (and the classic family's conversions); longer segments run fastest as a plain loop
         // (binary32 excepted: it needs four MMAs per load)
-        // The ragged form: refill with the MMA family, plain loop with the classic one.
-        const int best_pipe = ragged ? (mfma ? 1 : 0) : (mfma && s.lg >= 5 && dtype != REDUX_F32 ? 0 : 1);
+        // The ragged form: always refill.
+        const int best_pipe = ragged ? 1 : (mfma && s.lg >= 5 && dtype != REDUX_F32 ? 0 : 1);
         s.pipe = g_set.seg_short_pipe >= 0 ? (int)g_set.seg_short_pipe : best_pipe;
         const bool wide = s.lg >= 5;       // 32 or 64 lanes per segment: eight loads share an accumulator
         with_short_family(dtype, [&](auto elem) {

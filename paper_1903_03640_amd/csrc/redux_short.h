@@ -57,10 +57,12 @@ __device__ __forceinline__ unsigned short_index(int u, unsigned tid)
 // j = V mod 2^lg of segment V >> lg; it reads the j-th aligned vector overlapping that segment and keeps the
 // segment's bytes only.  An aligned vector that holds at least one byte of the array lies in the array's
 // pages, so the bytes read beyond either end of the array are mapped; they are cleared like all others.
+// Returns the vector as loaded and, in *m, which entry of the byte-mask table clears what is not the segment's:
+// the AND is left to the consumer, so that the load can stay in flight.
 template <bool NT, bool RAGGED>
-__device__ __forceinline__ u32x4 short_fetch(const ShortArgs &a, u64 V)
+__device__ __forceinline__ u32x4 short_fetch(const ShortArgs &a, u64 V, unsigned *m)
 {
-    if (!RAGGED) return load16<NT>((const u32x4 *)a.x + V);
+    if (!RAGGED) { *m = 0; return load16<NT>((const u32x4 *)a.x + V); }
     const u64 seg = V >> a.lg;
     const unsigned j = (unsigned)V & ((1u << a.lg) - 1u);
     const u64 first = (u64)(uintptr_t)a.x + seg * a.seg_bytes;       // address of the segment's first byte
@@ -74,7 +76,8 @@ __device__ __forceinline__ u32x4 short_fetch(const ShortArgs &a, u64 V)
     // bytes [lo, hi) of the vector belong to the segment
     const unsigned lo = j == 0 ? off : 0u;
     const unsigned hi = j >= cover ? 0u : (end - 16u * j >= 16u ? 16u : end - 16u * j);
-    return keep_bytes(v, lo, hi);
+    *m = lo * 17u + hi;
+    return v;
 }
 
 // `count` (1, 2 or 4) consecutive results of one lane, as one store where alignment allows
@@ -176,29 +179,30 @@ struct ShortI8 {
 
 // One whole slab into registers.
 template <bool NT, bool RAGGED>
-__device__ __forceinline__ void short_load(u32x4 *dst, const ShortArgs &a, u64 slab, unsigned tid)
+__device__ __forceinline__ void short_load(u32x4 *dst, unsigned *m, const ShortArgs &a, u64 slab, unsigned tid)
 {
 #pragma unroll
-    for (int u = 0; u < kShortLoads; ++u) dst[u] = short_fetch<NT, RAGGED>(a, slab * kShortSlab + short_index(u, tid));
+    for (int u = 0; u < kShortLoads; ++u) dst[u] = short_fetch<NT, RAGGED>(a, slab * kShortSlab + short_index(u, tid), &m[u]);
 }
 
 // The slab that holds the end of the array; slots past the end read zeros.
 template <bool NT, bool RAGGED>
-__device__ __forceinline__ void short_load_partial(u32x4 *dst, const ShortArgs &a, u64 slab, unsigned tid)
+__device__ __forceinline__ void short_load_partial(u32x4 *dst, unsigned *m, const ShortArgs &a, u64 slab, unsigned tid)
 {
 #pragma unroll
     for (int u = 0; u < kShortLoads; ++u) {
         const u64 V = slab * kShortSlab + short_index(u, tid);
         u32x4 v = {0u, 0u, 0u, 0u};
-        if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V);
+        m[u] = 0;                                                    // (entry 0 keeps nothing)
+        if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V, &m[u]);
         dst[u] = v;
     }
 }
 
-// `work(cur, slab, refill)` does everything for one slab held in `cur` and calls refill(u) as soon as it has
-// consumed cur[u]: the register is then reloaded with the same block's next slab, so eight loads per lane stay
-// in flight while the MMAs (or the butterfly) and the stores run.  The block's last slab is peeled off, so that
-// no load in the loop is conditional and the wait in front of each use leaves exactly the seven newer loads
+// `work(cur, m, slab, refill)` does everything for one slab held in `cur` (with mask entries m) and calls refill(u) as
+// soon as it has consumed cur[u]: the register is then reloaded with the same block's next slab, so eight loads per
+// lane stay in flight while the MMAs (or the butterfly) and the stores run.  The block's last slab is peeled off, so
+// that no load in the loop is conditional and the wait in front of each use leaves exactly the seven newer loads
 // outstanding.  The slab that holds the ragged end of the array is done by one block afterwards.
 template <bool NT, bool RAGGED, class Work>
 __device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, Work &&work)
@@ -209,33 +213,36 @@ __device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, W
     if (count && a.pipe == 0) {
         for (u64 k = 0; k < count; ++k) {
             u32x4 cur[kShortLoads];
-            short_load<NT, RAGGED>(cur, a, s0 + k * stride, tid);
+            unsigned m[kShortLoads];
+            short_load<NT, RAGGED>(cur, m, a, s0 + k * stride, tid);
             __builtin_amdgcn_sched_barrier(0);
-            work(cur, s0 + k * stride, [](int) {});
+            work(cur, m, s0 + k * stride, [](int) {});
         }
     } else if (count) {
         u32x4 cur[kShortLoads];
+        unsigned m[kShortLoads];
 #pragma unroll
         for (int u = 0; u < kShortLoads; ++u) {      // issued strictly in the order they are consumed in: the waits count on it
-            cur[u] = short_fetch<NT, RAGGED>(a, s0 * kShortSlab + short_index(u, tid));
+            cur[u] = short_fetch<NT, RAGGED>(a, s0 * kShortSlab + short_index(u, tid), &m[u]);
             __builtin_amdgcn_sched_barrier(0);
         }
         u64 slab = s0;
         for (u64 k = 1; k < count; ++k, slab += stride) {
             const u64 next = (slab + stride) * kShortSlab;
             __builtin_amdgcn_sched_barrier(0);
-            work(cur, slab, [&](int u) {
-                cur[u] = short_fetch<NT, RAGGED>(a, next + short_index(u, tid));
+            work(cur, m, slab, [&](int u) {
+                cur[u] = short_fetch<NT, RAGGED>(a, next + short_index(u, tid), &m[u]);
                 __builtin_amdgcn_sched_barrier(0);                   // keep the refill right behind the use
             });
         }
         __builtin_amdgcn_sched_barrier(0);
-        work(cur, slab, [](int) {});
+        work(cur, m, slab, [](int) {});
     }
     if (nfull * kShortSlab < a.nvec && blockIdx.x == (unsigned)(nfull % gridDim.x)) {
         u32x4 last[kShortLoads];
-        short_load_partial<NT, RAGGED>(last, a, nfull, tid);
-        work(last, nfull, [](int) {});
+        unsigned m[kShortLoads];
+        short_load_partial<NT, RAGGED>(last, m, a, nfull, tid);
+        work(last, m, nfull, [](int) {});
     }
 }
 
@@ -277,6 +284,8 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
     constexpr int U = kShortLoads;
     constexpr int NACC = U / LPA;
     const unsigned tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    __shared__ u32x4 masks[RAGGED ? kByteMasks : 1];
+    if (RAGGED) fill_byte_masks(masks);
     const unsigned g = lane >> 4, n = lane & 15u;
     const unsigned lg = a.lg;
     const unsigned cpl = LPA == 4 ? 4u : (lg == 5 ? 2u : 1u);      // columns per load
@@ -299,13 +308,14 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
     const unsigned per_lane = mask >= 3u ? 4u : mask + 1u;        // results this lane writes per accumulator: 4, 2 or 1
     typename E::Out *out = (typename E::Out *)a.out;
 
-    short_stream<NT, RAGGED>(a, tid, [&](const u32x4 *cur, u64 slab, auto refill) {
+    short_stream<NT, RAGGED>(a, tid, [&](const u32x4 *cur, const unsigned *m, u64 slab, auto refill) {
 #pragma unroll
         for (int q = 0; q < NACC; ++q) {
             typename E::Acc d = E::zero();
 #pragma unroll
             for (int t = 0; t < LPA; ++t) {
-                d = E::mma1(cur[q * LPA + t], sel[t], d);
+                const u32x4 v = RAGGED ? (cur[q * LPA + t] & masks[m[q * LPA + t]]) : cur[q * LPA + t];
+                d = E::mma1(v, sel[t], d);
                 refill(q * LPA + t);
             }
             f32x4 dp = {0.f, 0.f, 0.f, 0.f};
@@ -320,7 +330,9 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
                     for (int t = 0; t < LPA; ++t) {
                         const u64 V = slab * kShortSlab + short_index(q * LPA + t, tid);
                         u32x4 v = {0u, 0u, 0u, 0u};
-                        if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V);
+                        unsigned mv = 0;
+                        if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V, &mv);
+                        if (RAGGED) v = v & masks[mv];
                         short_classic_one<E>(a, v, V, lane);
                     }
                     continue;
@@ -342,10 +354,12 @@ template <class E, bool NT, bool RAGGED>
 __global__ void __launch_bounds__(kBlock) sum_short_classic_kernel(ShortArgs a)
 {
     const unsigned tid = threadIdx.x, lane = tid & 63u;
-    short_stream<NT, RAGGED>(a, tid, [&](const u32x4 *cur, u64 slab, auto refill) {
+    __shared__ u32x4 masks[RAGGED ? kByteMasks : 1];
+    if (RAGGED) fill_byte_masks(masks);
+    short_stream<NT, RAGGED>(a, tid, [&](const u32x4 *cur, const unsigned *m, u64 slab, auto refill) {
 #pragma unroll
         for (int u = 0; u < kShortLoads; ++u) {
-            const u32x4 v = cur[u];
+            const u32x4 v = RAGGED ? (cur[u] & masks[m[u]]) : cur[u];
             refill(u);
             short_classic_one<E>(a, v, slab * kShortSlab + short_index(u, tid), lane);
         }

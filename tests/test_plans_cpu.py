@@ -118,9 +118,7 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
         assert p.grid <= max(1, -(-(nseg * lanes) // 2048))
     elif p.kernel == redux.KERNEL_ROWS:
         assert dtype in (redux.F16, redux.I8) and aligned and (seglen * es) % 16 == 0
-        nv = seglen * es // 16
-        lanes = 1 << (nv - 1).bit_length()
-        assert not (seg_ragged and nv * 32 >= 25 * lanes and seglen * es <= 1008)      # fuller lane groups go to the ragged form
+        assert not (seg_ragged and seglen * es <= 1008)              # only where the ragged form is off (or does not reach)
         assert p.vectors == seglen * es // 16 and 1 <= p.vectors <= rows_max
         assert p.unroll in (1, 2, 4, 8) and (p.vectors <= 4 * p.unroll or p.unroll == 8)
         waves = p.grid * 4
@@ -165,10 +163,12 @@ def test_segmented_plan_defaults_on_mi355x():
     assert (short.kernel, short.vectors, short.unroll, short.grid) == (redux.KERNEL_SHORT, 8, 8, 256)   # 128 B: contiguous stream
     assert redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256).kernel == redux.KERNEL_SHORT     # every dtype
     assert redux.plan_sum_segmented(100, 64, redux.F16, 0, 256).grid == 1                             # 12.5 KiB: one slab
+    rag = redux.plan_sum_segmented(1 << 22, 72, redux.F16, 0, 256)
+    assert (rag.kernel, rag.vectors) == (redux.KERNEL_RAGGED, 16)                                     # 144 B: 9 of 16 lanes busy
+    redux.set_param("seg_ragged", 0)
     rows = redux.plan_sum_segmented(1 << 22, 72, redux.F16, 0, 256)
-    assert (rows.kernel, rows.vectors, rows.unroll) == (redux.KERNEL_ROWS, 9, 4)                      # 144 B: not a power of two
-    full = redux.plan_sum_segmented(1 << 22, 120, redux.F16, 0, 256)                                  # 240 B: 15 of 16 lanes busy
-    assert (full.kernel, full.vectors) == (redux.KERNEL_RAGGED, 16)
+    assert (rows.kernel, rows.vectors, rows.unroll) == (redux.KERNEL_ROWS, 9, 4)
+    redux.set_param("seg_ragged", 1)
     redux.set_param("seg_short", 0)
     for dt in (redux.F16, redux.BF16):
         ragged = redux.plan_sum_segmented(1 << 22, 64, dt, 0, 256)                                    # full lane groups: the ragged form
