@@ -5,8 +5,8 @@ over a seeded synthetic array already resident in HBM.
 Default workload: C3, the n = 2^30 + 12345 binary16 sum the headline metric is quoted on.
 Prints ONE JSON line (see the keys below).  Usage:
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1..C5] [--variant auto|mfma|classic]
-                    [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1..C5] [--variant auto|mfma|classic|multipass]
+                    [--seglen L] [--set NAME=VALUE] [--no-cpu-baseline]
 
 `value`            whole-job throughput in GB/s: algorithmic bytes (2 B per binary16 element, 1 B per
                    int8 element) x K / wall time of K back-to-back calls, bracketed by device
@@ -36,7 +36,7 @@ HBM_PEAK_GBPS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     ("C3", "mfma"): 2147587147, ("C3", "classic"): 2147589909,     # profiles/redux_sum_f16_C3.md
     ("C4", "mfma"): 1073831055, ("C4", "classic"): 1073839173,     # profiles/redux_sum_i8_C4.md
-    ("C5", "mfma"): 537417867, ("C5", "classic"): 537428045,       # profiles/redux_sum_segmented_f16_C5.md
+    ("C5", "mfma"): 537411811, ("C5", "classic"): 537421025,       # profiles/redux_sum_segmented_f16_C5.md
 }
 
 
@@ -48,6 +48,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--variant", default="auto", choices=["auto", "mfma", "classic", "multipass"],
                     help="kernel family of redux_sum; 'multipass' times redux_sum_multipass (the level-by-level form) instead")
+    ap.add_argument("--seglen", type=int, default=0, metavar="L",
+                    help="with --workload C5: cut the same array into segments of L elements instead of 4096 "
+                         "(to time and profile the short- and ragged-segment kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the reduction, run --steps plain copies of MIB MiB (known traffic) "
@@ -86,6 +89,13 @@ def main() -> int:
         return 0
 
     cfg = workloads.CONFIGS[args.workload]
+    if args.seglen:
+        if not cfg.segmented or args.seglen < 1 or args.seglen > cfg.n:
+            print("bench.py: --seglen needs --workload C5 and 1 <= L <= %d" % cfg.n, file=sys.stderr)
+            return 2
+        import dataclasses
+        nseg = cfg.n // args.seglen
+        cfg = dataclasses.replace(cfg, n=nseg * args.seglen, nseg=nseg, seglen=args.seglen)
     t0 = time.perf_counter()
     host = workloads.make(cfg)
     gen_s = time.perf_counter() - t0
@@ -129,7 +139,7 @@ def main() -> int:
     achieved = nbytes / (launch_us * 1e-6) / 1e9
 
     variant_run = "multipass" if multipass else {0: "mfma", 1: "mfma", 2: "classic"}[redux.get_variant()]   # auto resolves to mfma
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, variant_run))
+    traffic = None if args.seglen else MEASURED_TRAFFIC_BYTES.get((args.workload, variant_run))
 
     line = {
         "metric": "achieved HBM GB/s for the fp16 sum (algorithmic bytes / time), 1x MI355X"
