@@ -593,10 +593,10 @@ def test_shutdown_and_reuse_and_host_threads(dev):
 
 
 def test_randomised_shapes_and_settings(dev):
-    """300 random (entry point, dtype, size, base offset, family, launch parameters) cases against the oracle.
+    """400 random (entry point, dtype, size, base offset, family, launch parameters) cases against the oracle.
     Every case stays inside what the host checks allow; the seed is fixed so a failure names its case."""
     rng = np.random.default_rng(20240)
-    for case in range(300):
+    for case in range(400):
         kind = ("flat", "seg", "multipass")[int(rng.integers(0, 3))]
         is_f16 = bool(rng.integers(0, 2))
         variant = ("mfma", "classic", "auto")[int(rng.integers(0, 3))]
@@ -610,12 +610,16 @@ def test_randomised_shapes_and_settings(dev):
         off = int(rng.integers(0, 8 if is_f16 else 16))
         if kind == "seg":
             nseg = int(rng.choice([1, 2, 17, 300, 5000]))
-            seglen = int(rng.choice([1, 7, 8, 64, 100, 512, 1024, 2048, 4099, 30000]))
+            seglen = int(rng.choice([1, 7, 8, 24, 64, 100, 333, 512, 520, 1024, 2048, 4099, 30000]))
             if nseg * seglen > (1 << 23):
                 nseg = max(1, (1 << 23) // seglen)
             redux.set_param("seg_parts", int(rng.choice([0, 0, 2, 16])))
             redux.set_param("seg_tiles", int(rng.integers(0, 2)))
             redux.set_param("seg_block_bytes", int(rng.choice([65536, 0, 2048])))
+            redux.set_param("seg_short", int(rng.integers(0, 2)))
+            redux.set_param("seg_ragged", int(rng.integers(0, 2)))
+            redux.set_param("seg_short_pipe", int(rng.integers(-1, 2)))
+            redux.set_param("seg_blocks_per_cu", int(rng.choice([0, 0, 1, 5])))
             n = nseg * seglen
         else:
             n = int(rng.choice([0, 1, 100, 4097, 70001, (1 << 20) + 5, (1 << 22) + 77]))
