@@ -168,7 +168,8 @@ typedef enum {
                                 segment with the next segment's loads issued ahead */
     REDUX_KERNEL_BLOCK  = 5, /* redux_sum_segmented, long segments: one block per segment or per piece of one
                                 (parts > 1: a per-segment finish kernel follows) */
-    REDUX_KERNEL_SHORT  = 6, /* redux_sum_segmented, 16-byte aligned segments of 16, 32, ... 1024 bytes: the array is
+    REDUX_KERNEL_SHORT  = 6, /* redux_sum_segmented, 16-byte aligned segments of 16, 32, ... 1024 bytes (MMA family, except
+                                binary32: ... 4096 bytes): the array is
                                 read as one contiguous stream and 0/1 selection matrices in the two MMAs (or a
                                 shortened lane butterfly) yield every segment's sum */
     REDUX_KERNEL_RAGGED = 7  /* redux_sum_segmented, any other segment of up to 1008 bytes: the same kernel, each group
@@ -212,8 +213,8 @@ int redux_get_variant(void);
  *                               sixteen-segments-per-wavefront kernel; 0 = never (default 64)
  *   "seg_block_bytes"   0..2^40 segmented sum: segments of at least this many bytes take one 256-thread block
  *                               each (or one per piece) and are streamed like the flat sum; 0 = never (default 32768)
- *   "seg_short"         0/1     segmented sum: 16-byte aligned segments of a power-of-two size from 16 to 1024
- *                               bytes take the contiguous-stream kernel (default 1)
+ *   "seg_short"         0/1     segmented sum: 16-byte aligned segments of a power-of-two size from 16 to 1024 bytes (4096
+ *                               with the MMA family, binary32 excepted) take the contiguous-stream kernel (default 1)
  *   "seg_ragged"        0/1     segmented sum: every other segment of up to 1008 bytes takes that kernel's ragged form
  *                               (default 1)
  *   "seg_short_pipe"    -1,0,1  that kernel: 1 = every register is reloaded from the block's next 32 KiB as soon as it has

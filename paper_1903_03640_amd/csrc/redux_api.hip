@@ -341,8 +341,10 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
     p.part_len = seglen;
     p.nvec = 0;
     const u64 seg_bytes = seglen * es;
-    // aligned power-of-two segments of 16 B .. 1 KiB: read as one contiguous stream, 0/1 selection matrices in the MMAs
-    if (g_set.seg_short && x_addr % 16 == 0 && seg_bytes >= 16 && seg_bytes <= 1024 && (seg_bytes & (seg_bytes - 1)) == 0) {
+    // aligned power-of-two segments of 16 B .. 1 KiB (4 KiB): read as one contiguous stream, 0/1 selection matrices in the MMAs
+    // (measured: with the MMA family also 2 KiB, +7 %, and 4 KiB, +3 %, against one wavefront per segment; 8 KiB is slower)
+    const u64 short_limit = effective_variant(dtype) == REDUX_VARIANT_MFMA && dtype != REDUX_F32 ? 4096 : 1024;
+    if (g_set.seg_short && x_addr % 16 == 0 && seg_bytes >= 16 && seg_bytes <= short_limit && (seg_bytes & (seg_bytes - 1)) == 0) {
         p.kernel = REDUX_KERNEL_SHORT;
         p.nvec = (unsigned)(seg_bytes / 16);
         p.unroll = kShortLoads;

@@ -1,6 +1,6 @@
-// redux_short.h -- segmented sum of short segments (up to 1 KiB each), read as one contiguous stream.
+// redux_short.h -- segmented sum of short segments (up to 4 KiB each), read as one contiguous stream.
 //
-// Aligned form: a segment is 2^lg whole 16-byte vectors (lg = 0 .. 6) and the array starts on a 16-byte
+// Aligned form: a segment is 2^lg whole 16-byte vectors (lg = 0 .. 8) and the array starts on a 16-byte
 // boundary, so every wavefront-wide load (64 vectors, 1 KiB) holds whole segments and the grid can read
 // the array exactly like the flat sum does.  What changes is the constant operand of the two MMAs of
 // Section IV-A: instead of all ones they are 0/1 *selection* matrices, so one MMA pair yields many
@@ -10,7 +10,8 @@
 //               A[l % 16][k-group l / 16].  B_t has ones only where k-group g meets column c(t, g), so
 //               D[i][c(t, g)] is the sum of the elements of vector 16 g + i of load t: up to four
 //               loads (sixteen k-groups) share one accumulator and fill its sixteen columns with 256
-//               per-vector sums.  For segments of 32 or 64 vectors two or four k-groups share a column.
+//               per-vector sums.  For segments of 32 or 64 vectors two or four k-groups share a column; for
+//               128 or 256 vectors (2 or 4 KiB) two or four whole loads of the wavefront do.
 //   second MMA  D' <- S x D with S[m][i] = 1 where row i belongs to sub-segment m of its column
 //               (i >> lg == m): D'[m][c] is the sum of segment m of column c.  For segments of sixteen
 //               vectors or more S is all ones, the second MMA of the paper.
@@ -48,9 +49,10 @@ struct ShortArgs {
 
 // slot index, inside its slab, that load u of thread tid fills: every load of the block covers 256
 // consecutive slots (4 KiB contiguous when aligned), every wavefront 64 of them
-__device__ __forceinline__ unsigned short_index(int u, unsigned tid)
+// (segments of more than 64 slots: every wavefront owns 512 consecutive slots, so that a segment stays in one wavefront)
+__device__ __forceinline__ unsigned short_index(int u, unsigned tid, bool wide)
 {
-    return (unsigned)u * kBlock + tid;
+    return wide ? (tid >> 6) * (64u * kShortLoads) + (unsigned)u * 64u + (tid & 63u) : (unsigned)u * kBlock + tid;
 }
 
 // The vector of slot V (V < a.nvec).  Aligned form: vector V of the array.  Ragged form: slot V is lane
@@ -182,7 +184,7 @@ template <bool NT, bool RAGGED>
 __device__ __forceinline__ void short_load(u32x4 *dst, unsigned *m, const ShortArgs &a, u64 slab, unsigned tid)
 {
 #pragma unroll
-    for (int u = 0; u < kShortLoads; ++u) dst[u] = short_fetch<NT, RAGGED>(a, slab * kShortSlab + short_index(u, tid), &m[u]);
+    for (int u = 0; u < kShortLoads; ++u) dst[u] = short_fetch<NT, RAGGED>(a, slab * kShortSlab + short_index(u, tid, a.lg >= 7), &m[u]);
 }
 
 // The slab that holds the end of the array; slots past the end read zeros.
@@ -191,7 +193,7 @@ __device__ __forceinline__ void short_load_partial(u32x4 *dst, unsigned *m, cons
 {
 #pragma unroll
     for (int u = 0; u < kShortLoads; ++u) {
-        const u64 V = slab * kShortSlab + short_index(u, tid);
+        const u64 V = slab * kShortSlab + short_index(u, tid, a.lg >= 7);
         u32x4 v = {0u, 0u, 0u, 0u};
         m[u] = 0;                                                    // (entry 0 keeps nothing)
         if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V, &m[u]);
@@ -223,7 +225,7 @@ __device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, W
         unsigned m[kShortLoads];
 #pragma unroll
         for (int u = 0; u < kShortLoads; ++u) {      // issued strictly in the order they are consumed in: the waits count on it
-            cur[u] = short_fetch<NT, RAGGED>(a, s0 * kShortSlab + short_index(u, tid), &m[u]);
+            cur[u] = short_fetch<NT, RAGGED>(a, s0 * kShortSlab + short_index(u, tid, a.lg >= 7), &m[u]);
             __builtin_amdgcn_sched_barrier(0);
         }
         u64 slab = s0;
@@ -231,7 +233,7 @@ __device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, W
             const u64 next = (slab + stride) * kShortSlab;
             __builtin_amdgcn_sched_barrier(0);
             work(cur, m, slab, [&](int u) {
-                cur[u] = short_fetch<NT, RAGGED>(a, next + short_index(u, tid), &m[u]);
+                cur[u] = short_fetch<NT, RAGGED>(a, next + short_index(u, tid, a.lg >= 7), &m[u]);
                 __builtin_amdgcn_sched_barrier(0);                   // keep the refill right behind the use
             });
         }
@@ -267,13 +269,42 @@ __device__ __forceinline__ Lane short_butterfly(Lane s, unsigned lg)
     return s;
 }
 
-// one load of the classic family: the vector in v fills slot V
+// one load of the classic family: the vector in v fills slot V (segments of up to 64 slots)
 template <class E>
 __device__ __forceinline__ void short_classic_one(const ShortArgs &a, u32x4 v, u64 V, unsigned lane)
 {
     const typename E::Lane s = short_butterfly(E::lane_sum(v), a.lg);
     const u64 seg = V >> a.lg;
     if ((lane & ((1u << a.lg) - 1u)) == 0 && seg < a.nseg) ((typename E::Out *)a.out)[seg] = E::lane_out(s);
+}
+
+// Loads U0 .. U0 + COUNT - 1 of one slab through the classic family; get(u) hands over vector u and may start its
+// refill.  Segments of 128, 256 or 512 slots span 2, 4 or 8 loads of the wavefront: their lane sums are added up
+// before the butterfly.
+template <class E, int U0, int COUNT, class Get>
+__device__ __forceinline__ void short_classic_range(const ShortArgs &a, u64 slab, unsigned tid, Get &&get)
+{
+    const unsigned lane = tid & 63u;
+    if (a.lg <= 6) {
+#pragma unroll
+        for (int u = U0; u < U0 + COUNT; ++u) {
+            const u32x4 v = get(u);
+            short_classic_one<E>(a, v, slab * kShortSlab + short_index(u, tid, false), lane);
+        }
+    } else {
+        const unsigned per_seg = 1u << (a.lg - 6);               // loads per segment
+        typename E::Lane s = 0;
+#pragma unroll
+        for (int u = U0; u < U0 + COUNT; ++u) {
+            s = s + E::lane_sum(get(u));
+            if ((((unsigned)u + 1u) & (per_seg - 1u)) == 0) {
+                const typename E::Lane total = short_butterfly(s, 6);
+                const u64 seg = (slab * kShortSlab + short_index(u, tid, true)) >> a.lg;
+                if (lane == 0 && seg < a.nseg) ((typename E::Out *)a.out)[seg] = E::lane_out(total);
+                s = 0;
+            }
+        }
+    }
 }
 
 // LPA = loads that share one accumulator: 4 for segments up to sixteen vectors (four columns per load),
@@ -289,21 +320,23 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
     const unsigned g = lane >> 4, n = lane & 15u;
     const unsigned lg = a.lg;
     const unsigned cpl = LPA == 4 ? 4u : (lg == 5 ? 2u : 1u);      // columns per load
+    const bool wide = lg >= 7;                                     // a segment spans 2, 4 or 8 loads of the wavefront
+    const unsigned sh = wide ? lg - 6u : 0u;
     const unsigned lgc = lg < 4 ? lg : 4u;
     const unsigned mask = (16u >> lgc) - 1u;                       // segments per column - 1
 
-    // first MMA: k-group g of load t feeds column t * cpl + g * cpl / 4
+    // first MMA: k-group g of load t feeds column t * cpl + g * cpl / 4 (wide: all of load t feeds column t >> sh)
     bool sel[LPA];
 #pragma unroll
-    for (int t = 0; t < LPA; ++t) sel[t] = (n == (unsigned)t * cpl + (g * cpl) / 4u);
+    for (int t = 0; t < LPA; ++t) sel[t] = (n == (wide ? (unsigned)t >> sh : (unsigned)t * cpl + (g * cpl) / 4u));
     // second MMA, step r: the A operand of this lane is S[m = n][i = 4 g + r]
     float srow[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) srow[r] = (((4u * g + (unsigned)r) >> lgc) == (n & mask)) ? 1.0f : 0.0f;
     // after the second MMA this lane holds rows m = 4 g + r' of column n: the sums of segments m of
     // the 64 / cpl slots that start at slot col_off of load col_load
-    const bool col_used = n < (unsigned)LPA * cpl && 4u * g <= mask;
-    const unsigned col_load = n / cpl;
+    const bool col_used = n < (wide ? 8u >> sh : (unsigned)LPA * cpl) && 4u * g <= mask;
+    const unsigned col_load = wide ? n << sh : n / cpl;
     const unsigned col_off = (n % cpl) * (64u / cpl);
     const unsigned per_lane = mask >= 3u ? 4u : mask + 1u;        // results this lane writes per accumulator: 4, 2 or 1
     typename E::Out *out = (typename E::Out *)a.out;
@@ -326,20 +359,27 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
                 const f32x4 z = dp - dp;
                 const bool bad = (z[0] != 0.f) | (z[1] != 0.f) | (z[2] != 0.f) | (z[3] != 0.f);
                 if (__builtin_amdgcn_ballot_w64(bad) != 0) {       // the same for the whole wavefront
-#pragma unroll
-                    for (int t = 0; t < LPA; ++t) {
-                        const u64 V = slab * kShortSlab + short_index(q * LPA + t, tid);
-                        u32x4 v = {0u, 0u, 0u, 0u};
-                        unsigned mv = 0;
-                        if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V, &mv);
-                        if (RAGGED) v = v & masks[mv];
-                        short_classic_one<E>(a, v, V, lane);
-                    }
+                    if (q == 0)
+                        short_classic_range<E, 0, LPA>(a, slab, tid, [&](int u) {
+                            const u64 V = slab * kShortSlab + short_index(u, tid, wide);
+                            u32x4 v = {0u, 0u, 0u, 0u};
+                            unsigned mv = 0;
+                            if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V, &mv);
+                            return RAGGED ? (v & masks[mv]) : v;
+                        });
+                    else
+                        short_classic_range<E, (NACC > 1 ? LPA : 0), LPA>(a, slab, tid, [&](int u) {
+                            const u64 V = slab * kShortSlab + short_index(u, tid, wide);
+                            u32x4 v = {0u, 0u, 0u, 0u};
+                            unsigned mv = 0;
+                            if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V, &mv);
+                            return RAGGED ? (v & masks[mv]) : v;
+                        });
                     continue;
                 }
             }
             if (col_used) {
-                const u64 vb = slab * kShortSlab + short_index(q * LPA + (int)col_load, wave * 64u) + col_off;
+                const u64 vb = slab * kShortSlab + short_index(q * LPA + (int)col_load, wave * 64u, wide) + col_off;
                 const u64 seg0 = (vb >> lg) + 4u * g;
                 if (seg0 < a.nseg) {
                     const typename E::Out res[4] = {E::fold_out(dp[0]), E::fold_out(dp[1]), E::fold_out(dp[2]), E::fold_out(dp[3])};
@@ -353,16 +393,15 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
 template <class E, bool NT, bool RAGGED>
 __global__ void __launch_bounds__(kBlock) sum_short_classic_kernel(ShortArgs a)
 {
-    const unsigned tid = threadIdx.x, lane = tid & 63u;
+    const unsigned tid = threadIdx.x;
     __shared__ u32x4 masks[RAGGED ? kByteMasks : 1];
     if (RAGGED) fill_byte_masks(masks);
     short_stream<NT, RAGGED>(a, tid, [&](const u32x4 *cur, const unsigned *m, u64 slab, auto refill) {
-#pragma unroll
-        for (int u = 0; u < kShortLoads; ++u) {
+        short_classic_range<E, 0, kShortLoads>(a, slab, tid, [&](int u) {
             const u32x4 v = RAGGED ? (cur[u] & masks[m[u]]) : cur[u];
             refill(u);
-            short_classic_one<E>(a, v, slab * kShortSlab + short_index(u, tid), lane);
-        }
+            return v;
+        });
     });
 }
 

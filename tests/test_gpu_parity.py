@@ -537,12 +537,18 @@ def test_segmented_whole_tile_segments(dev, variant, tiles):
         x = workloads.normal_f16(tiles + nseg, nseg * seglen)
         xd = to_dev(x, dev)
         want, want_abs = oracle.sum_segmented_f16(x, nseg, seglen)
-        want_kernel = redux.KERNEL_SHORT if tiles == 1 else redux.KERNEL_TILES    # 1 KiB: the short-segment kernel comes first
+        # 1 KiB, and with the MMA family 2 and 4 KiB: the contiguous-stream kernel comes first
+        want_kernel = redux.KERNEL_SHORT if tiles == 1 or (variant != "classic" and tiles <= 4) else redux.KERNEL_TILES
         assert redux.plan_sum_segmented(nseg, seglen, redux.F16, xd.data_ptr(), 256).kernel == want_kernel
         got = redux.sum_segmented(xd, nseg, seglen)
+        redux.set_param("seg_short", 0)                     # the whole-tile kernel for every size
+        assert redux.plan_sum_segmented(nseg, seglen, redux.F16, xd.data_ptr(), 256).kernel == (redux.KERNEL_ROWS if tiles == 1 else redux.KERNEL_TILES)
+        mid = redux.sum_segmented(xd, nseg, seglen)
         redux.set_param("seg_tiles", 0)
         ref = redux.sum_segmented(xd, nseg, seglen)
         redux.set_param("seg_tiles", 1)
+        redux.set_param("seg_short", 1)
+        assert np.all(np.abs(mid.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
         torch.cuda.synchronize()
         assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
         assert np.all(np.abs(ref.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)

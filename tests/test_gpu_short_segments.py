@@ -18,7 +18,7 @@ KINDS = ("f16", "bf16", "f32", "e4m3", "e5m2", "i8")
 ESIZE = {"f16": 2, "bf16": 2, "f32": 4, "e4m3": 1, "e5m2": 1, "i8": 1}
 ODT = {"bf16": oracle.BF16, "f32": oracle.F32, "e4m3": oracle.F8E4M3, "e5m2": oracle.F8E5M2}
 CODE = {"f16": redux.F16, "bf16": redux.BF16, "f32": redux.F32, "e4m3": redux.F8E4M3, "e5m2": redux.F8E5M2, "i8": redux.I8}
-SEG_BYTES = (16, 32, 64, 128, 256, 512, 1024)
+SEG_BYTES = (16, 32, 64, 128, 256, 512, 1024, 2048, 4096)     # the last two: MMA family only (binary32 excepted)
 # one wavefront's worth, a ragged count inside one slab, several slabs with a ragged last one, many slabs per block
 NSEGS = (1, 3, 64, 1000, 4097, 70001)
 
@@ -73,8 +73,14 @@ def reset():
 
 
 def expect_short(nseg, seglen, kind):
+    """The plan for this shape under the current variant: the contiguous-stream kernel up to 1 KiB, and up to 4 KiB
+    with the MMA family (binary32 excepted); the whole-tile kernel takes the rest if there are enough segments."""
     plan = redux.plan_sum_segmented(nseg, seglen, CODE[kind], x_address=0, compute_units=256)
-    assert plan.kernel == redux.KERNEL_SHORT, (kind, nseg, seglen, plan.kernel)
+    wide_ok = redux.get_variant() == redux.VARIANTS["mfma"] and kind != "f32"
+    if seglen * ESIZE[kind] <= 1024 or wide_ok:
+        assert plan.kernel == redux.KERNEL_SHORT, (kind, nseg, seglen, plan.kernel)
+    else:
+        assert plan.kernel in (redux.KERNEL_TILES, redux.KERNEL_WAVE), (kind, nseg, seglen, plan.kernel)
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -144,9 +150,12 @@ def test_matches_the_other_kernels_and_is_repeatable(dev, variant):
 
 
 def test_misaligned_or_odd_sizes_take_another_kernel(dev):
+    redux.set_variant("classic")
     for seglen, addr in ((64, 2), (24, 0), (1024, 0), (4, 0)):
         plan = redux.plan_sum_segmented(1000, seglen, redux.F16, x_address=addr, compute_units=256)
         assert plan.kernel != redux.KERNEL_SHORT, (seglen, addr)
+    redux.set_variant("auto")
+    assert redux.plan_sum_segmented(1000, 4096, redux.F16, x_address=0, compute_units=256).kernel != redux.KERNEL_SHORT   # 8 KiB
     # and a misaligned base still gives the right sums
     nseg, seglen = 3000, 64
     pats = workloads.normal_f16(11, nseg * seglen)
@@ -237,7 +246,7 @@ def test_non_finite_values_stay_in_their_segment(dev, kind, variant):
     inf_bits = {"f16": 0x7C00, "bf16": 0x7F80, "f32": 0x7F800000, "e5m2": 0x7C, "e4m3": None}[kind]
     nan_bits = {"f16": 0x7E00, "bf16": 0x7FC0, "f32": 0x7FC00000, "e5m2": 0x7E, "e4m3": 0x7F}[kind]
     sign = {2: 0x8000, 4: 0x80000000, 1: 0x80}[es]
-    for seg_bytes, offset in ((16, 0), (64, 0), (256, 0), (512, 0), (1024, 0), (40, 1), (200, 0), (1000, 1)):
+    for seg_bytes, offset in ((16, 0), (64, 0), (256, 0), (512, 0), (1024, 0), (2048, 0), (4096, 0), (40, 1), (200, 0), (1000, 1)):
         seglen = seg_bytes // es
         nseg = 3 * 2048 + 11
         pats = patterns(kind, seg_bytes, nseg * seglen).copy()

@@ -102,7 +102,8 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
     redux.set_param("seg_ragged", seg_ragged)
     p = redux.plan_sum_segmented(nseg, seglen, dtype, addr, cus)
     assert 1 <= p.grid <= 16 * cus
-    pow2_short = aligned and 16 <= seglen * es <= 1024 and (seglen * es) & (seglen * es - 1) == 0
+    limit = 4096 if dtype not in (redux.F32, redux.F8E4M3, redux.F8E5M2) else 1024    # variant auto: MMA family except for the 8-bit floats
+    pow2_short = aligned and 16 <= seglen * es <= limit and (seglen * es) & (seglen * es - 1) == 0
     assert (p.kernel == redux.KERNEL_SHORT) == bool(seg_short and pow2_short)
     if p.kernel == redux.KERNEL_SHORT:
         assert p.vectors == seglen * es // 16 and p.unroll == 8 and p.parts == 1
@@ -151,7 +152,9 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
 def test_segmented_plan_defaults_on_mi355x():
     c5 = redux.plan_sum_segmented(65536, 4096, redux.F16, 0, 256)
     assert (c5.kernel, c5.unroll, c5.grid, c5.parts) == (redux.KERNEL_TILES, 8, 256, 1)      # 8 KiB segments: pipelined
-    assert redux.plan_sum_segmented(65536, 1024, redux.F16, 0, 256).grid == 768                 # 2 KiB: three blocks per CU
+    two_k = redux.plan_sum_segmented(65536, 1024, redux.F16, 0, 256)
+    assert (two_k.kernel, two_k.vectors, two_k.grid) == (redux.KERNEL_SHORT, 128, 256)          # 2 KiB: contiguous stream, two loads per segment
+    assert redux.plan_sum_segmented(65536, 512, redux.F32, 0, 256).grid == 768                  # binary32, 2 KiB: whole-tile kernel, three blocks per CU
     redux.set_param("seg_tiles", 0)
     c5 = redux.plan_sum_segmented(65536, 4096, redux.F16, 0, 256)
     assert (c5.kernel, c5.unroll, c5.grid, c5.parts) == (redux.KERNEL_WAVE, 2, 1024, 1)           # 512 vectors: two loads per lane, four blocks per CU
