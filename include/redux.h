@@ -101,11 +101,20 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
  *   out     device pointer to nseg results (int64_t for I8, float for every floating-point dtype).
  *   nseg == 0 is a no-op; seglen == 0 writes nseg zeros.
  *
- * The kernel is chosen from (nseg, seglen): short 16-byte-aligned segments (up to 1 KiB) go sixteen to
- * a wavefront, one per row of the A operand, and need only the first MMA; otherwise one wavefront takes
- * one segment (first MMA chained over its tiles, second MMA to fold the rows), with a pipelined form for
- * aligned segments of exactly 2, 4 or 8 KiB; segments of 32 KiB and more take a whole block each; a few
- * long segments are cut into pieces whose totals (in the workspace) a second kernel adds per segment.
+ *   x needs the alignment of its element type only, and seglen may be any number of elements.
+ *
+ * The kernel is chosen from (nseg, seglen, alignment); redux_plan_sum_segmented reports the choice.
+ * Segments of up to 1 KiB (aligned powers of two: 4 KiB) are read as one contiguous stream, a group of 2^k lanes
+ * per segment, and the constant operands of the two MMAs become 0/1 selection matrices, so that one MMA pair yields
+ * many sums; otherwise one wavefront takes one segment (first MMA chained over its tiles, second MMA to fold the
+ * rows), with a leaner form for aligned segments of exactly 1, 2, 4 or 8 KiB; segments of 32 KiB and more take a
+ * whole block each; a few long segments are cut into pieces whose totals (in the workspace) a second kernel adds
+ * per segment.
+ *
+ * Reads outside x: segments that do not start or end on a 16-byte boundary are read as the 16-byte aligned vectors
+ * that overlap them, so up to 15 bytes before x and after x + nseg*seglen*elemsize may be read (never written).  They
+ * share a 16-byte granule, hence a page, with bytes of x, and they never enter a sum.
+ * Non-finite values stay in their segment: an infinity or NaN affects out[s] of its own segment only.
  */
 int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, void *out, void *stream);
 
