@@ -380,8 +380,10 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
     // vectors that overlap its segment and clearing the bytes outside it
     if (ragged_fit) {
         // most vectors a segment can touch: its first byte sits at most 16 - es bytes into a vector (at exactly
-        // x mod 16 if segments are whole vectors long)
-        const u64 max_off = seg_bytes % 16 == 0 ? (u64)(x_addr % 16) : (u64)(16 - es);
+        // x mod 16 if segments are whole vectors long; segments that divide a vector and start on their own size
+        // never straddle one)
+        const u64 max_off = seg_bytes % 16 == 0 ? (u64)(x_addr % 16)
+                          : (16 % seg_bytes == 0 && x_addr % seg_bytes == 0) ? 16 - seg_bytes : (u64)(16 - es);
         const u64 cover = (max_off + seg_bytes + 15) / 16;
         p.kernel = REDUX_KERNEL_RAGGED;
         p.nvec = (unsigned)ragged_lanes(cover);

@@ -217,7 +217,7 @@ def test_ragged_against_oracle(dev, kind, variant):
 def test_ragged_every_segment_lands_in_its_own_slot(dev, kind, variant):
     redux.set_variant(variant)
     es = ESIZE[kind]
-    for seg_bytes, offset in ((es, 1), (3 * es, 0), (20, 1), (52, 3), (236, 1), (1008, 0), (1008, 1), (48, 1), (1004, 0)):
+    for seg_bytes, offset in ((es, 1), (es, 0), (4, 0), (8, 0), (8, 4 // es), (3 * es, 0), (20, 1), (52, 3), (236, 1), (1008, 0), (1008, 1), (48, 1), (1004, 0)):
         if seg_bytes % es:
             continue
         seglen = seg_bytes // es

@@ -114,7 +114,7 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
         lanes = p.vectors
         assert lanes in (1, 2, 4, 8, 16, 32, 64)
         # every placement of a segment fits its lane group: first byte at most 16 - es bytes into a vector
-        worst = (addr % 16 if sb % 16 == 0 else 16 - es)
+        worst = addr % 16 if sb % 16 == 0 else (16 - sb if 16 % sb == 0 and addr % sb == 0 else 16 - es)
         assert lanes * 16 >= worst + sb and (lanes == 1 or (lanes // 2) * 16 < worst + sb)
         assert p.grid <= max(1, -(-(nseg * lanes) // 2048))
     elif p.kernel == redux.KERNEL_ROWS:
@@ -187,6 +187,8 @@ def test_segmented_plan_defaults_on_mi355x():
     ragged = redux.plan_sum_segmented(1 << 20, 100, redux.BF16, 0, 256)                               # 200 B anywhere: 14 vectors
     assert (ragged.kernel, ragged.vectors) == (redux.KERNEL_RAGGED, 16)
     assert redux.plan_sum_segmented(1 << 20, 3, redux.F8E4M3, 0, 256).vectors == 2                    # 3 B can straddle two vectors
+    assert redux.plan_sum_segmented(1 << 20, 2, redux.F16, 0, 256).vectors == 1                       # 4 B on a 4-byte boundary cannot
+    assert redux.plan_sum_segmented(1 << 20, 2, redux.F16, 2, 256).vectors == 2
     assert redux.plan_sum_segmented(1 << 20, 252, redux.F32, 0, 256).vectors == 64                    # 1008 B: the longest
     assert redux.plan_sum_segmented(1 << 20, 253, redux.F32, 0, 256).kernel == redux.KERNEL_WAVE
     redux.set_param("seg_ragged", 0)
