@@ -240,10 +240,13 @@ int redux_get_variant(void);
  *   "layout"            0..2    which part of the array a block reads: 0 = blocks interleaved over the
  *                               whole array, 1 = one contiguous share per block, 2 = one contiguous
  *                               eighth per accelerator die, interleaved among that die's blocks (default 2)
- *   "finish"            -1..2   how block partials become the result: 0/1 = the block that arrives last
+ *   "finish"            -1..3   how block partials become the result: 0/1 = the block that arrives last
  *                               sums them in the same kernel (0: acquire+release on every block's ticket,
  *                               1: release only, acquire in the last block), 2 = a second one-block kernel
- *                               on the same stream, -1 = chosen from the input size (default -1)
+ *                               on the same stream, 3 = every block adds its total to the result atomically
+ *                               (the atomic scheme of Section II, for comparison: a fill kernel clears the
+ *                               result first, and floating-point results then depend on the order of arrival
+ *                               in their last bits), -1 = 1 or 2, chosen from the input size (default -1)
  *   "max_chain"         1..65536 loop iterations between folds of the MMA accumulators into the wide
  *                               per-wavefront total (bounds binary32 chain length; keeps int32
  *                               accumulators below 2^31 for any input)

@@ -294,7 +294,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "lit_unroll")) { *lo = 0; *hi = 16; return &g_set.lit_unroll; }
     if (!std::strcmp(name, "lit_blocks_per_cu")) { *lo = 0; *hi = 16; return &g_set.lit_blocks_per_cu; }
     if (!std::strcmp(name, "layout")) { *lo = 0; *hi = 2; return &g_set.layout; }
-    if (!std::strcmp(name, "finish")) { *lo = -1; *hi = 2; return &g_set.finish; }
+    if (!std::strcmp(name, "finish")) { *lo = -1; *hi = 3; return &g_set.finish; }
     return nullptr;
 }
 
@@ -318,11 +318,11 @@ FlatPlan plan_flat(u64 nvec, int cus)
     }
     const u64 nslab = nvec / ((u64)kBlock * p.unroll);
     p.grid = (unsigned)(nslab < 1 ? 1 : (nslab < gmax ? nslab : gmax));
-    // Measured: finishing inside the kernel (a device-wide release per block) costs about 7 us more than a
-    // second one-block kernel (4.5 us) once the input is 128 MiB or more, and 1-3 us less up to 32 MiB,
-    // where the second launch is what shows.
+    // Measured (us per call, 64 / 128 / 256 blocks): finishing inside the kernel -- a device-wide release per block --
+    // takes 4.8 / 6.3 / 9.2 at 2 / 4 / 8 MiB and stays 2.7 us (large inputs: 7 us) behind a second one-block kernel,
+    // which takes 6.4 flat up to 16 MiB (two launches back to back).  So up to 4 MiB the same kernel finishes.
     p.finish = (int)g_set.finish;
-    if (p.finish < 0) p.finish = nvec > ((u64)32 << 20) / 16 ? 2 : 1;
+    if (p.finish < 0) p.finish = nvec > ((u64)4 << 20) / 16 ? 2 : 1;
     return p;
 }
 
@@ -516,6 +516,12 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
 
     const bool nt = g_set.nontemporal != 0;
     const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
+    if (a.finish == 3) {   // atomic additions start from zero
+        if (dtype != REDUX_I8) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(1), dim3(64), 0, st, (float *)out, (u64)1);
+        else                   hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(1), dim3(64), 0, st, (i64 *)out, (u64)1);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    }
     with_flat_family(dtype, mfma, [&](auto family) { launch_flat<decltype(family)>(unroll, nt, grid, st, a); });
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);

@@ -442,7 +442,7 @@ struct FlatArgs {
     void *out;
     unsigned max_chain; // loop iterations between folds
     int layout;         // which slabs a block takes (see slab_schedule)
-    int finish;         // 0/1: the last block to arrive sums the partials; 2: a second kernel does
+    int finish;         // 0/1: the last block to arrive sums the partials; 2: a second kernel does; 3: atomic additions
 };
 
 constexpr int kXcds = 8;  // workgroup b is dispatched to accelerator die b % 8
@@ -526,6 +526,14 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
     if (a.finish == 2) {
         // partials are summed by finish_kernel, launched behind this kernel on the same stream
         if (tid == 0) a.partials[blockIdx.x] = __builtin_bit_cast(u64, (lds[0] + lds[1]) + (lds[2] + lds[3]));
+        return;
+    }
+    if (a.finish == 3) {
+        // the atomic-addition scheme of Section II: every block adds its total to the result (cleared by a fill kernel
+        // launched ahead).  For floating point the order of arrival decides the rounding, so runs differ in the last bits.
+        if (tid == 0)
+            __hip_atomic_fetch_add((typename F::Out *)a.out, F::to_out((lds[0] + lds[1]) + (lds[2] + lds[3])), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
     if (tid == 0) {

@@ -179,7 +179,7 @@ def test_flat_chain_folds_and_small_grids(dev, variant, max_chain, max_grid):
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("layout", [0, 1, 2])
-@pytest.mark.parametrize("finish", [0, 1, 2])
+@pytest.mark.parametrize("finish", [0, 1, 2, 3])
 def test_flat_layouts_and_finishes(dev, variant, layout, finish):
     redux.set_param("layout", layout)
     redux.set_param("finish", finish)
@@ -611,7 +611,7 @@ def test_randomised_shapes_and_settings(dev):
         redux.set_param("max_grid", int(rng.choice([1, 3, 64, 16384])))
         redux.set_param("max_chain", int(rng.choice([1, 7, 256])))
         redux.set_param("layout", int(rng.integers(0, 3)))
-        redux.set_param("finish", int(rng.integers(-1, 3)))
+        redux.set_param("finish", int(rng.integers(-1, 4)))
         redux.set_param("nontemporal", int(rng.integers(0, 2)))
         off = int(rng.integers(0, 8 if is_f16 else 16))
         if kind == "seg":
