@@ -112,3 +112,32 @@ def test_error_of_final_rounding_only(dev):
             assert redux.sum(xd).item() == exact
         redux.set_variant("auto")
         assert redux.sum_multipass(xd)[0].item() == exact
+
+
+def test_error_vs_chain_length(dev):
+    """How long a binary32 accumulator chain may get before it is folded into the binary64 total: one block reads
+    2^27 elements (8192 loop iterations), with the fold every `max_chain` iterations.  Every accumulator entry then
+    adds at most 2 * max_chain MFMA results in a row; the first-order bound (2 * max_chain + 96) * 2^-24 * sum|x|
+    must hold, and the error grows with the chain (run with -s for the table)."""
+    n = 1 << 27
+    redux.set_variant("mfma")
+    redux.set_param("max_grid", 1)
+    print("\n|error| / sum|x| by chain length (one block, n = 2^27; 2^-24 = %.2e)" % U32)
+    print("  dist       " + "".join("%-11d" % c for c in (1, 4, 16, 64, 256, 1024, 8192)))
+    for dist in ("uniform01", "tenth", "normal"):
+        x = make(dist, n, 77)
+        _, sum_abs, units, nonfinite = oracle.sum_f16_exact(x)
+        assert not nonfinite
+        exact = units / float(1 << 24)
+        xd = torch.from_numpy(x).to(dev)
+        rels = []
+        for chain in (1, 4, 16, 64, 256, 1024, 8192):
+            redux.set_param("max_chain", chain)
+            got = redux.sum(xd).item()
+            rel = abs(got - exact) / sum_abs
+            assert rel <= (2 * chain + 96) * U32, (dist, chain, rel)
+            rels.append(rel)
+        print("  %-10s " % dist + "".join("%-11s" % ("%.2e" % r) for r in rels))
+        assert rels[0] <= 2 * U32                          # folded every iteration: only the final rounding is left
+    redux.set_param("max_chain", 256)
+    redux.set_param("max_grid", 16384)
