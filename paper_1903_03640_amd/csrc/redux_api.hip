@@ -139,7 +139,10 @@ void launch_literal_f16(bool first, bool fast, const void *in, u64 n, void *outp
         if (fast) hipLaunchKernelGGL((literal_level_kernel<M, true, U, true>), dim3(grid), dim3(kBlock), 0, st, in, n, (float *)outp);
         else      hipLaunchKernelGGL((literal_level_kernel<M, true, U, false>), dim3(grid), dim3(kBlock), 0, st, in, n, (float *)outp);
     } else {
-        hipLaunchKernelGGL((literal_level_kernel<M, false, U, true>), dim3(grid), dim3(kBlock), 0, st, in, n, (float *)outp);
+        // (sixteen 32 x 32 tiles of binary32 per wavefront step would not fit the register file; the kernel loops over
+        // its own batches, so any grid fits any U)
+        constexpr int UL = (M == 32 && U > 8) ? 8 : U;
+        hipLaunchKernelGGL((literal_level_kernel<M, false, UL, true>), dim3(grid), dim3(kBlock), 0, st, in, n, (float *)outp);
     }
 }
 
@@ -390,8 +393,7 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         p.unroll = kShortLoads;
         const u64 nslab = (nseg * p.nvec + kShortSlab - 1) / kShortSlab;
         // measured: the address and mask arithmetic per load wants more wavefronts per compute unit than the aligned form
-        const long best_bpc = effective_variant(dtype) == REDUX_VARIANT_MFMA ? 6 : 8;
-        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : best_bpc);
+        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 8);
         if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
         if (gmax < 1) gmax = 1;
         p.grid = (unsigned)(nslab < gmax ? nslab : gmax);

@@ -639,9 +639,10 @@ __global__ void __launch_bounds__(kBlock) sum_segmented_kernel(SegArgs a)
         F::clear(acc);
         Total total = 0;
         if (len) {
-            const u64 addr = (u64)(uintptr_t)a.x + (seg * a.seglen + first) * F::kElemSize;
-            const unsigned off = (unsigned)addr & 15u;
-            const u32x4 *base = (const u32x4 *)(addr - off);
+            // (pointer arithmetic on the kernel argument keeps the loads in the global address space)
+            const unsigned char *start = a.x + (seg * a.seglen + first) * F::kElemSize;
+            const unsigned off = (unsigned)(uintptr_t)start & 15u;
+            const u32x4 *base = (const u32x4 *)(start - off);
             const u64 end = off + len * F::kElemSize;          // end of the piece, in bytes from its first aligned vector
             const u64 cover = (end + 15) >> 4;                 // aligned vectors that overlap the piece
             unsigned chain = 0;

@@ -26,8 +26,9 @@
 //
 // A zero in a selection matrix still multiplies its data: an infinity or NaN in one segment would turn
 // the other segments of its accumulator into NaN (0 x inf).  So whenever an accumulator yields a
-// non-finite result -- which every non-finite input forces in its own segment -- its loads are read again
-// and summed with the lane butterfly, which never mixes segments.
+// non-finite result -- which every non-finite input forces in its own segment -- the wavefront's part of
+// that slab is read again after the streaming loop and summed with the lane butterfly, which never mixes
+// segments.
 #pragma once
 #include "redux_kernels.h"
 
@@ -67,14 +68,17 @@ __device__ __forceinline__ u32x4 short_fetch(const ShortArgs &a, u64 V, unsigned
     if (!RAGGED) { *m = 0; return load16<NT>((const u32x4 *)a.x + V); }
     const u64 seg = V >> a.lg;
     const unsigned j = (unsigned)V & ((1u << a.lg) - 1u);
-    const u64 first = (u64)(uintptr_t)a.x + seg * a.seg_bytes;       // address of the segment's first byte
-    const unsigned off = (unsigned)first & 15u;
+    // (pointer arithmetic on the kernel argument, not integer arithmetic on its value: the compiler then knows the
+    // address is global memory and issues global, not flat, loads -- a flat load also counts as an LDS operation, and
+    // every wait for the byte-mask table would wait for it)
+    const unsigned char *first = a.x + seg * a.seg_bytes;            // the segment's first byte
+    const unsigned off = (unsigned)(uintptr_t)first & 15u;
     const unsigned end = off + (unsigned)a.seg_bytes;                // segment end, in bytes from its first aligned vector
     const unsigned cover = (end + 15u) >> 4;                         // aligned vectors that overlap the segment (at least 1)
     // Lanes past the last overlapping vector read that vector again (the same cache line as their neighbour: no
     // extra traffic) and keep nothing of it, so that every lane issues its load and waits can be counted.
     const unsigned jj = j < cover ? j : cover - 1u;
-    const u32x4 v = load16<NT>((const u32x4 *)((first - off) + 16ull * jj));
+    const u32x4 v = load16<NT>((const u32x4 *)(first - off) + jj);
     // bytes [lo, hi) of the vector belong to the segment
     const unsigned lo = j == 0 ? off : 0u;
     const unsigned hi = j >= cover ? 0u : (end - 16u * j >= 16u ? 16u : end - 16u * j);
@@ -180,20 +184,22 @@ struct ShortI8 {
 };
 
 // One whole slab into registers.
-template <bool NT, bool RAGGED>
+// (CANWIDE: whether this kernel is ever launched for segments of more than 64 slots)
+template <bool NT, bool RAGGED, bool CANWIDE>
 __device__ __forceinline__ void short_load(u32x4 *dst, unsigned *m, const ShortArgs &a, u64 slab, unsigned tid)
 {
 #pragma unroll
-    for (int u = 0; u < kShortLoads; ++u) dst[u] = short_fetch<NT, RAGGED>(a, slab * kShortSlab + short_index(u, tid, a.lg >= 7), &m[u]);
+    for (int u = 0; u < kShortLoads; ++u)
+        dst[u] = short_fetch<NT, RAGGED>(a, slab * kShortSlab + short_index(u, tid, CANWIDE && a.lg >= 7), &m[u]);
 }
 
 // The slab that holds the end of the array; slots past the end read zeros.
-template <bool NT, bool RAGGED>
+template <bool NT, bool RAGGED, bool CANWIDE>
 __device__ __forceinline__ void short_load_partial(u32x4 *dst, unsigned *m, const ShortArgs &a, u64 slab, unsigned tid)
 {
 #pragma unroll
     for (int u = 0; u < kShortLoads; ++u) {
-        const u64 V = slab * kShortSlab + short_index(u, tid, a.lg >= 7);
+        const u64 V = slab * kShortSlab + short_index(u, tid, CANWIDE && a.lg >= 7);
         u32x4 v = {0u, 0u, 0u, 0u};
         m[u] = 0;                                                    // (entry 0 keeps nothing)
         if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V, &m[u]);
@@ -206,45 +212,72 @@ __device__ __forceinline__ void short_load_partial(u32x4 *dst, unsigned *m, cons
 // lane stay in flight while the MMAs (or the butterfly) and the stores run.  The block's last slab is peeled off, so
 // that no load in the loop is conditional and the wait in front of each use leaves exactly the seven newer loads
 // outstanding.  The slab that holds the ragged end of the array is done by one block afterwards.
-template <bool NT, bool RAGGED, class Work>
-__device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, Work &&work)
+//
+// work returns whether any of this wavefront's results of the slab must be computed again (the same answer in every
+// lane); `redo(cur, m, slab)` does that.  It runs after the streaming loops, over the range of slabs that asked for it:
+// anything heavier than a flag inside those loops -- above all a load under a branch -- costs them their pipelining.
+template <bool NT, bool RAGGED, bool CANWIDE, class Work, class Redo>
+__device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, Work &&work, Redo &&redo)
 {
     const u64 nfull = a.nvec / kShortSlab;
     u64 s0, stride, count;
     slab_schedule(a.layout, nfull, gridDim.x, blockIdx.x, &s0, &stride, &count);
+    u64 redo_first = ~0ull, redo_last = 0;                           // positions in this block's schedule
     if (count && a.pipe == 0) {
         for (u64 k = 0; k < count; ++k) {
             u32x4 cur[kShortLoads];
             unsigned m[kShortLoads];
-            short_load<NT, RAGGED>(cur, m, a, s0 + k * stride, tid);
+            short_load<NT, RAGGED, CANWIDE>(cur, m, a, s0 + k * stride, tid);
             __builtin_amdgcn_sched_barrier(0);
-            work(cur, m, s0 + k * stride, [](int) {});
+            if (work(cur, m, s0 + k * stride, [](int) {})) {
+                redo_first = redo_first < k ? redo_first : k;
+                redo_last = k;
+            }
         }
     } else if (count) {
         u32x4 cur[kShortLoads];
         unsigned m[kShortLoads];
 #pragma unroll
         for (int u = 0; u < kShortLoads; ++u) {      // issued strictly in the order they are consumed in: the waits count on it
-            cur[u] = short_fetch<NT, RAGGED>(a, s0 * kShortSlab + short_index(u, tid, a.lg >= 7), &m[u]);
+            cur[u] = short_fetch<NT, RAGGED>(a, s0 * kShortSlab + short_index(u, tid, CANWIDE && a.lg >= 7), &m[u]);
             __builtin_amdgcn_sched_barrier(0);
         }
         u64 slab = s0;
         for (u64 k = 1; k < count; ++k, slab += stride) {
             const u64 next = (slab + stride) * kShortSlab;
             __builtin_amdgcn_sched_barrier(0);
-            work(cur, m, slab, [&](int u) {
-                cur[u] = short_fetch<NT, RAGGED>(a, next + short_index(u, tid, a.lg >= 7), &m[u]);
+            const bool again = work(cur, m, slab, [&](int u) {
+                cur[u] = short_fetch<NT, RAGGED>(a, next + short_index(u, tid, CANWIDE && a.lg >= 7), &m[u]);
                 __builtin_amdgcn_sched_barrier(0);                   // keep the refill right behind the use
             });
+            if (again) {
+                redo_first = redo_first < k - 1 ? redo_first : k - 1;
+                redo_last = k - 1;
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
-        work(cur, m, slab, [](int) {});
+        if (work(cur, m, slab, [](int) {})) {
+            redo_first = redo_first < count - 1 ? redo_first : count - 1;
+            redo_last = count - 1;
+        }
+    }
+    if (redo_first <= redo_last) {
+        __builtin_amdgcn_s_waitcnt(0);                               // the first pass's stores have landed
+        for (u64 k = redo_first; k <= redo_last; ++k) {
+            u32x4 cur[kShortLoads];
+            unsigned m[kShortLoads];
+            short_load<NT, RAGGED, CANWIDE>(cur, m, a, s0 + k * stride, tid);
+            redo(cur, m, s0 + k * stride);
+        }
     }
     if (nfull * kShortSlab < a.nvec && blockIdx.x == (unsigned)(nfull % gridDim.x)) {
         u32x4 last[kShortLoads];
         unsigned m[kShortLoads];
-        short_load_partial<NT, RAGGED>(last, m, a, nfull, tid);
-        work(last, m, nfull, [](int) {});
+        short_load_partial<NT, RAGGED, CANWIDE>(last, m, a, nfull, tid);
+        if (work(last, m, nfull, [](int) {})) {
+            __builtin_amdgcn_s_waitcnt(0);
+            redo(last, m, nfull);
+        }
     }
 }
 
@@ -281,11 +314,11 @@ __device__ __forceinline__ void short_classic_one(const ShortArgs &a, u32x4 v, u
 // Loads U0 .. U0 + COUNT - 1 of one slab through the classic family; get(u) hands over vector u and may start its
 // refill.  Segments of 128, 256 or 512 slots span 2, 4 or 8 loads of the wavefront: their lane sums are added up
 // before the butterfly.
-template <class E, int U0, int COUNT, class Get>
+template <class E, int U0, int COUNT, bool CANWIDE, class Get>
 __device__ __forceinline__ void short_classic_range(const ShortArgs &a, u64 slab, unsigned tid, Get &&get)
 {
     const unsigned lane = tid & 63u;
-    if (a.lg <= 6) {
+    if (!CANWIDE || a.lg <= 6) {
 #pragma unroll
         for (int u = U0; u < U0 + COUNT; ++u) {
             const u32x4 v = get(u);
@@ -320,7 +353,8 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
     const unsigned g = lane >> 4, n = lane & 15u;
     const unsigned lg = a.lg;
     const unsigned cpl = LPA == 4 ? 4u : (lg == 5 ? 2u : 1u);      // columns per load
-    const bool wide = lg >= 7;                                     // a segment spans 2, 4 or 8 loads of the wavefront
+    constexpr bool CANWIDE = LPA == 8 && !RAGGED;
+    const bool wide = CANWIDE && lg >= 7;                          // a segment spans 2, 4 or 8 loads of the wavefront
     const unsigned sh = wide ? lg - 6u : 0u;
     const unsigned lgc = lg < 4 ? lg : 4u;
     const unsigned mask = (16u >> lgc) - 1u;                       // segments per column - 1
@@ -341,7 +375,8 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
     const unsigned per_lane = mask >= 3u ? 4u : mask + 1u;        // results this lane writes per accumulator: 4, 2 or 1
     typename E::Out *out = (typename E::Out *)a.out;
 
-    short_stream<NT, RAGGED>(a, tid, [&](const u32x4 *cur, const unsigned *m, u64 slab, auto refill) {
+    short_stream<NT, RAGGED, CANWIDE>(a, tid, [&](const u32x4 *cur, const unsigned *m, u64 slab, auto refill) {
+        bool again = false;                                        // some accumulator holds a non-finite value
 #pragma unroll
         for (int q = 0; q < NACC; ++q) {
             typename E::Acc d = E::zero();
@@ -357,26 +392,7 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
             if (E::kCanBeNonFinite) {
                 // finite - finite is 0; infinities and NaNs give NaN, which differs from itself
                 const f32x4 z = dp - dp;
-                const bool bad = (z[0] != 0.f) | (z[1] != 0.f) | (z[2] != 0.f) | (z[3] != 0.f);
-                if (__builtin_amdgcn_ballot_w64(bad) != 0) {       // the same for the whole wavefront
-                    if (q == 0)
-                        short_classic_range<E, 0, LPA>(a, slab, tid, [&](int u) {
-                            const u64 V = slab * kShortSlab + short_index(u, tid, wide);
-                            u32x4 v = {0u, 0u, 0u, 0u};
-                            unsigned mv = 0;
-                            if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V, &mv);
-                            return RAGGED ? (v & masks[mv]) : v;
-                        });
-                    else
-                        short_classic_range<E, (NACC > 1 ? LPA : 0), LPA>(a, slab, tid, [&](int u) {
-                            const u64 V = slab * kShortSlab + short_index(u, tid, wide);
-                            u32x4 v = {0u, 0u, 0u, 0u};
-                            unsigned mv = 0;
-                            if (V < a.nvec) v = short_fetch<NT, RAGGED>(a, V, &mv);
-                            return RAGGED ? (v & masks[mv]) : v;
-                        });
-                    continue;
-                }
+                again |= (z[0] != 0.f) | (z[1] != 0.f) | (z[2] != 0.f) | (z[3] != 0.f);
             }
             if (col_used) {
                 const u64 vb = slab * kShortSlab + short_index(q * LPA + (int)col_load, wave * 64u, wide) + col_off;
@@ -387,6 +403,10 @@ __global__ void __launch_bounds__(kBlock) sum_short_mfma_kernel(ShortArgs a)
                 }
             }
         }
+        return __builtin_amdgcn_ballot_w64(again) != 0;            // the same for the whole wavefront
+    }, [&](const u32x4 *cur, const unsigned *m, u64 slab) {
+        // the whole slab of this wavefront again, with the lane butterfly, which never mixes segments
+        short_classic_range<E, 0, kShortLoads, CANWIDE>(a, slab, tid, [&](int u) { return RAGGED ? (cur[u] & masks[m[u]]) : cur[u]; });
     });
 }
 
@@ -396,13 +416,15 @@ __global__ void __launch_bounds__(kBlock) sum_short_classic_kernel(ShortArgs a)
     const unsigned tid = threadIdx.x;
     __shared__ u32x4 masks[RAGGED ? kByteMasks : 1];
     if (RAGGED) fill_byte_masks(masks);
-    short_stream<NT, RAGGED>(a, tid, [&](const u32x4 *cur, const unsigned *m, u64 slab, auto refill) {
-        short_classic_range<E, 0, kShortLoads>(a, slab, tid, [&](int u) {
+    // (segments of more than 64 slots never come here: the host gives them to the MMA family only)
+    short_stream<NT, RAGGED, false>(a, tid, [&](const u32x4 *cur, const unsigned *m, u64 slab, auto refill) {
+        short_classic_range<E, 0, kShortLoads, false>(a, slab, tid, [&](int u) {
             const u32x4 v = RAGGED ? (cur[u] & masks[m[u]]) : cur[u];
             refill(u);
             return v;
         });
-    });
+        return false;
+    }, [](const u32x4 *, const unsigned *, u64) {});
 }
 
 } // namespace redux
