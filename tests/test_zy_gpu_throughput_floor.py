@@ -1,0 +1,87 @@
+"""Throughput floors on a MI355X: every kernel of the library at one typical shape must reach 70 % of what it
+measured when it was tuned.  Parity tests cannot see a kernel that computes the right sums at a third of its speed
+(a lost software pipeline, a flat load, a register spill all did exactly that during development); this does.
+The floors are far below the measured figures (box-to-box and run-to-run spread is under 10 %), best of three runs."""
+import pytest
+
+from paper_1903_03640_amd import redux
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+FLOOR = 0.70
+
+
+def best_gbps(fn, nbytes, steps=20, repeats=3):
+    best = 0.0
+    for _ in range(repeats):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, nbytes * steps / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    return best
+
+
+@pytest.fixture(scope="module")
+def arena():
+    assert torch.cuda.is_available()
+    redux.load()
+    torch.cuda.set_device(0)
+    if torch.cuda.get_device_properties(0).multi_processor_count != 256:
+        pytest.skip("floors are MI355X figures")
+    yield torch.zeros((1 << 29) + 64, dtype=torch.int8, device="cuda")
+    redux.set_variant("auto")
+
+
+# (variant, dtype, segment bytes or None for the flat sum, element offset of the base, kernel expected, measured GB/s)
+CASES = [
+    ("mfma", torch.float16, None, 0, redux.KERNEL_FLAT, 7100),
+    ("classic", torch.float16, None, 0, redux.KERNEL_FLAT, 7100),
+    ("mfma", torch.int8, None, 0, redux.KERNEL_FLAT, 7000),
+    ("mfma", torch.float16, 16, 0, redux.KERNEL_SHORT, 4950),
+    ("mfma", torch.float16, 128, 0, redux.KERNEL_SHORT, 6300),
+    ("mfma", torch.float16, 1024, 0, redux.KERNEL_SHORT, 7300),
+    ("mfma", torch.float16, 4096, 0, redux.KERNEL_SHORT, 7100),
+    ("classic", torch.float16, 128, 0, redux.KERNEL_SHORT, 5950),
+    ("mfma", torch.bfloat16, 256, 0, redux.KERNEL_SHORT, 6900),
+    ("mfma", torch.int8, 256, 0, redux.KERNEL_SHORT, 6400),
+    ("classic", torch.float8_e4m3fn, 256, 0, redux.KERNEL_SHORT, 6500),
+    ("mfma", torch.float16, 200, 0, redux.KERNEL_RAGGED, 5850),
+    ("classic", torch.float16, 200, 0, redux.KERNEL_RAGGED, 5800),
+    ("mfma", torch.float16, 64, 1, redux.KERNEL_RAGGED, 4900),
+    ("classic", torch.float32, 400, 0, redux.KERNEL_RAGGED, 6100),
+    ("mfma", torch.float16, 8192, 0, redux.KERNEL_TILES, 7150),
+    ("classic", torch.float16, 8192, 0, redux.KERNEL_TILES, 7100),
+    ("mfma", torch.float16, 3000, 0, redux.KERNEL_WAVE, 6100),
+    ("classic", torch.float16, 12000, 0, redux.KERNEL_WAVE, 6850),
+    ("mfma", torch.float16, 131072, 0, redux.KERNEL_BLOCK, 6900),
+    ("mfma", torch.float16, 2 << 20, 0, redux.KERNEL_BLOCK, 6800),
+]
+
+
+@pytest.mark.parametrize("variant,dtype,seg_bytes,offset,kernel,measured", CASES)
+def test_throughput_floor(arena, variant, dtype, seg_bytes, offset, kernel, measured):
+    redux.set_variant(variant)
+    x = arena.view(dtype)
+    es = x.element_size()
+    total = (1 << 29) // es
+    if seg_bytes is None:
+        x = x[:total]
+        out = torch.empty(1, dtype=torch.int64 if dtype == torch.int8 else torch.float32, device="cuda")
+        got = best_gbps(lambda: redux.sum(x, out=out), total * es)
+    else:
+        seglen = seg_bytes // es
+        nseg = (total - 8) // seglen
+        x = x[offset:offset + nseg * seglen]
+        plan = redux.plan_sum_segmented(nseg, seglen, redux._dtype_of(x), x.data_ptr(), 256)
+        assert plan.kernel == kernel, (plan.kernel, kernel)
+        out = torch.empty(nseg, dtype=torch.int64 if dtype == torch.int8 else torch.float32, device="cuda")
+        got = best_gbps(lambda: redux.sum_segmented(x, nseg, seglen, out=out), nseg * seglen * es)
+    assert got >= FLOOR * measured, "%.0f GB/s, measured %d when tuned" % (got, measured)
+    print("%-8s %-22s %8s B: %.0f GB/s (%.0f %% of %d)" % (variant, str(dtype), seg_bytes, got, 100 * got / measured, measured))
