@@ -496,14 +496,18 @@ def test_graph_replay_matches_eager(dev):
     x = to_dev(workloads.normal_f16(61, n), dev)
     xs = to_dev(workloads.uniform_f16(62, nseg * seglen, symmetric=True), dev)
     xi = to_dev(workloads.uniform_i8(63, small_n), dev)
+    nshort = 20000                                            # the same array as short aligned (128 B) and ragged (200 B) segments
     outs = [torch.zeros(1, dtype=torch.float32, device=dev), torch.zeros(nseg, dtype=torch.float32, device=dev),
-            torch.zeros(1, dtype=torch.int64, device=dev), torch.zeros(1, dtype=torch.float32, device=dev)]
+            torch.zeros(1, dtype=torch.int64, device=dev), torch.zeros(1, dtype=torch.float32, device=dev),
+            torch.zeros(nshort, dtype=torch.float32, device=dev), torch.zeros(nshort, dtype=torch.float32, device=dev)]
 
     def run_all():
         redux.sum(x, out=outs[0])
         redux.sum_segmented(xs, nseg, seglen, out=outs[1])
         redux.sum(xi, out=outs[2])
         redux.sum_multipass(x, out=outs[3])
+        redux.sum_segmented(x, nshort, 64, out=outs[4])
+        redux.sum_segmented(x, nshort, 100, out=outs[5])
 
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
