@@ -506,8 +506,8 @@ def test_graph_replay_matches_eager(dev):
         redux.sum_segmented(xs, nseg, seglen, out=outs[1])
         redux.sum(xi, out=outs[2])
         redux.sum_multipass(x, out=outs[3])
-        redux.sum_segmented(x, nshort, 64, out=outs[4])
-        redux.sum_segmented(x, nshort, 100, out=outs[5])
+        redux.sum_segmented(x[:nshort * 64], nshort, 64, out=outs[4])
+        redux.sum_segmented(x[:nshort * 100], nshort, 100, out=outs[5])
 
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
