@@ -42,7 +42,7 @@ struct ShortArgs {
     u64 nseg;
     u64 nvec;           // nseg << lg: lane slots, one 16-byte vector each
     u64 seg_bytes;      // ragged form: bytes per segment
-    unsigned lg;        // log2(lanes per segment), 0 .. 6
+    unsigned lg;        // log2(lane slots per segment): 0 .. 6, aligned form of the MMA family also 7 and 8
     void *out;
     int layout;         // see slab_schedule
     int pipe;           // 0 = plain loop, 1 = refill each register as soon as it is consumed
