@@ -138,7 +138,7 @@ def main() -> int:
     launch_us = dev_ms * 1e3 / args.steps
     achieved = nbytes / (launch_us * 1e-6) / 1e9
 
-    variant_run = "multipass" if multipass else {0: "mfma", 1: "mfma", 2: "classic"}[redux.get_variant()]   # auto resolves to mfma
+    variant_run = "multipass" if multipass else redux.resolved_variant(redux._dtype_of(x), cfg.segmented)
     traffic = None if args.seglen else MEASURED_TRAFFIC_BYTES.get((args.workload, variant_run))
 
     line = {

@@ -63,7 +63,8 @@ typedef enum {
 
 /* Which kernel family computes the sum. */
 typedef enum {
-    REDUX_VARIANT_AUTO    = 0, /* the library's default choice: MFMA, except CLASSIC for the 8-bit floats */
+    REDUX_VARIANT_AUTO    = 0, /* the family that measured faster: CLASSIC for redux_sum (by about 1 %), MFMA for
+                                  redux_sum_segmented -- except CLASSIC for the 8-bit floats, whose MFMAs drop bits */
     REDUX_VARIANT_MFMA    = 1, /* MMA encoding: data tile x all-ones, accumulator chained through C   */
     REDUX_VARIANT_CLASSIC = 2  /* per-lane serial accumulation + wavefront tree (Section III)         */
 } redux_variant;
@@ -209,6 +210,9 @@ int redux_plan_block_slabs(int layout, uint64_t nslab, uint64_t grid, uint64_t b
  * environment variable REDUX_VARIANT = auto | mfma | classic. */
 int redux_set_variant(int variant);
 int redux_get_variant(void);
+/* The family (REDUX_VARIANT_MFMA or _CLASSIC) that a redux_sum (segmented == 0) or redux_sum_segmented (!= 0) call on
+ * `dtype` runs with under the current setting; a negative redux_status for an unknown dtype. */
+int redux_resolved_variant(int dtype, int segmented);
 
 /*
  * Launch parameters (process-wide; for tuning and tests).  Names:

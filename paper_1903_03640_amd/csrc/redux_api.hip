@@ -266,10 +266,15 @@ void with_short_family(int dtype, Fn &&fn)
     }
 }
 
-int effective_variant(int dtype)
+// The family a call runs with.  `flat`: redux_sum (otherwise redux_sum_segmented).
+int effective_variant(int dtype, bool flat = false)
 {
     int v = g_set.variant;
     if (v != REDUX_VARIANT_AUTO) return v;
+    // Measured on the 1-2 GiB flat sums: the classic family is 0.7-1.4 % faster (289.6 vs 292.2 us on 2 GiB of binary16,
+    // 144.5 vs 145.5 us on 1 GiB of int8; the same sign on every machine tried).  Segmented sums: the MMA family is as
+    // fast (8 KiB segments) or 5-30 % faster (short and ragged segments).
+    if (flat) return REDUX_VARIANT_CLASSIC;
     // The 8-bit floating-point MFMAs align the eight products of a lane to the largest of them and keep
     // only 14 bits below it (measured), so small terms next to a large one are dropped: up to
     // 7 * 2^-14 of sum|x|, above the 1e-4 this library promises.  Their default is the classic family.
@@ -517,7 +522,7 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
     a.finish = plan.finish;
 
     const bool nt = g_set.nontemporal != 0;
-    const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
+    const bool mfma = effective_variant(dtype, true) == REDUX_VARIANT_MFMA;
     if (a.finish == 3) {   // atomic additions start from zero
         if (dtype != REDUX_I8) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(1), dim3(64), 0, st, (float *)out, (u64)1);
         else                   hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(1), dim3(64), 0, st, (i64 *)out, (u64)1);
@@ -868,6 +873,14 @@ int redux_get_variant(void)
     std::call_once(g_env_once, read_env);
     std::lock_guard<std::mutex> lock(g_mu);
     return g_set.variant;
+}
+
+int redux_resolved_variant(int dtype, int segmented)
+{
+    std::call_once(g_env_once, read_env);
+    if (elem_size_of(dtype) == 0) return REDUX_ERR_DTYPE;
+    std::lock_guard<std::mutex> lock(g_mu);
+    return effective_variant(dtype, segmented == 0);
 }
 
 int redux_set_param(const char *name, long value)

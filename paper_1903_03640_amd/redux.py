@@ -20,7 +20,7 @@ VARIANTS = {"auto": 0, "mfma": 1, "classic": 2}
 SYMBOLS = (
     "redux_sum", "redux_sum_segmented", "redux_sum_multipass", "redux_mma_group_probe", "redux_calibration_copy",
     "redux_plan_sum", "redux_plan_sum_segmented", "redux_plan_block_slabs",
-    "redux_set_variant", "redux_get_variant", "redux_set_param", "redux_get_param",
+    "redux_set_variant", "redux_get_variant", "redux_resolved_variant", "redux_set_param", "redux_get_param",
     "redux_strerror", "redux_last_hip_error", "redux_shutdown", "redux_version",
 )
 
@@ -74,6 +74,8 @@ def load():
         lib.redux_set_variant.argtypes = [ci]
         lib.redux_get_variant.restype = ci
         lib.redux_get_variant.argtypes = []
+        lib.redux_resolved_variant.restype = ci
+        lib.redux_resolved_variant.argtypes = [ci, ci]
         lib.redux_set_param.restype = ci
         lib.redux_set_param.argtypes = [ctypes.c_char_p, ctypes.c_long]
         lib.redux_get_param.restype = ctypes.c_long
@@ -110,6 +112,14 @@ def set_variant(variant) -> None:
 
 def get_variant() -> int:
     return load().redux_get_variant()
+
+
+def resolved_variant(dtype: int, segmented: bool) -> str:
+    """'mfma' or 'classic': the family a call on `dtype` runs with under the current setting."""
+    v = load().redux_resolved_variant(dtype, 1 if segmented else 0)
+    if v < 0:
+        raise ReduxError(v, "redux_resolved_variant")
+    return {1: "mfma", 2: "classic"}[v]
 
 
 def set_param(name: str, value: int) -> None:

@@ -71,3 +71,20 @@ def test_settings():
             redux.set_param(*bad)
     assert redux.get_param("no_such_param") < -(1 << 40)
     assert "gfx950" in redux.version()
+
+
+def test_resolved_variant_without_a_gpu():
+    """What 'auto' resolves to: the classic family for the flat sum, the MMA family for segmented sums, except the
+    8-bit floats (classic everywhere); an explicit setting wins; unknown dtypes are an error."""
+    redux.set_variant("auto")
+    for dt in (redux.F16, redux.I8, redux.BF16, redux.F32, redux.F8E4M3, redux.F8E5M2):
+        assert redux.resolved_variant(dt, segmented=False) == "classic"
+    for dt in (redux.F16, redux.I8, redux.BF16, redux.F32):
+        assert redux.resolved_variant(dt, segmented=True) == "mfma"
+    for dt in (redux.F8E4M3, redux.F8E5M2):
+        assert redux.resolved_variant(dt, segmented=True) == "classic"
+    for v in ("mfma", "classic"):
+        redux.set_variant(v)
+        assert redux.resolved_variant(redux.F8E4M3, segmented=True) == v and redux.resolved_variant(redux.F16, segmented=False) == v
+    redux.set_variant("auto")
+    assert redux.load().redux_resolved_variant(9, 0) == -2
