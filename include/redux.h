@@ -27,7 +27,7 @@
  *     by the stream; calls on different streams use different workspaces.
  *   - Determinism: for a given input, device, variant and launch parameters
  *     the result is bit-identical from call to call (partials are combined in
- *     a fixed order; no floating-point atomics).
+ *     a fixed order; no floating-point atomics unless "finish" = 3 is asked for).
  */
 #ifndef REDUX_H
 #define REDUX_H
