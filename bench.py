@@ -34,8 +34,8 @@ HBM_PEAK_GBPS = 8000.0
 # factor a plain copy kernel of known size reads on the same counters); see profiles/.
 # Keyed by (workload, variant actually run).  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("C3", "mfma"): 2147587147, ("C3", "classic"): 2147589909,     # profiles/redux_sum_f16_C3.md
-    ("C4", "mfma"): 1073831055, ("C4", "classic"): 1073839173,     # profiles/redux_sum_i8_C4.md
+    ("C3", "mfma"): 2147593438, ("C3", "classic"): 2147600392,     # profiles/redux_sum_f16_C3.md
+    ("C4", "mfma"): 1073853054, ("C4", "classic"): 1073842846,     # profiles/redux_sum_i8_C4.md
     ("C5", "mfma"): 537411811, ("C5", "classic"): 537421025,       # profiles/redux_sum_segmented_f16_C5.md
 }
 

@@ -221,6 +221,8 @@ int redux_resolved_variant(int dtype, int segmented);
  *   "max_grid"          1..16384 upper limit on the number of blocks (default 16384)
  *   "unroll"            0,1,2,4,8   16-byte loads in flight per lane; 0 = chosen from the size (default 0)
  *   "nontemporal"       0/1     use non-temporal (streaming) loads (default 1)
+ *   "stagger"           0..64   flat sum, blocks that run at least 32 loop iterations (256 MiB and up): wavefront w of a
+ *                               block starts w x stagger x 64 cycles late, worth 1-2 us per call (default 4)
  *   "rows_max_vec"      0..64   segmented sum, binary16 and int8, only where "seg_short" / "seg_ragged" do not apply:
  *                               segments of at most this many 16-byte vectors (and 16-byte aligned) take the
  *                               sixteen-segments-per-wavefront kernel; 0 = never (default 64)

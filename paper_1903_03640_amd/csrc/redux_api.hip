@@ -28,6 +28,7 @@ struct Settings {
     long layout = 2;
     long rows_max_vec = 64;       // short-segment kernel up to this many 16-byte vectors per segment (0 = off)
     long seg_parts = 0;           // 0 = pieces per long segment chosen from the shape
+    long stagger = 4;             // flat sum: wavefront w of a block starts w x stagger x 64 cycles late (long runs only)
     long seg_short_pipe = -1;     // that kernel: 1 = refill each register as soon as it is consumed, 0 = plain loop, -1 = measured best
     long seg_ragged = 1;          // use that kernel's ragged form for all other segments of up to 1008 bytes
     long seg_short = 1;           // use the contiguous-stream kernel for aligned power-of-two segments of 16 B .. 1 KiB
@@ -293,6 +294,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "max_grid")) { *lo = 1; *hi = kMaxGrid; return &g_set.max_grid; }
     if (!std::strcmp(name, "rows_max_vec")) { *lo = 0; *hi = 64; return &g_set.rows_max_vec; }
     if (!std::strcmp(name, "seg_block_bytes")) { *lo = 0; *hi = (long)1 << 40; return &g_set.seg_block_bytes; }
+    if (!std::strcmp(name, "stagger")) { *lo = 0; *hi = 64; return &g_set.stagger; }
     if (!std::strcmp(name, "seg_short_pipe")) { *lo = -1; *hi = 1; return &g_set.seg_short_pipe; }
     if (!std::strcmp(name, "seg_ragged")) { *lo = 0; *hi = 1; return &g_set.seg_ragged; }
     if (!std::strcmp(name, "seg_short")) { *lo = 0; *hi = 1; return &g_set.seg_short; }
@@ -514,6 +516,7 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
     a.out = out;
     a.max_chain = (unsigned)g_set.max_chain;
     a.layout = (int)g_set.layout;
+    a.stagger = (unsigned)g_set.stagger;
     a.finish = (int)g_set.finish;
 
     const FlatPlan plan = plan_flat(a.run.nvec, cus);
