@@ -8,7 +8,9 @@ Two parts:
 
 * ``redux_oracle.c`` -- the definition of the sum written out in plain C
   (binary64 serial / pairwise / Neumaier / exact 128-bit fixed point for
-  binary16 input, int64 for int8 input), loaded here through ctypes.
+  binary16 input, int64 for int8 input), loaded here through ctypes; plus a
+  many-core form of the same sums (contiguous chunks, one OpenMP thread each,
+  combined in chunk order) for timing the oracle on all host cores.
 * ``mma_reduction.py`` -- a numpy replay of the paper's own algorithm
   (Section IV-A: MMA against all-ones, then all-ones against the result,
   applied level by level), used to pin the encoding.
@@ -35,7 +37,7 @@ def build(force: bool = False) -> str:
     if force or stale:
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"]
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"]
         )
         os.replace(tmp, _LIB)
     return _LIB
@@ -73,6 +75,14 @@ def _load():
         lib.redux_oracle_sum_f8_exact.argtypes = [vp, c_sz, ctypes.c_int, c_ip, c_ip, ctypes.POINTER(ctypes.c_int)]
         lib.redux_oracle_sum_segmented_any.restype = ctypes.c_int
         lib.redux_oracle_sum_segmented_any.argtypes = [vp, c_sz, c_sz, ctypes.c_int, vp, vp]
+        lib.redux_oracle_max_threads.restype = ctypes.c_int
+        lib.redux_oracle_max_threads.argtypes = []
+        lib.redux_oracle_sum_f16_chunks.restype = ctypes.c_int
+        lib.redux_oracle_sum_f16_chunks.argtypes = [vp, c_sz, ctypes.c_int, c_dp, c_dp]
+        lib.redux_oracle_sum_i8_chunks.restype = ctypes.c_int
+        lib.redux_oracle_sum_i8_chunks.argtypes = [vp, c_sz, ctypes.c_int, c_ip, c_ip]
+        lib.redux_oracle_sum_segmented_f16_chunks.restype = ctypes.c_int
+        lib.redux_oracle_sum_segmented_f16_chunks.argtypes = [vp, c_sz, c_sz, ctypes.c_int, vp, vp]
         for name, argt in (("redux_oracle_bf16_decode", ctypes.c_uint16), ("redux_oracle_f32_decode", ctypes.c_uint32),
                            ("redux_oracle_f8e4m3_decode", ctypes.c_uint8), ("redux_oracle_f8e5m2_decode", ctypes.c_uint8)):
             fn = getattr(lib, name)
@@ -181,6 +191,45 @@ def sum_segmented_i8(x, nseg: int, seglen: int) -> Tuple[np.ndarray, np.ndarray]
     rc = _load().redux_oracle_sum_segmented_i8(_ptr(a), nseg, seglen, _ptr(s), _ptr(sa))
     if rc:
         raise RuntimeError("redux_oracle_sum_segmented_i8 failed: %d" % rc)
+    return s, sa
+
+
+# ---- many-core form: contiguous chunks, one OpenMP thread each, combined in chunk order ----------------------
+
+def max_threads() -> int:
+    """Threads the many-core form gets by default on this host (OMP_NUM_THREADS or the core count)."""
+    return int(_load().redux_oracle_max_threads())
+
+
+def sum_f16_chunks(x, chunks: int = 0) -> Tuple[float, float]:
+    """(sum, sum|x|): the array cut into `chunks` contiguous chunks (0 = max_threads()), each summed pairwise by
+    its own thread, chunk sums added in chunk order."""
+    a = _as_u16(x)
+    s, sa = ctypes.c_double(), ctypes.c_double()
+    rc = _load().redux_oracle_sum_f16_chunks(_ptr(a), a.size, chunks or max_threads(), ctypes.byref(s), ctypes.byref(sa))
+    if rc:
+        raise RuntimeError("redux_oracle_sum_f16_chunks failed: %d" % rc)
+    return s.value, sa.value
+
+
+def sum_i8_chunks(x, chunks: int = 0) -> Tuple[int, int]:
+    a = _as_i8(x)
+    s, sa = ctypes.c_int64(), ctypes.c_int64()
+    rc = _load().redux_oracle_sum_i8_chunks(_ptr(a), a.size, chunks or max_threads(), ctypes.byref(s), ctypes.byref(sa))
+    if rc:
+        raise RuntimeError("redux_oracle_sum_i8_chunks failed: %d" % rc)
+    return s.value, sa.value
+
+
+def sum_segmented_f16_chunks(x, nseg: int, seglen: int, chunks: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    a = _as_u16(x)
+    if a.size != nseg * seglen:
+        raise ValueError("size %d != nseg*seglen %d" % (a.size, nseg * seglen))
+    s = np.zeros(nseg, dtype=np.float64)
+    sa = np.zeros(nseg, dtype=np.float64)
+    rc = _load().redux_oracle_sum_segmented_f16_chunks(_ptr(a), nseg, seglen, chunks or max_threads(), _ptr(s), _ptr(sa))
+    if rc:
+        raise RuntimeError("redux_oracle_sum_segmented_f16_chunks failed: %d" % rc)
     return s, sa
 
 

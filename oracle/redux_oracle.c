@@ -1,5 +1,5 @@
 /*
- * redux_oracle.c -- plain, slow, single-threaded CPU oracle for the arithmetic
+ * redux_oracle.c -- plain, slow CPU oracle for the arithmetic
  * reduction R(X) = sum_{i=1..n} x_i (paper Section III, the definition of the
  * arithmetic reduction).
  *
@@ -18,8 +18,8 @@
  *
  *   binary16 input  -> every value is decoded exactly to binary64, then
  *       summed in binary64 four independent ways:
- *         serial   : one accumulator, left to right (the "simple loop with a
- *                    single accumulator" of Section III);
+ *         serial   : one accumulator, elements taken left to right (the
+ *                    sequential algorithm that Section III starts from);
  *         pairwise : recursive halving with a 128-element serial base case;
  *         neumaier : Kahan-Babuska compensated serial sum (compensated
  *                    summation is the remedy named in Section II);
@@ -42,11 +42,21 @@
  * reports their presence through *nonfinite and leaves them out of the
  * integer sum.
  *
- * Build: gcc -O2 -std=c11 -shared -fPIC -o libredux_oracle.so redux_oracle.c -lm
+ * Many-core form (the *_chunks routines): the array is cut into contiguous
+ * chunks, chunk t of T being elements [t*n/T, (t+1)*n/T); every chunk is summed
+ * by the single-threaded routine above (one OpenMP thread per chunk) and the
+ * chunk sums are added in chunk order, so the result depends on T but never on
+ * scheduling.  It exists so that the CPU baseline can be timed on all host cores.
+ *
+ * Build: gcc -O2 -std=c11 -fopenmp -shared -fPIC -o libredux_oracle.so redux_oracle.c -lm
+ * (without -fopenmp the chunks are summed one after the other, with the same result)
  */
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #define ORACLE_OK 0
 #define ORACLE_ERR_NULL (-1)
@@ -375,5 +385,86 @@ int redux_oracle_sum_segmented_any(const void *x, size_t nseg, size_t seglen, in
     if (dtype < ORACLE_BF16 || dtype > ORACLE_F8E5M2) return ORACLE_ERR_DTYPE;
     if ((nseg && seglen && !x) || (nseg && (!sum || !sum_abs))) return ORACLE_ERR_NULL;
     for (size_t s = 0; s < nseg; ++s) pairwise_any(x, s * seglen, seglen, dtype, &sum[s], &sum_abs[s]);
+    return ORACLE_OK;
+}
+
+/* ---- many-core form: contiguous chunks, one thread each, combined in chunk order ---------- */
+
+#define ORACLE_ERR_CHUNKS (-2)
+#define ORACLE_MAX_CHUNKS 4096
+
+/* Threads an OpenMP parallel region would get (1 when built without OpenMP). */
+int redux_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* first element of chunk t when n elements are cut into T chunks; chunk T starts at n */
+static size_t chunk_begin(size_t n, size_t t, size_t T)
+{
+    return (size_t)(((unsigned __int128)n * t) / T);
+}
+
+int redux_oracle_sum_f16_chunks(const uint16_t *x, size_t n, int chunks, double *sum, double *sum_abs)
+{
+    if ((n && !x) || !sum || !sum_abs) return ORACLE_ERR_NULL;
+    if (chunks < 1 || chunks > ORACLE_MAX_CHUNKS) return ORACLE_ERR_CHUNKS;
+    static double ps[ORACLE_MAX_CHUNKS], pa[ORACLE_MAX_CHUNKS];
+    const double *t = decode_table();       /* filled before the threads start */
+    const size_t T = (size_t)chunks;
+#pragma omp parallel for num_threads(chunks) schedule(static, 1)
+    for (int c = 0; c < chunks; ++c) {
+        const size_t lo = chunk_begin(n, (size_t)c, T), hi = chunk_begin(n, (size_t)c + 1, T);
+        pairwise(t, x + lo, hi - lo, &ps[c], &pa[c]);
+    }
+    double s = 0.0, a = 0.0;
+    for (int c = 0; c < chunks; ++c) {      /* chunk order, whatever order the threads finished in */
+        s += ps[c];
+        a += pa[c];
+    }
+    *sum = s;
+    *sum_abs = a;
+    return ORACLE_OK;
+}
+
+int redux_oracle_sum_i8_chunks(const int8_t *x, size_t n, int chunks, int64_t *sum, int64_t *sum_abs)
+{
+    if ((n && !x) || !sum || !sum_abs) return ORACLE_ERR_NULL;
+    if (chunks < 1 || chunks > ORACLE_MAX_CHUNKS) return ORACLE_ERR_CHUNKS;
+    static int64_t ps[ORACLE_MAX_CHUNKS], pa[ORACLE_MAX_CHUNKS];
+    const size_t T = (size_t)chunks;
+#pragma omp parallel for num_threads(chunks) schedule(static, 1)
+    for (int c = 0; c < chunks; ++c) {
+        const size_t lo = chunk_begin(n, (size_t)c, T), hi = chunk_begin(n, (size_t)c + 1, T);
+        (void)redux_oracle_sum_i8(x + lo, hi - lo, &ps[c], &pa[c]);
+    }
+    int64_t s = 0, a = 0;
+    for (int c = 0; c < chunks; ++c) {
+        s += ps[c];
+        a += pa[c];
+    }
+    *sum = s;
+    *sum_abs = a;
+    return ORACLE_OK;
+}
+
+/* Segmented: segments are independent, so chunk t takes segments [t*nseg/T, (t+1)*nseg/T) whole;
+ * every segment's sum is exactly the single-threaded one. */
+int redux_oracle_sum_segmented_f16_chunks(const uint16_t *x, size_t nseg, size_t seglen, int chunks,
+                                          double *sum, double *sum_abs)
+{
+    if ((nseg && seglen && !x) || (nseg && (!sum || !sum_abs))) return ORACLE_ERR_NULL;
+    if (chunks < 1 || chunks > ORACLE_MAX_CHUNKS) return ORACLE_ERR_CHUNKS;
+    const double *t = decode_table();
+    const size_t T = (size_t)chunks;
+#pragma omp parallel for num_threads(chunks) schedule(static, 1)
+    for (int c = 0; c < chunks; ++c) {
+        const size_t lo = chunk_begin(nseg, (size_t)c, T), hi = chunk_begin(nseg, (size_t)c + 1, T);
+        for (size_t sgm = lo; sgm < hi; ++sgm) pairwise(t, x + sgm * seglen, seglen, &sum[sgm], &sum_abs[sgm]);
+    }
     return ORACLE_OK;
 }

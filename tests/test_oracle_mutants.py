@@ -34,6 +34,10 @@ MUTANTS = [
      "if (n <= 128) {\n        double ss = 0.0, aa = 0.0;\n        for (size_t i = (n > 100); i < n; ++i) {\n            double v = t[x[i]];"),
     ("sum of |x| forgets the absolute value", "        double v = t[x[i]];\n        s += v;\n        a += fabs(v);\n    }\n    *sum = s;\n    *sum_abs = a;\n    return ORACLE_OK;\n}\n\nstatic void pairwise",
      "        double v = t[x[i]];\n        s += v;\n        a += v;\n    }\n    *sum = s;\n    *sum_abs = a;\n    return ORACLE_OK;\n}\n\nstatic void pairwise"),
+    ("chunks of n / T elements: the remainder is lost", "return (size_t)(((unsigned __int128)n * t) / T);", "return (n / T) * t;"),
+    ("chunk sums: last chunk left out", "for (int c = 0; c < chunks; ++c) {      /* chunk order, whatever order the threads finished in */",
+     "for (int c = 0; c + 1 < chunks + (chunks < 2); ++c) {      /* chunk order, whatever order the threads finished in */"),
+    ("int8 chunks start one element late", "(void)redux_oracle_sum_i8(x + lo, hi - lo, &ps[c], &pa[c]);", "(void)redux_oracle_sum_i8(x + lo + (lo > 0), hi - lo - (lo > 0), &ps[c], &pa[c]);"),
 ]
 
 

@@ -274,3 +274,84 @@ def test_extremes_do_not_overflow():
     assert oracle.sum_f16(x)[0] == 65504.0 * n
     x[::2] = -65504.0
     assert oracle.sum_f16(x) == (0.0, 65504.0 * n)
+
+
+# ---- many-core form: contiguous chunks, one thread each, combined in chunk order ---------------------------
+
+CHUNKS = [1, 2, 3, 7, 8, 64, 1000]
+
+
+@pytest.mark.parametrize("chunks", CHUNKS)
+def test_chunked_closed_forms_are_exact(chunks):
+    """Closed forms whose every partial sum is representable: the chunked sums must be exact, and equal to the
+    128-bit fixed-point sum."""
+    for n in (0, 1, 5, 63, 1000, (1 << 20) + 3):
+        ones = np.ones(n, dtype=np.float16)
+        assert oracle.sum_f16_chunks(ones, chunks) == (float(n), float(n))
+        ramp = ((np.arange(n) % 2048) + 1).astype(np.float16)                  # sum 1..k, all exact in binary16
+        q, r = divmod(n, 2048)
+        want = q * 2048 * 2049 // 2 + r * (r + 1) // 2
+        assert oracle.sum_f16_chunks(ramp, chunks)[0] == float(want)
+        assert oracle.sum_f16_chunks(ramp, chunks)[0] == oracle.sum_f16_exact(ramp)[0]
+        alt = np.where(np.arange(n) % 2 == 0, 1.5, -1.5).astype(np.float16)
+        assert oracle.sum_f16_chunks(alt, chunks) == (1.5 * (n % 2), 1.5 * n)
+        i8 = ((np.arange(n) % 256) - 128).astype(np.int8)
+        assert oracle.sum_i8_chunks(i8, chunks) == oracle.sum_i8(i8)
+        assert oracle.sum_i8_chunks(np.full(n, -128, dtype=np.int8), chunks) == (-128 * n, 128 * n)
+
+
+@pytest.mark.parametrize("chunks", CHUNKS)
+def test_chunks_tile_the_array(chunks):
+    """A single non-zero element at every position: a chunk boundary that drops or repeats an element shows."""
+    for n in (1, 2, 7, 64, 129, 1001):
+        x = np.zeros(n, dtype=np.float16)
+        xi = np.zeros(n, dtype=np.int8)
+        for i in range(n):
+            x[i], xi[i] = 3.0, -7
+            assert oracle.sum_f16_chunks(x, chunks) == (3.0, 3.0), (n, i)
+            assert oracle.sum_i8_chunks(xi, chunks) == (-7, 7), (n, i)
+            x[i], xi[i] = 0.0, 0
+
+
+@pytest.mark.parametrize("chunks", CHUNKS)
+def test_chunked_sum_agrees_with_single_thread_and_exact(chunks):
+    rng = np.random.default_rng(chunks)
+    for n in (10, 1000, 100003, (1 << 21) + 17):
+        for x in (rng.random(n).astype(np.float16), rng.standard_normal(n).astype(np.float16),
+                  (rng.standard_normal(n) * 1000).astype(np.float16)):
+            s, a = oracle.sum_f16_chunks(x, chunks)
+            s1, a1 = oracle.sum_f16(x)
+            se, ae = oracle.sum_f16_exact(x)[:2]
+            assert abs(s - s1) <= 2 * ulp64(a1) and abs(a - a1) <= 2 * ulp64(a1)
+            assert abs(s - se) <= 2 * ulp64(ae) and abs(a - ae) <= 2 * ulp64(ae)
+        xi = rng.integers(-128, 128, n, dtype=np.int8)
+        assert oracle.sum_i8_chunks(xi, chunks) == (int(xi.astype(np.int64).sum()), int(np.abs(xi.astype(np.int64)).sum()))
+
+
+def test_chunked_sum_brute_force_against_fractions():
+    rng = np.random.default_rng(5)
+    for n in (1, 2, 3, 17, 64):
+        x = (rng.standard_normal(n) * 8).astype(np.float16)
+        want = sum(frac_of_f16(x), Fraction(0))
+        for chunks in (1, 2, 5, 64, 100):
+            assert Fraction(oracle.sum_f16_chunks(x, chunks)[0]) == want       # small sums of binary16 are exact in binary64
+
+
+@pytest.mark.parametrize("chunks", [1, 3, 8, 50])
+def test_chunked_segmented_equals_single_thread(chunks):
+    rng = np.random.default_rng(9)
+    for nseg, seglen in ((1, 10), (7, 1), (33, 129), (100, 1000), (5, 0)):
+        x = rng.standard_normal(nseg * seglen).astype(np.float16)
+        s, a = oracle.sum_segmented_f16_chunks(x, nseg, seglen, chunks)
+        s1, a1 = oracle.sum_segmented_f16(x, nseg, seglen)
+        assert np.array_equal(s, s1) and np.array_equal(a, a1)
+
+
+def test_chunk_count_is_checked_and_default_uses_every_thread():
+    x = np.ones(100, dtype=np.float16)
+    assert oracle.max_threads() >= 1
+    assert oracle.sum_f16_chunks(x) == (100.0, 100.0)
+    with pytest.raises(RuntimeError):
+        oracle.sum_f16_chunks(x, 5000)
+    with pytest.raises(RuntimeError):
+        oracle.sum_i8_chunks(np.ones(3, dtype=np.int8), -1)
