@@ -24,7 +24,11 @@
  *     counter, < 128 KiB) per (device, stream); it is created by the first
  *     call on that stream (one hipMalloc, so not during stream capture) and
  *     released by redux_shutdown().  Two calls on the same stream are ordered
- *     by the stream; calls on different streams use different workspaces.
+ *     by the stream; calls on different streams use different workspaces, and host threads
+ *     calling on different streams do not wait for each other's launches.
+ *   - HIP graphs: a captured call holds the addresses of the library's buffers as they were at capture.
+ *     They stay valid until redux_shutdown(); a graph captured before redux_shutdown() must not be
+ *     replayed after it (capture it again).
  *   - Determinism: for a given input, device, variant and launch parameters
  *     the result is bit-identical from call to call (partials are combined in
  *     a fixed order; no floating-point atomics unless "finish" = 3 is asked for).
@@ -63,8 +67,9 @@ typedef enum {
 
 /* Which kernel family computes the sum. */
 typedef enum {
-    REDUX_VARIANT_AUTO    = 0, /* the family that measured faster: CLASSIC for redux_sum (by about 1 %), MFMA for
-                                  redux_sum_segmented -- except CLASSIC for the 8-bit floats, whose MFMAs drop bits */
+    REDUX_VARIANT_AUTO    = 0, /* MFMA (as fast as CLASSIC on the flat sum, with the vector ALU idle; faster on segmented
+                                  sums) -- except CLASSIC for the 8-bit floats, whose MFMAs drop bits, and for the flat
+                                  sum of binary32, whose MMA needs four MFMAs per load and measures 5 % slower */
     REDUX_VARIANT_MFMA    = 1, /* MMA encoding: data tile x all-ones, accumulator chained through C   */
     REDUX_VARIANT_CLASSIC = 2  /* per-lane serial accumulation + wavefront tree (Section III)         */
 } redux_variant;
@@ -107,9 +112,10 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
  * The kernel is chosen from (nseg, seglen, alignment); redux_plan_sum_segmented reports the choice.
  * Segments of up to 1 KiB (aligned powers of two: 4 KiB) are read as one contiguous stream, a group of 2^k lanes
  * per segment, and the constant operands of the two MMAs become 0/1 selection matrices, so that one MMA pair yields
- * many sums; otherwise one wavefront takes one segment (first MMA chained over its tiles, second MMA to fold the
- * rows), with a leaner form for aligned segments of exactly 1, 2, 4 or 8 KiB; segments of 32 KiB and more take a
- * whole block each; a few long segments are cut into pieces whose totals (in the workspace) a second kernel adds
+ * many sums; longer segments are taken a run of up to sixteen at a time by one wavefront, which streams the run as
+ * one contiguous piece of memory (first MMA with a one-column selector per segment, issued twice for a load that
+ * holds a segment boundary; second MMA to fold the rows of all columns at once), with a leaner form for aligned
+ * segments of exactly 1, 2, 4 or 8 KiB; segments of 32 KiB and more take a whole block each; a few long segments are cut into pieces whose totals (in the workspace) a second kernel adds
  * per segment.
  *
  * Reads outside x: segments that do not start or end on a 16-byte boundary are read as the 16-byte aligned vectors
@@ -134,7 +140,8 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
  *   levels   host pointer or NULL; receives the number of levels (= kernel launches); 0 for n == 0.
  *
  * The arrays of partial sums (n/256 and n/65536 entries) are library-owned per (device, stream) and grow
- * on demand (hipMalloc; a larger request frees the old buffer first, which waits for the device).
+ * on demand (hipMalloc, so not during stream capture; an outgrown buffer is kept until redux_shutdown, because a
+ * captured graph may still hold its address).
  * This entry point exists to measure the algorithm as published against redux_sum, which chains the
  * accumulator through C and makes one pass; it is not the fast path.
  */
@@ -182,8 +189,11 @@ typedef enum {
                                 binary32: ... 4096 bytes): the array is
                                 read as one contiguous stream and 0/1 selection matrices in the two MMAs (or a
                                 shortened lane butterfly) yield every segment's sum */
-    REDUX_KERNEL_RAGGED = 7  /* redux_sum_segmented, any other segment of up to 1008 bytes: the same kernel, each group
+    REDUX_KERNEL_RAGGED = 7, /* redux_sum_segmented, any other segment of up to 1008 bytes: the same kernel, each group
                                 of `vectors` lanes reading the aligned vectors that overlap its segment */
+    REDUX_KERNEL_RUNS   = 8  /* redux_sum_segmented, segments from 1009 to 7999 bytes of any length and alignment: one
+                                wavefront streams a run of `vectors` (1 .. 16) consecutive whole segments, every lane of
+                                every load busy; each segment of the run owns one column of the MMA accumulator */
 } redux_kernel;
 
 typedef struct {
@@ -196,6 +206,8 @@ typedef struct {
     unsigned head;     /* FLAT: elements before the first 16-byte aligned vector */
     unsigned tail;     /* FLAT: elements after the last whole vector */
     uint64_t vectors;  /* FLAT: whole 16-byte vectors; ROWS: vectors per segment */
+    unsigned chain;    /* loop iterations between folds of the MMA accumulators: "max_chain", lowered for int8 so that
+                          no int32 accumulator can pass 2^31 whatever the input holds */
 } redux_plan;
 
 int redux_plan_sum(size_t n, int dtype, uintptr_t x_address, int compute_units, redux_plan *plan);
@@ -221,6 +233,9 @@ int redux_resolved_variant(int dtype, int segmented);
  *   "max_grid"          1..16384 upper limit on the number of blocks (default 16384)
  *   "unroll"            0,1,2,4,8   16-byte loads in flight per lane; 0 = chosen from the size (default 0)
  *   "nontemporal"       0/1     use non-temporal (streaming) loads (default 1)
+ *   "pause"             -1..64  flat sum: every loop iteration of a wavefront ends with this many 64-cycle sleeps;
+ *                               -1 = the measured best (8 for the MMA family on binary16, bfloat16 and int8 runs of
+ *                               512 MiB and more, else 0) (default -1)
  *   "stagger"           0..64   flat sum, blocks that run at least 32 loop iterations (256 MiB and up): wavefront w of a
  *                               block starts w x stagger x 64 cycles late, worth 1-2 us per call (default 4)
  *   "rows_max_vec"      0..64   segmented sum, binary16 and int8, only where "seg_short" / "seg_ragged" do not apply:
@@ -232,6 +247,14 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               with the MMA family, binary32 excepted) take the contiguous-stream kernel (default 1)
  *   "seg_ragged"        0/1     segmented sum: every other segment of up to 1008 bytes takes that kernel's ragged form
  *                               (default 1)
+ *   "seg_runs"          0/1     segmented sum: segments of more than 1008 and at most "seg_runs_max" bytes (and less than
+ *                               "seg_block_bytes") that are not cut into pieces take the run-of-segments kernel; 0 = one
+ *                               wavefront per segment instead (default 1)
+ *   "seg_runs_max"      1009..2^18  largest segment in bytes that kernel takes (default 7999: measured, from 8000 bytes
+ *                               on one wavefront per segment is faster)
+ *   "seg_run_len"       0..16   that kernel: segments per run; 0 = the length with the most bytes per cost (iterations, of
+ *                               which the last is partly idle, plus a fixed cost per run) on a grid whose last round
+ *                               of runs is as full as possible (default 0)
  *   "seg_short_pipe"    -1,0,1  that kernel: 1 = every register is reloaded from the block's next 32 KiB as soon as it has
  *                               been consumed, 0 = plain load-then-work loop, -1 = the measured best for the shape (default -1)
  *   "seg_tiles"         0/1     segmented sum: 16-byte aligned segments of exactly 1, 2, 4 or 8 KiB, at least
@@ -246,16 +269,19 @@ int redux_resolved_variant(int dtype, int segmented);
  *   "layout"            0..2    which part of the array a block reads: 0 = blocks interleaved over the
  *                               whole array, 1 = one contiguous share per block, 2 = one contiguous
  *                               eighth per accelerator die, interleaved among that die's blocks (default 2)
- *   "finish"            -1..3   how block partials become the result: 0/1 = the block that arrives last
+ *   "finish"            -1..4   how block partials become the result: 0/1/4 = the block that arrives last
  *                               sums them in the same kernel (0: acquire+release on every block's ticket,
- *                               1: release only, acquire in the last block), 2 = a second one-block kernel
+ *                               1: release only, acquire in the last block, 4: no release fence at all -- the
+ *                               partial is published by a device-scope atomic exchange whose completion the
+ *                               ticket waits for), 2 = a second one-block kernel
  *                               on the same stream, 3 = every block adds its total to the result atomically
  *                               (the atomic scheme of Section II, for comparison: a fill kernel clears the
  *                               result first, and floating-point results then depend on the order of arrival
- *                               in their last bits), -1 = 1 or 2, chosen from the input size (default -1)
+ *                               in their last bits), -1 = the measured best for the input size (default -1)
  *   "max_chain"         1..65536 loop iterations between folds of the MMA accumulators into the wide
- *                               per-wavefront total (bounds binary32 chain length; keeps int32
- *                               accumulators below 2^31 for any input)
+ *                               per-wavefront total (bounds binary32 chain length).  For int8 the library lowers
+ *                               it where needed so that an int32 accumulator stays below 2^31 for any input
+ *                               (redux_plan.chain reports the value used)
  * Returns REDUX_ERR_PARAM for an unknown name or a value out of range.
  */
 int redux_set_param(const char *name, long value);

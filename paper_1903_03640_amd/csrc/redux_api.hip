@@ -4,6 +4,7 @@
 #include "redux_kernels.h"
 #include "redux_literal.h"
 #include "redux_short.h"
+#include "redux_runs.h"
 
 #include <climits>
 #include <cstdlib>
@@ -11,6 +12,7 @@
 #include <map>
 #include <mutex>
 #include <utility>
+#include <vector>
 
 using namespace redux;
 
@@ -33,11 +35,15 @@ struct Settings {
     long seg_ragged = 1;          // use that kernel's ragged form for all other segments of up to 1008 bytes
     long seg_short = 1;           // use the contiguous-stream kernel for aligned power-of-two segments of 16 B .. 1 KiB
     long seg_tiles = 1;           // use the pipelined kernel for segments of 1, 2, 4 or 8 whole tiles
+    long seg_runs = 1;            // use the run-of-segments kernel for segments above 1008 bytes that are not cut into pieces
+    long seg_run_len = 0;         // segments per run (0 = from the shape)
+    long seg_runs_max = 7999;     // largest segment (bytes) that kernel takes
     long seg_block_bytes = 32768; // segments of at least this many bytes take one block each (0 = never)
     long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
     long lit_blocks_per_cu = 0;
     long lit_m = 16;              // linear size m of the MMA matrices of the level-by-level form
     long finish = -1;             // -1 = from the input size
+    long pause = -1;              // flat sum: 64-cycle sleeps at the end of every loop iteration (-1 = measured best)
 };
 Settings g_set;
 std::once_flag g_env_once;
@@ -114,20 +120,24 @@ struct LevelBuffers {
 };
 std::map<std::pair<int, hipStream_t>, LevelBuffers> g_levels;
 
+// Buffers that were outgrown.  A captured graph holds the addresses that were current when it was captured, so nothing
+// is freed (and the device is never waited for) before redux_shutdown.
+std::vector<void *> g_retired;
+
 int get_level_buffers(int dev, hipStream_t st, size_t bytes0, size_t bytes1, LevelBuffers *out)
 {
     LevelBuffers &lb = g_levels[std::make_pair(dev, st)];
     const size_t want[2] = {bytes0, bytes1};
     for (int i = 0; i < 2; ++i) {
         if (lb.bytes[i] >= want[i]) continue;
-        if (lb.buf[i]) (void)hipFree(lb.buf[i]);          // waits for work that may still use it
-        lb.buf[i] = nullptr;
-        lb.bytes[i] = 0;
+        // at least double, so that a slowly growing input retires a bounded total (less than the final size)
+        const size_t bytes = want[i] > 2 * lb.bytes[i] ? want[i] : 2 * lb.bytes[i];
         void *p = nullptr;
-        hipError_t e = hipMalloc(&p, want[i]);
+        hipError_t e = hipMalloc(&p, bytes);
         if (e != hipSuccess) return hip_fail(e, REDUX_ERR_NOMEM);
+        if (lb.buf[i]) g_retired.push_back(lb.buf[i]);
         lb.buf[i] = p;
-        lb.bytes[i] = want[i];
+        lb.bytes[i] = bytes;
     }
     *out = lb;
     return REDUX_OK;
@@ -268,18 +278,21 @@ void with_short_family(int dtype, Fn &&fn)
 }
 
 // The family a call runs with.  `flat`: redux_sum (otherwise redux_sum_segmented).
-int effective_variant(int dtype, bool flat = false)
+int effective_variant(const Settings &S, int dtype, bool flat = false)
 {
-    int v = g_set.variant;
+    int v = S.variant;
     if (v != REDUX_VARIANT_AUTO) return v;
-    // Measured on the 1-2 GiB flat sums: the classic family is 0.7-1.4 % faster (289.6 vs 292.2 us on 2 GiB of binary16,
-    // 144.5 vs 145.5 us on 1 GiB of int8; the same sign on every machine tried).  Segmented sums: the MMA family is as
-    // fast (8 KiB segments) or 5-30 % faster (short and ragged segments).
-    if (flat) return REDUX_VARIANT_CLASSIC;
     // The 8-bit floating-point MFMAs align the eight products of a lane to the largest of them and keep
     // only 14 bits below it (measured), so small terms next to a large one are dropped: up to
     // 7 * 2^-14 of sum|x|, above the 1e-4 this library promises.  Their default is the classic family.
     if (dtype == REDUX_F8E4M3 || dtype == REDUX_F8E5M2) return REDUX_VARIANT_CLASSIC;
+    // Everything else: the MMA family.  Flat sums of 1-2 GiB: both families move the same bytes in the same time
+    // (interleaved runs of 100 calls: 289.8 +- 0.4 against 289.2 +- 0.3 us on 2 GiB of binary16), so the tie goes to the
+    // family that keeps the vector ALU idle (2.9 % against 21.5 % busy); after an idle period the MMA family is also
+    // 3 % faster for the first forty calls (294 against 304 us).  Segmented sums: as fast (8 KiB segments) or 5-30 %
+    // faster (short and ragged segments).  Binary32 flat sums are the exception: its MMA takes four K-slices, hence four
+    // 8-pass MFMAs, per 16-byte load, and measures 5 % behind the classic family (306 against 290 us on 2 GiB).
+    if (flat && dtype == REDUX_F32) return REDUX_VARIANT_CLASSIC;
     return REDUX_VARIANT_MFMA;
 }
 
@@ -298,29 +311,48 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "seg_short_pipe")) { *lo = -1; *hi = 1; return &g_set.seg_short_pipe; }
     if (!std::strcmp(name, "seg_ragged")) { *lo = 0; *hi = 1; return &g_set.seg_ragged; }
     if (!std::strcmp(name, "seg_short")) { *lo = 0; *hi = 1; return &g_set.seg_short; }
+    if (!std::strcmp(name, "seg_runs")) { *lo = 0; *hi = 1; return &g_set.seg_runs; }
+    if (!std::strcmp(name, "seg_runs_max")) { *lo = 1009; *hi = 1 << 18; return &g_set.seg_runs_max; }
+    if (!std::strcmp(name, "seg_run_len")) { *lo = 0; *hi = 16; return &g_set.seg_run_len; }
     if (!std::strcmp(name, "seg_tiles")) { *lo = 0; *hi = 1; return &g_set.seg_tiles; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
     if (!std::strcmp(name, "lit_m")) { *lo = 4; *hi = 32; return &g_set.lit_m; }
     if (!std::strcmp(name, "lit_unroll")) { *lo = 0; *hi = 16; return &g_set.lit_unroll; }
     if (!std::strcmp(name, "lit_blocks_per_cu")) { *lo = 0; *hi = 16; return &g_set.lit_blocks_per_cu; }
     if (!std::strcmp(name, "layout")) { *lo = 0; *hi = 2; return &g_set.layout; }
-    if (!std::strcmp(name, "finish")) { *lo = -1; *hi = 3; return &g_set.finish; }
+    if (!std::strcmp(name, "pause")) { *lo = -1; *hi = 64; return &g_set.pause; }
+    if (!std::strcmp(name, "finish")) { *lo = -1; *hi = 4; return &g_set.finish; }
     return nullptr;
 }
 
 // ---- launch plans: pure host arithmetic, shared by the entry points and by redux_plan_* ---------------------
-struct FlatPlan { int unroll; unsigned grid; int finish; };
+struct FlatPlan { int unroll; unsigned grid; int finish; unsigned chain; unsigned pause; };
 
 // Launch shape of the flat sum.  Measured on MI355X: read bandwidth peaks with about 8 MiB in flight
 // (one 256-thread block per compute unit, eight 16-byte loads per lane) and drops by several percent
 // when more blocks are resident.  Small inputs keep the deep unroll as long as that leaves 64 blocks.
-FlatPlan plan_flat(u64 nvec, int cus)
+// Loop iterations between folds of the MMA accumulators into the wide per-wavefront total: the "max_chain" setting, lowered
+// for int8 where an int32 accumulator could otherwise pass 2^31.  One int8 MFMA adds at most 64 x 128 = 2^13 in magnitude to an
+// accumulator entry and an iteration issues `unroll` of them over `chains` accumulators; the classic family adds at most
+// 4 x 128 = 2^9 per running sum per 16-byte vector.
+unsigned chain_length(const Settings &S, int dtype, bool mfma, int unroll, int chains)
+{
+    u64 chain = (u64)S.max_chain;
+    if (dtype == REDUX_I8) {
+        const u64 per_iter = mfma ? (u64)8192 * (u64)((unroll + chains - 1) / chains) : (u64)512 * (u64)unroll;
+        const u64 cap = (((u64)1 << 31) - 1) / per_iter;
+        if (chain > cap) chain = cap;
+    }
+    return (unsigned)chain;
+}
+
+FlatPlan plan_flat(const Settings &S, u64 nvec, int cus, int dtype)
 {
     FlatPlan p;
-    u64 gmax = (u64)cus * (u64)g_set.blocks_per_cu;
-    if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+    u64 gmax = (u64)cus * (u64)S.blocks_per_cu;
+    if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
     if (gmax < 1) gmax = 1;
-    p.unroll = (int)g_set.unroll;
+    p.unroll = (int)S.unroll;
     if (p.unroll == 0) {
         const u64 want = gmax < 64 ? gmax : 64;
         p.unroll = 8;
@@ -328,11 +360,23 @@ FlatPlan plan_flat(u64 nvec, int cus)
     }
     const u64 nslab = nvec / ((u64)kBlock * p.unroll);
     p.grid = (unsigned)(nslab < 1 ? 1 : (nslab < gmax ? nslab : gmax));
-    // Measured (us per call, 64 / 128 / 256 blocks): finishing inside the kernel -- a device-wide release per block --
-    // takes 4.8 / 6.3 / 9.2 at 2 / 4 / 8 MiB and stays 2.7 us (large inputs: 7 us) behind a second one-block kernel,
-    // which takes 6.4 flat up to 16 MiB (two launches back to back).  So up to 4 MiB the same kernel finishes.
-    p.finish = (int)g_set.finish;
-    if (p.finish < 0) p.finish = nvec > ((u64)4 << 20) / 16 ? 2 : 1;
+    // Measured (us per whole call; 64 / 128 / 256 blocks at 2 / 4 / 8 MiB): finishing inside the kernel, every block
+    // publishing its partial with an atomic exchange and drawing a ticket (finish 4), takes 4.7 / 5.9 / 8.2 and a second
+    // one-block kernel (finish 2) 6.3 / 6.7 / 6.7: up to 4 MiB the same kernel finishes.  From 8 to 128 MiB all 256
+    // blocks arrive within a microsecond and their 512 read-modify-writes queue up (9.5 against 7.1 at 16 MiB, 24.5
+    // against 22.7 at 128 MiB), so the second kernel finishes.  From 256 MiB on the arrivals are spread out and both
+    // cost the same (40.3, 76.3, 148.0, 291.5 at 256 MiB ... 2 GiB): one kernel per call it is.
+    p.finish = (int)S.finish;
+    if (p.finish < 0) p.finish = (nvec <= ((u64)4 << 20) / 16 || nvec >= ((u64)256 << 20) / 16) ? 4 : 2;
+    const bool mfma = effective_variant(S, dtype, true) == REDUX_VARIANT_MFMA;
+    p.chain = chain_length(S, dtype, mfma, p.unroll, 4);
+    // Measured on 0.5 - 4 GiB of binary16, bfloat16 and int8: a wavefront of the MMA family that sleeps about 500 cycles
+    // between its last MMA and its next eight loads finishes the call 0.5 - 1.5 % earlier (2 GiB: 290.4 against 293.1 us),
+    // level with the classic family, whose conversions and additions take about as long.  Eight loads per lane on every
+    // compute unit are slightly more than the memory system needs in flight; the sleep shortens its queues.  Runs of
+    // 256 MiB and less gain nothing or lose, and binary32 (four MMAs per load) and the 8-bit floats (two) lose.
+    const bool one_mma_per_load = dtype == REDUX_F16 || dtype == REDUX_BF16 || dtype == REDUX_I8;
+    p.pause = S.pause >= 0 ? (unsigned)S.pause : (mfma && one_mma_per_load && nslab / p.grid >= 64 ? 8u : 0u);
     return p;
 }
 
@@ -342,9 +386,10 @@ struct SegPlan {
     unsigned grid;
     u64 parts, part_len; // pieces per segment and elements per piece (parts == 1: the whole segment)
     unsigned nvec;       // short, rows: 16-byte vectors per segment; ragged: lanes per segment
+    unsigned chain;      // loop iterations between folds (the kernels that loop over a segment)
 };
 
-SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_addr, int cus)
+SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_addr, int cus)
 {
     SegPlan p;
     p.parts = 1;
@@ -353,16 +398,16 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
     const u64 seg_bytes = seglen * es;
     // aligned power-of-two segments of 16 B .. 1 KiB (4 KiB): read as one contiguous stream, 0/1 selection matrices in the MMAs
     // (measured: with the MMA family also 2 KiB, +7 %, and 4 KiB, +3 %, against one wavefront per segment; 8 KiB is slower)
-    const u64 short_limit = effective_variant(dtype) == REDUX_VARIANT_MFMA && dtype != REDUX_F32 ? 4096 : 1024;
-    if (g_set.seg_short && x_addr % 16 == 0 && seg_bytes >= 16 && seg_bytes <= short_limit && (seg_bytes & (seg_bytes - 1)) == 0) {
+    const u64 short_limit = effective_variant(S, dtype) == REDUX_VARIANT_MFMA && dtype != REDUX_F32 ? 4096 : 1024;
+    if (S.seg_short && x_addr % 16 == 0 && seg_bytes >= 16 && seg_bytes <= short_limit && (seg_bytes & (seg_bytes - 1)) == 0) {
         p.kernel = REDUX_KERNEL_SHORT;
         p.nvec = (unsigned)(seg_bytes / 16);
         p.unroll = kShortLoads;
         const u64 nslab = (nseg * p.nvec + kShortSlab - 1) / kShortSlab;
         // measured: one block per compute unit for the MMA family, two for the classic one (its conversions are longer)
-        const long best_bpc = effective_variant(dtype) == REDUX_VARIANT_MFMA ? 1 : 2;
-        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : best_bpc);
-        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        const long best_bpc = effective_variant(S, dtype) == REDUX_VARIANT_MFMA ? 1 : 2;
+        u64 gmax = (u64)cus * (u64)(S.seg_blocks_per_cu ? S.seg_blocks_per_cu : best_bpc);
+        if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
         if (gmax < 1) gmax = 1;
         p.grid = (unsigned)(nslab < gmax ? nslab : gmax);
         return p;
@@ -370,9 +415,10 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
     // short segments: sixteen per wavefront, one per row of the A operand
     // (only when the ragged form below is switched off: measured, that form is as fast or faster at every size)
     const auto ragged_lanes = [](u64 cover) { u64 l = 1; while (l < cover) l *= 2; return l; };
-    const bool ragged_fit = g_set.seg_ragged && seg_bytes <= 1008 && nseg <= ((u64)1 << 56);
-    if (!ragged_fit && (dtype == REDUX_F16 || dtype == REDUX_I8) && g_set.rows_max_vec > 0 && seg_bytes % 16 == 0 &&
-        x_addr % 16 == 0 && seg_bytes / 16 <= (u64)g_set.rows_max_vec) {
+    const bool runs_fit = S.seg_runs && seg_bytes > 1008 && seg_bytes <= (u64)S.seg_runs_max;
+    const bool ragged_fit = S.seg_ragged && seg_bytes <= 1008 && nseg <= ((u64)1 << 56);
+    if (!ragged_fit && (dtype == REDUX_F16 || dtype == REDUX_I8) && S.rows_max_vec > 0 && seg_bytes % 16 == 0 &&
+        x_addr % 16 == 0 && seg_bytes / 16 <= (u64)S.rows_max_vec) {
         p.kernel = REDUX_KERNEL_ROWS;
         p.nvec = (unsigned)(seg_bytes / 16);
         const unsigned steps = (p.nvec + 3) / 4;
@@ -380,8 +426,8 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         const u64 groups_per_iter = 8 / p.unroll;
         const u64 nsuper = ((nseg + 15) / 16 + groups_per_iter - 1) / groups_per_iter;
         u64 blocks = (nsuper + kWaves - 1) / kWaves;
-        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 2);   // measured best
-        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        u64 gmax = (u64)cus * (u64)(S.seg_blocks_per_cu ? S.seg_blocks_per_cu : 2);   // measured best
+        if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
         if (gmax < 1) gmax = 1;
         p.grid = (unsigned)(blocks < gmax ? blocks : gmax);
         return p;
@@ -399,45 +445,51 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         p.nvec = (unsigned)ragged_lanes(cover);
         p.unroll = kShortLoads;
         const u64 nslab = (nseg * p.nvec + kShortSlab - 1) / kShortSlab;
-        // measured: the address and mask arithmetic per load wants more wavefronts per compute unit than the aligned form
-        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : 8);
-        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        // measured (offsets and masks are worked out once per lane, so a load costs what it costs in the aligned form):
+        // one block per compute unit when most lanes of a group hold data (400 B: 7.0 TB/s, 750 B - 1 KB: 7.1), two when
+        // about half of them idle (520 B, 33 of 64 lanes: 6.8 against 5.7) or the groups are small; the classic family,
+        // whose lanes also convert and add, one block more
+        const bool full = cover * 10 >= (u64)p.nvec * 7 && p.nvec >= 32;
+        const long best_bpc = effective_variant(S, dtype) == REDUX_VARIANT_MFMA ? (full ? 1 : 2)
+                                                                                : (cover * 10 >= (u64)p.nvec * 7 ? 2 : 3);
+        u64 gmax = (u64)cus * (u64)(S.seg_blocks_per_cu ? S.seg_blocks_per_cu : best_bpc);
+        if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
         if (gmax < 1) gmax = 1;
         p.grid = (unsigned)(nslab < gmax ? nslab : gmax);
         return p;
     }
     // segments of exactly 1, 2, 4 or 8 whole tiles, enough of them to fill the chip: the pipelined kernel
-    if (g_set.seg_tiles && x_addr % 16 == 0 && seg_bytes % 1024 == 0 && seg_bytes <= 8192 &&
+    if (S.seg_tiles && x_addr % 16 == 0 && seg_bytes % 1024 == 0 && seg_bytes <= 8192 &&
         ((seg_bytes / 1024) & (seg_bytes / 1024 - 1)) == 0 && nseg >= (u64)cus * kWaves) {
         p.kernel = REDUX_KERNEL_TILES;
         p.unroll = (int)(seg_bytes / 1024);
         u64 blocks = (nseg + kWaves - 1) / kWaves;
         const long best_bpc = p.unroll == 8 ? 1 : p.unroll == 4 ? 2 : p.unroll == 2 ? 3 : 8;   // measured on MI355X
-        u64 gmax = (u64)cus * (u64)(g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : best_bpc);
-        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        u64 gmax = (u64)cus * (u64)(S.seg_blocks_per_cu ? S.seg_blocks_per_cu : best_bpc);
+        if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
         if (gmax < 1) gmax = 1;
         p.grid = (unsigned)(blocks < gmax ? blocks : gmax);
         return p;
     }
     // long segments (32 KiB and up): one block per segment, cut into pieces of at least 32 KiB while there are
     // fewer than two pieces per compute unit, as far as the workspace allows
-    if (g_set.seg_block_bytes > 0 && seg_bytes >= (u64)g_set.seg_block_bytes) {
+    if (S.seg_block_bytes > 0 && seg_bytes >= (u64)S.seg_block_bytes) {
         const u64 want_blocks = (u64)cus * 2;
         u64 parts = 1;
-        if (g_set.seg_parts > 0) parts = (u64)g_set.seg_parts;
+        if (S.seg_parts > 0) parts = (u64)S.seg_parts;
         else while (nseg * parts < want_blocks && nseg * parts * 2 <= (u64)kMaxGrid && seg_bytes / (parts * 2) >= 32768) parts *= 2;
         if (parts > 1 && nseg <= (u64)kMaxGrid / parts) {
             p.parts = parts;
             p.part_len = ((seglen + parts - 1) / parts + 511) / 512 * 512;
         }
         p.kernel = REDUX_KERNEL_BLOCK;
-        p.unroll = (int)g_set.unroll;
+        p.unroll = (int)S.unroll;
         if (p.unroll == 0) p.unroll = 8;
         // measured: two blocks per compute unit hide the per-piece fold for pieces below 512 KiB
-        const long bpc = g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : (p.part_len * es >= ((u64)512 << 10) ? 1 : 2);
+        const long bpc = S.seg_blocks_per_cu ? S.seg_blocks_per_cu : (p.part_len * es >= ((u64)512 << 10) ? 1 : 2);
         const u64 blocks_needed = nseg * p.parts;
         u64 gmax = (u64)cus * (u64)bpc;
-        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
         if (gmax < 1) gmax = 1;
         p.grid = (unsigned)(blocks_needed < gmax ? blocks_needed : gmax);
         return p;
@@ -447,7 +499,7 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
     // compute unit, as far as the workspace allows.
     const u64 want_waves = (u64)cus * 8;
     u64 parts = 1;
-    if (g_set.seg_parts > 0) parts = (u64)g_set.seg_parts;
+    if (S.seg_parts > 0) parts = (u64)S.seg_parts;
     else while (nseg * parts < want_waves && nseg * parts * 2 <= (u64)kMaxGrid && seglen / (parts * 2) >= 8 * 512) parts *= 2;
     p.kernel = REDUX_KERNEL_WAVE;
     if (parts > 1 && nseg <= (u64)kMaxGrid / parts) {
@@ -455,12 +507,54 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
         p.parts = parts;
         p.part_len = ((seglen + parts - 1) / parts + 511) / 512 * 512;
     }
+    // Whole segments of more than 1008 bytes and less than 8000 (measured: from there on one wavefront per segment is
+    // ahead, 6.8 against 6.6 TB/s at 8000 B, 7.0 against 6.8 at 12000 B): a wavefront streams a run of up to sixteen
+    // of them as one contiguous piece.
+    if (p.kernel == REDUX_KERNEL_WAVE && runs_fit) {
+        p.kernel = REDUX_KERNEL_RUNS;
+        const bool mfma = effective_variant(S, dtype) == REDUX_VARIANT_MFMA;
+        // measured: the MMA family runs best with four loads per lane in flight and three blocks per compute unit (the
+        // fold and the store at the end of a run leave gaps that other wavefronts fill); the classic family, whose lanes
+        // also convert and add, wants eight loads and more wavefronts the shorter the segments are
+        p.unroll = S.unroll == 0 ? (mfma ? 4 : 8) : (S.unroll <= 4 ? 4 : 8);
+        const u64 step = 64 * (u64)p.unroll;                                    // vectors per iteration of a wavefront
+        const long bpc = S.seg_blocks_per_cu ? S.seg_blocks_per_cu : (mfma ? 3 : seg_bytes < 2560 ? 8 : 4);
+        u64 gmax = (u64)cus * (u64)bpc;
+        if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
+        if (gmax < 1) gmax = 1;
+        // Segments per run: a run costs its iterations (whole ones: the lanes of the last one that lie behind the run's
+        // end idle) plus a fixed amount for the fold, the store and the set-up of the next run, taken as one
+        // iteration of four loads.  Blocks take groups of four runs in rounds, and the last round is only partly
+        // filled: with g groups on b blocks the machine is busy for g / (b x ceil(g / b)) of the time (measured: 8200-byte
+        // segments in runs of 7 on 768 blocks, 2.08 rounds, 5.97 TB/s; in runs of 11, 1.3 rounds... 6.69).  The length
+        // with the most bytes per cost, times that share, wins.
+        u64 len = 1;
+        if (S.seg_run_len > 0) {
+            len = (u64)S.seg_run_len;
+        } else {
+            double best = 0.0;
+            for (u64 c = 1; c <= 16 && c <= nseg; ++c) {
+                const u64 slots = (15 + c * seg_bytes + 15) / 16;              // worst alignment of the run's first byte
+                const u64 iters = (slots + step - 1) / step;
+                const u64 groups = ((nseg + c - 1) / c + kWaves - 1) / kWaves;
+                const u64 rounds = (groups + gmax - 1) / gmax;
+                const double busy = (double)groups / (double)(gmax * rounds);
+                const double value = busy * (double)(c * seg_bytes) / (double)(iters * step * 16 + 4096);
+                if (value >= best) { best = value; len = c; }
+            }
+        }
+        p.nvec = (unsigned)len;
+        const u64 nruns = (nseg + len - 1) / len;
+        const u64 blocks = (nruns + kWaves - 1) / kWaves;
+        p.grid = (unsigned)(blocks < gmax ? blocks : gmax);
+        return p;
+    }
     // Measured on MI355X by piece size (aligned vectors a piece can overlap): up to 2 KiB two loads per lane take the
     // whole piece at once; up to 5 KiB one load per lane and as many wavefronts as fit hide the per-segment fold
     // best; longer pieces stream with two, then four loads in flight per lane.
     const u64 piece_bytes = p.part_len * es;
     const u64 cover = (piece_bytes + ((x_addr % 16 == 0 && seg_bytes % 16 == 0) ? 0 : 16 - es) + 15) / 16;
-    p.unroll = (int)g_set.unroll;
+    p.unroll = (int)S.unroll;
     long best_bpc = 0;
     if (p.unroll == 0) {
         if (cover <= 64)       { p.unroll = 1; best_bpc = 16; }
@@ -471,12 +565,20 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
     } else {
         best_bpc = 8 / p.unroll;
     }
-    const long bpc = g_set.seg_blocks_per_cu ? g_set.seg_blocks_per_cu : best_bpc;
+    const long bpc = S.seg_blocks_per_cu ? S.seg_blocks_per_cu : best_bpc;
     u64 blocks_needed = (nseg * p.parts + kWaves - 1) / kWaves;
     u64 gmax = (u64)cus * (u64)bpc;
-    if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+    if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
     if (gmax < 1) gmax = 1;
     p.grid = (unsigned)(blocks_needed < gmax ? blocks_needed : gmax);
+    return p;
+}
+
+SegPlan plan_segmented(const Settings &S, u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_addr, int cus)
+{
+    SegPlan p = plan_segmented_shape(S, nseg, seglen, dtype, es, x_addr, cus);
+    // one block per segment: the flat sum's four accumulator chains; one wavefront per segment: a single chain
+    p.chain = chain_length(S, dtype, effective_variant(S, dtype) == REDUX_VARIANT_MFMA, p.unroll, p.kernel == REDUX_KERNEL_BLOCK ? 4 : 1);
     return p;
 }
 
@@ -485,50 +587,35 @@ SegPlan plan_segmented(u64 nseg, u64 seglen, int dtype, size_t es, uintptr_t x_a
 // =====================================================================================================
 extern "C" {
 
-int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
+// The flat sum: `ws` is where the block partials and the ticket live.
+static int launch_sum(const Settings &S, int cus, const Workspace &ws, bool clear_ticket, const void *x, size_t n, size_t es,
+                      int dtype, void *out, hipStream_t st)
 {
-    std::call_once(g_env_once, read_env);
-    size_t es = 0;
-    int rc = check_common(x, n, dtype, out, 1, &es);
-    if (rc != REDUX_OK) return rc;
-
-    hipStream_t st = (hipStream_t)stream;
-    std::lock_guard<std::mutex> lock(g_mu);
-
-    if (n == 0) {  // the empty sum
-        if (dtype != REDUX_I8) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(1), dim3(64), 0, st, (float *)out, (u64)1);
-        else                   hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(1), dim3(64), 0, st, (i64 *)out, (u64)1);
-        hipError_t e = hipGetLastError();
-        return e == hipSuccess ? REDUX_OK : hip_fail(e);
-    }
-
-    int dev = 0, cus = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return hip_fail(e);
-    if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
-    Workspace ws;
-    if ((rc = get_workspace(dev, st, &ws)) != REDUX_OK) return rc;
-
     FlatArgs a;
     a.run = es == 4 ? make_run<4>(x, n) : es == 2 ? make_run<2>(x, n) : make_run<1>(x, n);
     a.partials = ws.partials;
     a.ticket = ws.ticket;
     a.out = out;
-    a.max_chain = (unsigned)g_set.max_chain;
-    a.layout = (int)g_set.layout;
-    a.stagger = (unsigned)g_set.stagger;
-    a.finish = (int)g_set.finish;
+    a.layout = (int)S.layout;
+    a.stagger = (unsigned)S.stagger;
 
-    const FlatPlan plan = plan_flat(a.run.nvec, cus);
+    const FlatPlan plan = plan_flat(S, a.run.nvec, cus, dtype);
     const int unroll = plan.unroll;
     const unsigned grid = plan.grid;
     a.finish = plan.finish;
+    a.max_chain = plan.chain;
+    a.pause = plan.pause;
 
-    const bool nt = g_set.nontemporal != 0;
-    const bool mfma = effective_variant(dtype, true) == REDUX_VARIANT_MFMA;
+    const bool nt = S.nontemporal != 0;
+    const bool mfma = effective_variant(S, dtype, true) == REDUX_VARIANT_MFMA;
+    hipError_t e;
     if (a.finish == 3) {   // atomic additions start from zero
         if (dtype != REDUX_I8) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(1), dim3(64), 0, st, (float *)out, (u64)1);
         else                   hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(1), dim3(64), 0, st, (i64 *)out, (u64)1);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    } else if (clear_ticket && a.finish != 2) {
+        hipLaunchKernelGGL(fill_zero_words_kernel, dim3(1), dim3(64), 0, st, a.ticket, 1u);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
     }
@@ -545,6 +632,39 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
     return REDUX_OK;
 }
 
+static int launch_empty_sum(int dtype, void *out, hipStream_t st)
+{
+    if (dtype != REDUX_I8) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(1), dim3(64), 0, st, (float *)out, (u64)1);
+    else                   hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(1), dim3(64), 0, st, (i64 *)out, (u64)1);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? REDUX_OK : hip_fail(e);
+}
+
+int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
+{
+    std::call_once(g_env_once, read_env);
+    size_t es = 0;
+    int rc = check_common(x, n, dtype, out, 1, &es);
+    if (rc != REDUX_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (n == 0) return launch_empty_sum(dtype, out, st);   // the empty sum
+
+    // process-wide state is read under the lock; the launches run outside it, so host threads do not serialise
+    Settings S;
+    int cus = 0;
+    Workspace ws;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        S = g_set;
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return hip_fail(e);
+        if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
+        if ((rc = get_workspace(dev, st, &ws)) != REDUX_OK) return rc;
+    }
+    return launch_sum(S, cus, ws, false, x, n, es, dtype, out, st);
+}
+
 int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, void *out, void *stream)
 {
     std::call_once(g_env_once, read_env);
@@ -557,7 +677,6 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     if (nseg == 0) return REDUX_OK;
 
     hipStream_t st = (hipStream_t)stream;
-    std::lock_guard<std::mutex> lock(g_mu);
 
     if (seglen == 0) {
         unsigned grid = (unsigned)((nseg + 255) / 256);
@@ -567,14 +686,21 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
         return e == hipSuccess ? REDUX_OK : hip_fail(e);
     }
 
+    // process-wide state is read under the lock; the launches run outside it
+    Settings S;
     int dev = 0, cus = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return hip_fail(e);
-    if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
+    hipError_t e;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        S = g_set;
+        e = hipGetDevice(&dev);
+        if (e != hipSuccess) return hip_fail(e);
+        if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
+    }
 
-    const bool nt = g_set.nontemporal != 0;
-    const bool mfma = effective_variant(dtype) == REDUX_VARIANT_MFMA;
-    const SegPlan plan = plan_segmented(nseg, seglen, dtype, es, (uintptr_t)x, cus);
+    const bool nt = S.nontemporal != 0;
+    const bool mfma = effective_variant(S, dtype) == REDUX_VARIANT_MFMA;
+    const SegPlan plan = plan_segmented(S, nseg, seglen, dtype, es, (uintptr_t)x, cus);
     const unsigned grid = plan.grid;
 
     // ---- short segments read as one contiguous stream: aligned powers of two, or ragged ----------------------
@@ -588,13 +714,13 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
         s.nvec = (u64)nseg << s.lg;
         s.seg_bytes = (u64)seglen * es;
         s.out = out;
-        s.layout = (int)g_set.layout;
+        s.layout = (int)S.layout;
         // measured: refilling registers one by one hides the second MMA and the stores of segments up to
         // 256 B (and the classic family's conversions); longer segments run fastest as a plain loop
         // (binary32 excepted: it needs four MMAs per load)
         // The ragged form: always refill.
         const int best_pipe = ragged ? 1 : (mfma && s.lg >= 5 && dtype != REDUX_F32 ? 0 : 1);
-        s.pipe = g_set.seg_short_pipe >= 0 ? (int)g_set.seg_short_pipe : best_pipe;
+        s.pipe = S.seg_short_pipe >= 0 ? (int)S.seg_short_pipe : best_pipe;
         const bool wide = s.lg >= 5;       // 32 or 64 lanes per segment: eight loads share an accumulator
         with_short_family(dtype, [&](auto elem) {
             typedef decltype(elem) E;
@@ -607,6 +733,27 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
             else        { constexpr bool RR = false; REDUX_SHORT_ALL(); }
 #undef REDUX_SHORT_ALL
 #undef REDUX_SHORT_NT
+        });
+        e = hipGetLastError();
+        return e == hipSuccess ? REDUX_OK : hip_fail(e);
+    }
+
+    // ---- medium segments: one wavefront streams a run of whole segments ----------------------------------------
+    if (plan.kernel == REDUX_KERNEL_RUNS) {
+        RunArgs r;
+        r.x = (const unsigned char *)x;
+        r.nseg = nseg;
+        r.seg_bytes = (unsigned)(seglen * es);
+        r.per_run = plan.nvec;
+        r.out = out;
+        r.layout = (int)S.layout;
+        with_short_family(dtype, [&](auto elem) {
+            typedef decltype(elem) E;
+#define REDUX_RUNS(KERNEL, UU) do { if (nt) hipLaunchKernelGGL((KERNEL<E, UU, true>), dim3(grid), dim3(kBlock), 0, st, r); \
+                                    else    hipLaunchKernelGGL((KERNEL<E, UU, false>), dim3(grid), dim3(kBlock), 0, st, r); } while (0)
+            if (mfma) { if (plan.unroll == 8) REDUX_RUNS(sum_segment_runs_mfma_kernel, 8); else REDUX_RUNS(sum_segment_runs_mfma_kernel, 4); }
+            else      { if (plan.unroll == 8) REDUX_RUNS(sum_segment_runs_classic_kernel, 8); else REDUX_RUNS(sum_segment_runs_classic_kernel, 4); }
+#undef REDUX_RUNS
         });
         e = hipGetLastError();
         return e == hipSuccess ? REDUX_OK : hip_fail(e);
@@ -638,12 +785,13 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     a.nseg = nseg;
     a.seglen = seglen;
     a.out = out;
-    a.max_chain = (unsigned)g_set.max_chain;
+    a.max_chain = plan.chain;
     a.parts = plan.parts;
     a.part_len = plan.part_len;
     a.partials = nullptr;
     if (plan.parts > 1) {
         Workspace ws;
+        std::lock_guard<std::mutex> lock(g_mu);
         if ((rc = get_workspace(dev, st, &ws)) != REDUX_OK) return rc;
         a.partials = ws.partials;
     }
@@ -699,21 +847,21 @@ int redux_sum_multipass(const void *x, size_t n, int dtype, void *out, int *leve
     if (levels) *levels = 0;
 
     hipStream_t st = (hipStream_t)stream;
-    std::lock_guard<std::mutex> lock(g_mu);
-    if (n == 0) {
-        if (dtype == REDUX_F16) hipLaunchKernelGGL(fill_zero_kernel<float>, dim3(1), dim3(64), 0, st, (float *)out, (u64)1);
-        else                    hipLaunchKernelGGL(fill_zero_kernel<i64>, dim3(1), dim3(64), 0, st, (i64 *)out, (u64)1);
-        hipError_t e = hipGetLastError();
-        return e == hipSuccess ? REDUX_OK : hip_fail(e);
+    if (n == 0) return launch_empty_sum(dtype, out, st);
+
+    Settings S;
+    int dev = 0, cus = 0;
+    hipError_t e;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        S = g_set;
+        e = hipGetDevice(&dev);
+        if (e != hipSuccess) return hip_fail(e);
+        if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
     }
 
-    int dev = 0, cus = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return hip_fail(e);
-    if ((rc = device_cus(dev, &cus)) != REDUX_OK) return rc;
-
     // group size m*m (m = 4, 16 or 32) for binary16; the int8 form has one shape (16 x 32, then 16 x 16)
-    const int m = dtype == REDUX_F16 ? (int)g_set.lit_m : 16;
+    const int m = dtype == REDUX_F16 ? (int)S.lit_m : 16;
     const u64 group = (u64)m * m;
     const u64 first_group = dtype == REDUX_F16 ? group : (u64)kLitGroupI8;
     const u64 tile = m == 32 ? 1024 : 256;                                   // elements one wavefront step consumes
@@ -721,11 +869,14 @@ int redux_sum_multipass(const void *x, size_t n, int dtype, void *out, int *leve
     const u64 n1 = ((u64)n + first_group - 1) / first_group;                 // partial sums after level 1
     const u64 n2 = (n1 + group - 1) / group;                                 // ... after level 2
     LevelBuffers lb;
-    if (n1 > 1 && (rc = get_level_buffers(dev, st, (size_t)n1 * ps + 16, (size_t)n2 * ps + 16, &lb)) != REDUX_OK) return rc;
+    if (n1 > 1) {
+        std::lock_guard<std::mutex> lock(g_mu);
+        if ((rc = get_level_buffers(dev, st, (size_t)n1 * ps + 16, (size_t)n2 * ps + 16, &lb)) != REDUX_OK) return rc;
+    }
 
     // measured best on MI355X (these kernels are bound by the matrix unit, not by HBM)
-    const int U = g_set.lit_unroll ? (int)g_set.lit_unroll : (dtype == REDUX_I8 ? 4 : m == 4 ? 4 : m == 16 ? 16 : 8);
-    const u64 bpc = g_set.lit_blocks_per_cu ? (u64)g_set.lit_blocks_per_cu : (dtype == REDUX_I8 ? 8 : m == 32 ? 2 : 4);
+    const int U = S.lit_unroll ? (int)S.lit_unroll : (dtype == REDUX_I8 ? 4 : m == 4 ? 4 : m == 16 ? 16 : 8);
+    const u64 bpc = S.lit_blocks_per_cu ? (u64)S.lit_blocks_per_cu : (dtype == REDUX_I8 ? 8 : m == 32 ? 2 : 4);
     const void *in = x;
     u64 count = n;
     int level = 0;
@@ -737,7 +888,7 @@ int redux_sum_multipass(const void *x, size_t n, int dtype, void *out, int *leve
         const u64 nbatch = (ntiles + U - 1) / U;
         u64 blocks = (nbatch + kWaves - 1) / kWaves;
         u64 gmax = (u64)cus * bpc;
-        if (gmax > (u64)g_set.max_grid) gmax = (u64)g_set.max_grid;
+        if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
         const unsigned grid = (unsigned)(blocks < gmax ? blocks : gmax);
         const bool first = level == 0;
         const bool fast = ((uintptr_t)in % (dtype == REDUX_F16 && m == 32 ? 16 : 8)) == 0;
@@ -815,7 +966,7 @@ int redux_plan_sum(size_t n, int dtype, uintptr_t x_address, int compute_units, 
     std::lock_guard<std::mutex> lock(g_mu);
     const void *x = (const void *)x_address;
     const Run run = es == 4 ? make_run<4>(x, n) : es == 2 ? make_run<2>(x, n) : make_run<1>(x, n);
-    const FlatPlan p = plan_flat(run.nvec, compute_units);
+    const FlatPlan p = plan_flat(g_set, run.nvec, compute_units, dtype);
     plan->kernel = REDUX_KERNEL_FLAT;
     plan->unroll = p.unroll;
     plan->grid = p.grid;
@@ -825,6 +976,7 @@ int redux_plan_sum(size_t n, int dtype, uintptr_t x_address, int compute_units, 
     plan->head = (unsigned)run.nhead;
     plan->tail = (unsigned)run.ntail;
     plan->vectors = run.nvec;
+    plan->chain = p.chain;
     return REDUX_OK;
 }
 
@@ -837,7 +989,7 @@ int redux_plan_sum_segmented(size_t nseg, size_t seglen, int dtype, uintptr_t x_
     if (nseg > ((size_t)1 << 59)) return REDUX_ERR_SIZE;
     if (compute_units < 1 || nseg == 0 || seglen == 0) return REDUX_ERR_PARAM;
     std::lock_guard<std::mutex> lock(g_mu);
-    const SegPlan p = plan_segmented(nseg, seglen, dtype, es, x_address, compute_units);
+    const SegPlan p = plan_segmented(g_set, nseg, seglen, dtype, es, x_address, compute_units);
     plan->kernel = p.kernel;
     plan->unroll = p.unroll;
     plan->grid = p.grid;
@@ -847,6 +999,7 @@ int redux_plan_sum_segmented(size_t nseg, size_t seglen, int dtype, uintptr_t x_
     plan->head = 0;
     plan->tail = 0;
     plan->vectors = p.nvec;
+    plan->chain = p.chain;
     return REDUX_OK;
 }
 
@@ -883,7 +1036,7 @@ int redux_resolved_variant(int dtype, int segmented)
     std::call_once(g_env_once, read_env);
     if (elem_size_of(dtype) == 0) return REDUX_ERR_DTYPE;
     std::lock_guard<std::mutex> lock(g_mu);
-    return effective_variant(dtype, segmented == 0);
+    return effective_variant(g_set, dtype, segmented == 0);
 }
 
 int redux_set_param(const char *name, long value)
@@ -934,6 +1087,8 @@ void redux_shutdown(void)
         for (int i = 0; i < 2; ++i)
             if (kv.second.buf[i]) (void)hipFree(kv.second.buf[i]);
     g_levels.clear();
+    for (void *p : g_retired) (void)hipFree(p);
+    g_retired.clear();
     g_cus.clear();
 }
 

@@ -442,8 +442,9 @@ struct FlatArgs {
     void *out;
     unsigned max_chain; // loop iterations between folds
     int layout;         // which slabs a block takes (see slab_schedule)
-    int finish;         // 0/1: the last block to arrive sums the partials; 2: a second kernel does; 3: atomic additions
+    int finish;         // 0/1/4: the last block to arrive sums the partials; 2: a second kernel does; 3: atomic additions
     unsigned stagger;   // start of wavefront w delayed by w x stagger x 64 cycles (long runs only)
+    unsigned pause;     // every loop iteration ends with this many 64-cycle sleeps (experiment)
 };
 
 constexpr int kXcds = 8;  // workgroup b is dispatched to accelerator die b % 8
@@ -509,6 +510,7 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
 #pragma unroll
         for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
         if (++chain >= a.max_chain) { wave_total += F::fold(acc); chain = 0; }
+        for (unsigned i = 0; i < a.pause; ++i) __builtin_amdgcn_s_sleep(1);
     }
 
     // vectors past the last whole slab: one block, lanes past the end contribute zeros
@@ -547,13 +549,27 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
     }
     if (tid == 0) {
         Total block_total = ((lds[0] + lds[1]) + (lds[2] + lds[3]));
-        store_partial(a.partials + blockIdx.x, block_total);
-        // release: the partial is visible device-wide before the ticket moves.  The block that draws the
+        // The partial must be visible device-wide before the ticket moves.  The block that draws the
         // last ticket has read, through the chain of read-modify-writes, from every other block's
-        // release; its acquire fence below then makes all partials visible to it.
-        unsigned t = (a.finish == 0)
-            ? __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT)
-            : __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        // ticket; its acquire fence below then makes all partials visible to it.
+        unsigned t;
+        if (a.finish == 4) {
+            // The partial is the only thing this block has to publish.  A device-scope release fence would write back
+            // every dirty line of this die's L2 (several microseconds per block, which is what finish 0/1 pay), so the
+            // partial travels in a read-modify-write instead: a device-scope atomic exchange is performed where the dies
+            // of the device meet, exactly like the ticket's own addition, and it has been performed once its old value
+            // has come back.  The ticket's increment is made to depend on that old value, so it cannot be issued earlier.
+            const u64 old = __hip_atomic_exchange(a.partials + blockIdx.x, __builtin_bit_cast(u64, block_total),
+                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            unsigned one = 1u;
+            asm volatile("" : "+s"(one) : "v"((unsigned)old), "v"((unsigned)(old >> 32)));   // `one` exists only after `old` does
+            t = __hip_atomic_fetch_add(a.ticket, one, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            store_partial(a.partials + blockIdx.x, block_total);
+            t = (a.finish == 0)
+                ? __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT)
+                : __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
         is_last = (t == gridDim.x - 1) ? 1u : 0u;
     }
     __syncthreads();
@@ -562,7 +578,8 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
         Total total = sum_partials<F>(a.partials, gridDim.x, lds);
         if (tid == 0) {
             *(typename F::Out *)a.out = F::to_out(total);
-            __hip_atomic_store(a.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // (a read-modify-write like every other access to the ticket, so that the next launch's additions find it)
+            (void)__hip_atomic_exchange(a.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }

@@ -1,0 +1,247 @@
+// redux_runs.h -- segmented sum of medium segments (about 1 KiB to 256 KiB each, any length, any alignment).
+//
+// One wavefront takes a *run* of up to sixteen consecutive whole segments and streams the 16-byte aligned vectors
+// that cover it, 64 x 8 at a time, exactly like the flat sum streams the array: every lane of every load holds
+// data, whatever the segment length is.  Only the two ends of a run are ragged (a run starts and ends on a segment
+// boundary, not on a vector boundary), so two neighbouring runs share at most one vector.
+//
+// MMA family.  Segment k of the run owns column k of the accumulator: the first MMA of Section IV-A,
+// D <- A x B + D, is issued with B = "ones in column k, zeros elsewhere", so row sums of the data land in column k
+// (D[i][k] += sum of the vector of lane 16 g + i over the four k-groups g).  A load that holds a segment boundary
+// is issued twice, once with the bytes in front of the boundary (into column k) and once with the bytes behind it
+// (into column k + 1); the bytes outside are cleared, which is the zero padding of Section IV-A.  Where the
+// boundaries fall is the same for every lane of the wavefront, so it is worked out in scalar registers; a lane only
+// clamps (boundary - 16 x lane) to 0..16 to find how many of its sixteen bytes lie in front.  At the end of the run
+// the second MMA, D' <- 1 x D, adds the sixteen rows of every column at once and lanes 0 .. 15 store one result
+// each.  Bytes in front of the run's first segment and behind its last one never enter an MMA.
+//
+// A zero in B still multiplies its data, so an infinity or NaN in one segment would turn the other columns into NaN:
+// a run whose D' holds a non-finite value is computed again by the classic form below, which never mixes segments.
+//
+// Classic family.  Every lane adds up its vectors; at a boundary the lanes' sums of the finished segment go through
+// the wavefront butterfly of Section III and lane 0 stores the result.
+#pragma once
+#include "redux_short.h"
+
+namespace redux {
+
+struct RunArgs {
+    const unsigned char *x;  // first element, aligned to the element size only
+    u64 nseg;
+    unsigned seg_bytes;      // bytes per segment: 16 .. 2^18 (the run's byte positions are kept in 32 bits)
+    unsigned per_run;        // segments per run: 1 .. 16
+    void *out;
+    int layout;              // which runs a block takes (see slab_schedule; a block takes four consecutive runs at a time)
+};
+
+// U = 16-byte loads per lane per iteration (4 or 8); an iteration of a wavefront takes 64 x U vectors
+
+// all-ones in the low b bytes of a vector, b = 0 .. 16, as a table in LDS
+__device__ __forceinline__ void fill_low_masks(u32x4 *table /* 17 entries, shared */)
+{
+    if (threadIdx.x < 17u) table[threadIdx.x] = keep_bytes(u32x4{~0u, ~0u, ~0u, ~0u}, 0u, threadIdx.x);
+    __syncthreads();
+}
+
+// Where a run lies: its first aligned vector, where its first segment starts in it, where its last one ends.
+struct RunGeometry {
+    const u32x4 *base;   // 16-byte aligned
+    unsigned off;        // first byte of the run's first segment, from base (0 .. 15)
+    unsigned total;      // first byte behind the run's last segment, from base
+    unsigned nvec;       // aligned vectors that overlap the run
+    unsigned count;      // segments in this run (the array's last run may be short)
+    u64 first;           // index of the run's first segment
+};
+
+__device__ __forceinline__ RunGeometry run_geometry(const RunArgs &a, u64 run)
+{
+    RunGeometry g;
+    g.first = run * a.per_run;
+    const u64 left = a.nseg - g.first;
+    g.count = left < (u64)a.per_run ? (unsigned)left : a.per_run;
+    // (pointer arithmetic on the kernel argument keeps the loads in the global address space)
+    const unsigned char *start = a.x + g.first * a.seg_bytes;
+    g.off = (unsigned)(uintptr_t)start & 15u;
+    g.base = (const u32x4 *)(start - g.off);
+    g.total = g.off + g.count * a.seg_bytes;
+    g.nvec = (g.total + 15u) >> 4;
+    return g;
+}
+
+// The 64 x U vectors of one iteration.  Lanes past the run's last vector read that vector again (one cache line
+// for all of them); their bytes lie behind the run's end and are dropped like everything there.  An aligned
+// vector that holds a byte of the array lies in the array's pages, so nothing unmapped is touched.
+template <int U, bool NT>
+__device__ __forceinline__ void run_load(u32x4 *cur, const RunGeometry &g, unsigned v0, unsigned lane)
+{
+    if (v0 + 64u * U <= g.nvec) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) cur[u] = load16<NT>(g.base + v0 + 64u * (unsigned)u + lane);
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned idx = v0 + 64u * (unsigned)u + lane;
+            cur[u] = load16<NT>(g.base + (idx < g.nvec ? idx : g.nvec - 1u));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);             // every load of the iteration in flight before the first use waits
+}
+
+// Walks the boundaries of a run.  `col` is the segment (0 .. count - 1) that the byte at `next` belongs to once
+// the boundary at `next` has been passed; before the first boundary (col = ~0) and behind the last one
+// (col = count) bytes belong to no segment of this run.
+struct RunCursor {
+    unsigned col, next;
+    __device__ __forceinline__ void start(const RunGeometry &g) { col = ~0u; next = g.off; }
+    __device__ __forceinline__ void pass(const RunGeometry &g, unsigned seg_bytes)
+    {
+        ++col;                                                        // ~0 -> 0 at the run's first byte
+        next = col < g.count ? next + seg_bytes : ~0u;                // no boundary behind the run's end
+    }
+};
+
+// How many of this lane's sixteen bytes of a load lie in front of the boundary `d` bytes into the load.
+__device__ __forceinline__ unsigned bytes_in_front(unsigned d, int lane16)
+{
+    const int k = (int)d - lane16;
+    return (unsigned)(k < 0 ? 0 : k > 16 ? 16 : k);
+}
+
+// ---- classic family: one run by the lane sums and the butterfly --------------------------------------------------
+template <class E, int U, bool NT>
+__device__ __forceinline__ void run_classic(const RunArgs &a, const RunGeometry &g, const u32x4 *low, unsigned lane)
+{
+    typedef typename E::Out Out;
+    Out *out = (Out *)a.out + g.first;
+    const int lane16 = 16 * (int)lane;
+    typename E::Lane s = 0;                        // this lane's share of the current segment
+    RunCursor c;
+    c.start(g);
+    for (unsigned v0 = 0; v0 < g.nvec; v0 += 64u * U) {
+        u32x4 cur[U];
+        run_load<U, NT>(cur, g, v0, lane);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned p = (v0 + 64u * (unsigned)u) * 16u;       // first byte of this load, from base
+            if (p >= g.total) continue;                              // (the same for every lane)
+            const u32x4 v = cur[u];
+            if (c.next - p >= 1024u) {                               // no boundary in this load
+                if (c.col < g.count) s = s + E::lane_sum(v);
+            } else {
+                u32x4 done = {0u, 0u, 0u, 0u};                       // bytes already handed to a segment
+                do {
+                    const u32x4 front = low[bytes_in_front(c.next - p, lane16)];
+                    if (c.col < g.count) {                           // the segment in front of the boundary is complete
+                        s = s + E::lane_sum(v & front & ~done);
+                        const typename E::Lane t = short_butterfly(s, 6u);
+                        if (lane == 0) out[c.col] = E::lane_out(t);
+                        s = 0;
+                    }
+                    done = front;
+                    c.pass(g, a.seg_bytes);
+                } while (c.next - p < 1024u);
+                if (c.col < g.count) s = s + E::lane_sum(v & ~done);
+            }
+        }
+    }
+    // A run that ends exactly where its last load ends never meets its last boundary inside a load.
+    if (c.col < g.count) {
+        const typename E::Lane t = short_butterfly(s, 6u);
+        if (lane == 0) out[c.col] = E::lane_out(t);
+    }
+}
+
+template <class E, int U, bool NT>
+__global__ void __launch_bounds__(kBlock) sum_segment_runs_classic_kernel(RunArgs a)
+{
+    const unsigned lane = threadIdx.x & 63u;
+    // (the wavefront's number read into a scalar register: everything about a run is then scalar, branches included)
+    const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    __shared__ u32x4 low[17];
+    fill_low_masks(low);
+    const u64 nruns = (a.nseg + a.per_run - 1) / a.per_run;
+    // the block takes groups of four consecutive runs, one per wavefront, in the order the flat sum takes its slabs
+    u64 g0, stride, count;
+    slab_schedule(a.layout, (nruns + kWaves - 1) / kWaves, gridDim.x, blockIdx.x, &g0, &stride, &count);
+    for (u64 k = 0; k < count; ++k) {
+        const u64 run = (g0 + k * stride) * kWaves + wave;
+        if (run < nruns) run_classic<E, U, NT>(a, run_geometry(a, run), low, lane);
+    }
+}
+
+// ---- MMA family ------------------------------------------------------------------------------------------------------
+// second MMA: D' <- 1 x D; every lane gets the total of column lane % 16.  *bad: some column is not finite.
+__device__ __forceinline__ float run_fold(const f32x4 &d, bool *bad)
+{
+    f32x4 dp = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) dp = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, d[r], dp, 0, 0, 0);
+    const float z = dp[0] - dp[0];                 // finite - finite is 0; an infinity or NaN gives NaN
+    *bad = z != 0.f;
+    return dp[0];
+}
+// int32 row sums: no MFMA takes int32, so the second MMA runs exactly in binary64 (a column stays far below 2^53)
+__device__ __forceinline__ i64 run_fold(const i32x4 &d, bool *bad)
+{
+    f64x4 dp = {0., 0., 0., 0.};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) dp = __builtin_amdgcn_mfma_f64_16x16x4f64(1.0, (double)d[r], dp, 0, 0, 0);
+    *bad = false;
+    return (i64)dp[0];
+}
+
+template <class E, int U, bool NT>
+__global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_kernel(RunArgs a)
+{
+    typedef typename E::Out Out;
+    const unsigned lane = threadIdx.x & 63u, n = lane & 15u;
+    const int lane16 = 16 * (int)lane;
+    // (the wavefront's number read into a scalar register: everything about a run is then scalar, branches included)
+    const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    __shared__ u32x4 low[17];
+    fill_low_masks(low);
+    const u64 nruns = (a.nseg + a.per_run - 1) / a.per_run;
+    // the block takes groups of four consecutive runs, one per wavefront, in the order the flat sum takes its slabs
+    u64 g0, stride, count;
+    slab_schedule(a.layout, (nruns + kWaves - 1) / kWaves, gridDim.x, blockIdx.x, &g0, &stride, &count);
+
+    for (u64 k = 0; k < count; ++k) {
+        const u64 run = (g0 + k * stride) * kWaves + wave;
+        if (run >= nruns) break;                   // (only in the block's last group)
+        const RunGeometry g = run_geometry(a, run);
+        typename E::Acc acc = E::zero();           // column k: the sixteen row sums of segment k of the run
+        RunCursor c;
+        c.start(g);
+        for (unsigned v0 = 0; v0 < g.nvec; v0 += 64u * U) {
+            u32x4 cur[U];
+            run_load<U, NT>(cur, g, v0, lane);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const unsigned p = (v0 + 64u * (unsigned)u) * 16u;   // first byte of this load, from base
+                if (p >= g.total) continue;                          // (the same for every lane)
+                const u32x4 v = cur[u];
+                if (c.next - p >= 1024u) {                           // no boundary in this load: one MMA, nothing cleared
+                    if (c.col < g.count) acc = E::mma1(v, n == c.col, acc);
+                } else {
+                    u32x4 done = {0u, 0u, 0u, 0u};                   // bytes already handed to a segment
+                    do {
+                        const u32x4 front = low[bytes_in_front(c.next - p, lane16)];
+                        if (c.col < g.count) acc = E::mma1(v & front & ~done, n == c.col, acc);
+                        done = front;
+                        c.pass(g, a.seg_bytes);
+                    } while (c.next - p < 1024u);
+                    if (c.col < g.count) acc = E::mma1(v & ~done, n == c.col, acc);
+                }
+            }
+        }
+        bool bad;
+        const Out total = E::fold_out_wide(run_fold(acc, &bad));
+        if (E::kCanBeNonFinite && __builtin_amdgcn_ballot_w64(bad) != 0) {
+            run_classic<E, U, NT>(a, g, low, lane); // the same run again, segment by segment
+        } else if (lane < g.count) {
+            ((Out *)a.out)[g.first + lane] = total; // lanes 0 .. 15 hold columns 0 .. 15
+        }
+    }
+}
+
+} // namespace redux

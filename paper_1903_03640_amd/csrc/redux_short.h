@@ -148,6 +148,7 @@ struct ShortFloat {
     static __device__ __forceinline__ Acc mma1(u32x4 v, bool sel, Acc d) { return mma1_select<KIND>(v, sel, d); }
     static __device__ __forceinline__ float fold_in(const Acc &d, int r) { return d[r]; }
     static __device__ __forceinline__ Out fold_out(float f) { return f; }
+    static __device__ __forceinline__ Out fold_out_wide(float f) { return f; }
     static __device__ __forceinline__ Lane lane_sum(u32x4 v)
     {
         float s[4] = {0.f, 0.f, 0.f, 0.f};
@@ -173,6 +174,7 @@ struct ShortI8 {
     }
     static __device__ __forceinline__ float fold_in(const Acc &d, int r) { return (float)d[r]; }
     static __device__ __forceinline__ Out fold_out(float f) { return (i64)f; }
+    static __device__ __forceinline__ Out fold_out_wide(i64 v) { return v; }
     static __device__ __forceinline__ Lane lane_sum(u32x4 v)
     {
         int s = 0;
@@ -237,17 +239,47 @@ __device__ __forceinline__ void short_stream(const ShortArgs &a, unsigned tid, W
     } else if (count) {
         u32x4 cur[kShortLoads];
         unsigned m[kShortLoads];
+        // Ragged form: what short_fetch derives from a slot -- where its vector lies relative to the slab and which bytes
+        // of it belong to the segment -- is the same in every slab.  A slab holds 2048 >> lg whole segments, a multiple
+        // of sixteen, so its first segment starts a multiple of 16 bytes behind the array's first byte, and slot
+        // (u, tid) meets the same alignment in every slab.  So the byte offsets and mask entries are worked out once;
+        // inside the loop a load is the slab's (wavefront-uniform) address plus a fixed 32-bit offset per lane.
+        unsigned voff[kShortLoads];
+        const unsigned xo = (unsigned)(uintptr_t)a.x & 15u;
+        const unsigned char *xa = a.x - xo;                                   // (pointer arithmetic: stays a global address)
+        const u64 slab_bytes = (u64)(kShortSlab >> a.lg) * a.seg_bytes;      // bytes of the segments of one slab
+        if (RAGGED) {
+#pragma unroll
+            for (int u = 0; u < kShortLoads; ++u) {
+                const unsigned idx = short_index(u, tid, false);
+                const unsigned j = idx & ((1u << a.lg) - 1u);
+                const unsigned rel = xo + (idx >> a.lg) * (unsigned)a.seg_bytes;  // first byte of the segment, from xa
+                const unsigned off = rel & 15u;
+                const unsigned end = off + (unsigned)a.seg_bytes;
+                const unsigned cover = (end + 15u) >> 4;
+                const unsigned jj = j < cover ? j : cover - 1u;
+                voff[u] = rel - off + 16u * jj;
+                const unsigned lo = j == 0 ? off : 0u;
+                const unsigned hi = j >= cover ? 0u : (end - 16u * j >= 16u ? 16u : end - 16u * j);
+                m[u] = lo * 17u + hi;
+            }
+        }
+        // vector of slot (u, tid) of slab `sl`
+        auto fetch = [&](u64 sl, int u) -> u32x4 {
+            if (RAGGED) return load16<NT>((const u32x4 *)(xa + sl * slab_bytes + voff[u]));
+            return short_fetch<NT, false>(a, sl * kShortSlab + short_index(u, tid, CANWIDE && a.lg >= 7), &m[u]);
+        };
 #pragma unroll
         for (int u = 0; u < kShortLoads; ++u) {      // issued strictly in the order they are consumed in: the waits count on it
-            cur[u] = short_fetch<NT, RAGGED>(a, s0 * kShortSlab + short_index(u, tid, CANWIDE && a.lg >= 7), &m[u]);
+            cur[u] = fetch(s0, u);
             __builtin_amdgcn_sched_barrier(0);
         }
         u64 slab = s0;
         for (u64 k = 1; k < count; ++k, slab += stride) {
-            const u64 next = (slab + stride) * kShortSlab;
+            const u64 next = slab + stride;
             __builtin_amdgcn_sched_barrier(0);
             const bool again = work(cur, m, slab, [&](int u) {
-                cur[u] = short_fetch<NT, RAGGED>(a, next + short_index(u, tid, CANWIDE && a.lg >= 7), &m[u]);
+                cur[u] = fetch(next, u);
                 __builtin_amdgcn_sched_barrier(0);                   // keep the refill right behind the use
             });
             if (again) {

@@ -31,10 +31,10 @@ class Plan(ctypes.Structure):
     """Mirror of redux_plan."""
     _fields_ = [("kernel", ctypes.c_int), ("unroll", ctypes.c_int), ("grid", ctypes.c_uint), ("finish", ctypes.c_int),
                 ("parts", ctypes.c_uint64), ("part_len", ctypes.c_uint64), ("head", ctypes.c_uint), ("tail", ctypes.c_uint),
-                ("vectors", ctypes.c_uint64)]
+                ("vectors", ctypes.c_uint64), ("chain", ctypes.c_uint)]
 
 
-KERNEL_FLAT, KERNEL_ROWS, KERNEL_WAVE, KERNEL_PIECES, KERNEL_TILES, KERNEL_BLOCK, KERNEL_SHORT, KERNEL_RAGGED = 0, 1, 2, 3, 4, 5, 6, 7
+KERNEL_FLAT, KERNEL_ROWS, KERNEL_WAVE, KERNEL_PIECES, KERNEL_TILES, KERNEL_BLOCK, KERNEL_SHORT, KERNEL_RAGGED, KERNEL_RUNS = 0, 1, 2, 3, 4, 5, 6, 7, 8
 
 
 class ReduxError(RuntimeError):
@@ -182,22 +182,29 @@ def plan_block_slabs(layout: int, nslab: int, grid: int, block: int):
 
 # ---- torch conveniences: allocate the output, pass the current stream --------------------------------
 
+_DTYPES = None
+
+
 def _dtype_of(x) -> int:
-    import torch
-    table = {torch.float16: F16, torch.int8: I8, torch.bfloat16: BF16, torch.float32: F32,
-             torch.float8_e4m3fn: F8E4M3, torch.float8_e5m2: F8E5M2}
-    if x.dtype not in table:
+    global _DTYPES
+    if _DTYPES is None:
+        import torch
+        _DTYPES = {torch.float16: F16, torch.int8: I8, torch.bfloat16: BF16, torch.float32: F32,
+                   torch.float8_e4m3fn: F8E4M3, torch.float8_e5m2: F8E5M2}
+    dt = _DTYPES.get(x.dtype)
+    if dt is None:
         raise TypeError("redux supports float16, int8, bfloat16, float32, float8_e4m3fn and float8_e5m2 tensors, got %s" % x.dtype)
-    return table[x.dtype]
+    return dt
 
 
-def _prep(x):
+def _prep(x) -> int:
+    """Checks x and returns the raw handle of the current stream of x's device."""
     import torch
     if not x.is_cuda:
         raise ValueError("redux needs a device tensor (there is no CPU path)")
     if not x.is_contiguous():
         raise ValueError("redux needs a contiguous tensor")
-    return torch.cuda.current_stream(x.device).cuda_stream
+    return torch._C._cuda_getCurrentRawStream(x.device.index)
 
 
 class _Device:
@@ -206,7 +213,7 @@ class _Device:
 
     def __init__(self, x):
         import torch
-        self.ctx = None if torch.cuda.current_device() == x.device.index else torch.cuda.device(x.device)
+        self.ctx = None if torch._C._cuda_getDevice() == x.device.index else torch.cuda.device(x.device)
 
     def __enter__(self):
         if self.ctx is not None:
@@ -224,8 +231,15 @@ def sum(x, out=None):
     dt = _dtype_of(x)
     if out is None:
         out = torch.empty(1, dtype=torch.int64 if dt == I8 else torch.float32, device=x.device)
-    with _Device(x):
-        _check(sum_raw(x.data_ptr() if x.numel() else 0, x.numel(), dt, out.data_ptr(), stream), "redux_sum")
+    n = x.numel()
+    lib = _lib if _lib is not None else load()
+    if torch._C._cuda_getDevice() == x.device.index:      # the usual case: nothing to switch, no context manager
+        rc = lib.redux_sum(x.data_ptr() if n else 0, n, dt, out.data_ptr(), stream)
+    else:
+        with torch.cuda.device(x.device):
+            rc = lib.redux_sum(x.data_ptr() if n else 0, n, dt, out.data_ptr(), stream)
+    if rc:
+        raise ReduxError(rc, "redux_sum")
     return out
 
 

@@ -10,6 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run on the GPU box only)")
+    config.addinivalue_line("markers", "perf: throughput floors; a miss fails only under `-m perf` or REDUX_PERF_STRICT=1")
 
 
 def pytest_collection_modifyitems(config, items):

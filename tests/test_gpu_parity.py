@@ -179,7 +179,7 @@ def test_flat_chain_folds_and_small_grids(dev, variant, max_chain, max_grid):
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("layout", [0, 1, 2])
-@pytest.mark.parametrize("finish", [0, 1, 2, 3])
+@pytest.mark.parametrize("finish", [0, 1, 2, 3, 4])
 def test_flat_layouts_and_finishes(dev, variant, layout, finish):
     redux.set_param("layout", layout)
     redux.set_param("finish", finish)
@@ -260,6 +260,28 @@ def test_variants_agree_and_runs_are_bit_identical(dev):
     want_abs = oracle.sum_f16(x.cpu().numpy())[1]
     assert abs(res["mfma"][0] - res["classic"][0]) <= 2 * TOL * want_abs
     assert res["mfma"][1] == res["classic"][1]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("finish", [0, 1, 4])
+def test_in_kernel_finish_sees_this_call_not_the_last(dev, variant, finish):
+    """Back-to-back calls alternate between two different arrays: a block partial left over from the previous
+    call (one that the finishing block read before this call's write had become visible) would give a wrong sum."""
+    redux.set_variant(variant)
+    redux.set_param("finish", finish)
+    for n, max_grid, bpc in (((1 << 23) + 77, 16384, 1), ((1 << 23) + 77, 1000, 16), ((1 << 20) + 3, 33, 1), (5000, 16384, 1)):
+        redux.set_param("max_grid", max_grid)
+        redux.set_param("blocks_per_cu", bpc)
+        a, b = workloads.uniform_i8(71, n), workloads.uniform_i8(72, n)
+        wa, wb = oracle.sum_i8(a)[0], oracle.sum_i8(b)[0]
+        assert wa != wb
+        xa, xb = to_dev(a, dev), to_dev(b, dev)
+        outs = torch.zeros(200, dtype=torch.int64, device=dev)
+        for k in range(200):
+            redux.sum(xa if k % 2 == 0 else xb, out=outs[k:k + 1])
+        torch.cuda.synchronize()
+        got = outs.cpu().numpy()
+        assert np.all(got[0::2] == wa) and np.all(got[1::2] == wb), (n, max_grid)
 
 
 def test_two_streams_do_not_share_a_workspace(dev):
@@ -485,6 +507,32 @@ def test_multipass_misaligned_unrolls_and_closed_forms(dev, m):
     assert abs(out.item() - 70000 * 2.0 ** -24) <= TOL * 70000 * 2.0 ** -24
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("value", [-128, 127])
+def test_int32_accumulators_at_the_longest_chain(dev, variant, value):
+    """One block, the longest chain that can be asked for, every element at an extreme: 2^31 int8 values in 65536
+    loop iterations of one block.  The int32 accumulators must not wrap (the library lowers the chain where they would)."""
+    n = 1 << 31
+    x = torch.full((n,), value, dtype=torch.int8, device=dev)
+    redux.set_variant(variant)
+    redux.set_param("max_chain", 65536)
+    redux.set_param("max_grid", 1)
+    got = redux.sum(x)
+    torch.cuda.synchronize()
+    assert int(got.item()) == value * n
+    del x
+    # one wavefront per segment with eight loads per lane: one accumulator takes every MMA of an iteration
+    nseg, seglen = 3, (1 << 28) + 17
+    xs = torch.full((nseg * seglen,), value, dtype=torch.int8, device=dev)
+    redux.set_param("max_grid", 16384)
+    redux.set_param("seg_block_bytes", 0)
+    redux.set_param("seg_parts", 1)
+    redux.set_param("unroll", 8)
+    gots = redux.sum_segmented(xs, nseg, seglen)
+    torch.cuda.synchronize()
+    assert gots.cpu().tolist() == [value * seglen] * nseg
+
+
 # ---- stream capture: the library's launches replay correctly from a HIP graph ----------------------------------
 
 def test_graph_replay_matches_eager(dev):
@@ -528,6 +576,35 @@ def test_graph_replay_matches_eager(dev):
             assert torch.equal(got, want), rep
     check_f16(eager[0].item(), x.cpu().numpy())
     assert eager[2].item() == oracle.sum_i8(xi.cpu().numpy())[0]
+
+
+def test_graph_survives_growth_of_the_level_buffers(dev):
+    """A captured level-by-level sum holds the addresses of the library's arrays of partial sums.  A later, larger call
+    on the same stream outgrows them; the graph must still replay correctly (outgrown buffers are kept, not freed)."""
+    small, large = (1 << 20) + 5, (1 << 25) + 9
+    xs = to_dev(workloads.normal_f16(81, small), dev)
+    xl = to_dev(workloads.normal_f16(82, large), dev)
+    out_s = torch.zeros(1, dtype=torch.float32, device=dev)
+    out_l = torch.zeros(1, dtype=torch.float32, device=dev)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        redux.sum_multipass(xs, out=out_s)                    # creates this stream's buffers at the small size
+    stream.synchronize()
+    eager = out_s.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        redux.sum_multipass(xs, out=out_s)
+    for rep in range(3):
+        with torch.cuda.stream(stream):
+            redux.sum_multipass(xl, out=out_l)                # outgrows the buffers the graph was captured with
+        stream.synchronize()
+        check_f16(out_l.item(), xl.cpu().numpy())
+        out_s.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_s, eager), rep
+    check_f16(eager.item(), xs.cpu().numpy())
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -615,7 +692,7 @@ def test_randomised_shapes_and_settings(dev):
         redux.set_param("max_grid", int(rng.choice([1, 3, 64, 16384])))
         redux.set_param("max_chain", int(rng.choice([1, 7, 256])))
         redux.set_param("layout", int(rng.integers(0, 3)))
-        redux.set_param("finish", int(rng.integers(-1, 4)))
+        redux.set_param("finish", int(rng.integers(-1, 5)))
         redux.set_param("nontemporal", int(rng.integers(0, 2)))
         off = int(rng.integers(0, 8 if is_f16 else 16))
         if kind == "seg":

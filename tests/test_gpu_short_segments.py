@@ -80,7 +80,7 @@ def expect_short(nseg, seglen, kind):
     if seglen * ESIZE[kind] <= 1024 or wide_ok:
         assert plan.kernel == redux.KERNEL_SHORT, (kind, nseg, seglen, plan.kernel)
     else:
-        assert plan.kernel in (redux.KERNEL_TILES, redux.KERNEL_WAVE), (kind, nseg, seglen, plan.kernel)
+        assert plan.kernel in (redux.KERNEL_TILES, redux.KERNEL_RUNS), (kind, nseg, seglen, plan.kernel)
 
 
 @pytest.mark.parametrize("variant", VARIANTS)

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(redux.LIB_PATH), reason="libr
 
 ES = {redux.F16: 2, redux.I8: 1, redux.BF16: 2, redux.F32: 4, redux.F8E4M3: 1, redux.F8E5M2: 1}
 DTYPES = sorted(ES)
-PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short", "seg_ragged")
+PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short", "seg_ragged", "seg_runs", "seg_run_len", "seg_runs_max")
 
 
 @pytest.fixture(autouse=True)
@@ -44,16 +44,18 @@ def test_flat_plan_invariants(n, dtype, mis, cus, bpc, max_grid, unroll):
     nslab = p.vectors // (256 * p.unroll)
     assert 1 <= p.grid <= min(cus * bpc, max_grid, 16384)
     assert p.grid <= max(nslab, 1)
-    assert p.finish in (1, 2)
+    assert p.finish in (2, 4)
+    assert 1 <= p.chain <= 256                                       # the default max_chain, possibly lowered for int8
     assert p.kernel == redux.KERNEL_FLAT
 
 
 def test_flat_plan_defaults_on_mi355x():
     c3 = redux.plan_sum((1 << 30) + 12345, redux.F16, 0, 256)
-    assert (c3.unroll, c3.grid, c3.finish) == (8, 256, 2)           # one block per CU, 8 loads per lane, second kernel
+    assert (c3.unroll, c3.grid, c3.finish) == (8, 256, 4)           # one block per CU, 8 loads per lane, one kernel per call
     assert (c3.head, c3.tail, c3.vectors) == (0, 1, 134219271)      # the last 16-byte vector holds one element
     c1 = redux.plan_sum(1 << 20, redux.F16, 0, 256)
-    assert (c1.unroll, c1.grid, c1.finish) == (8, 64, 1)            # small: few blocks, finishes in the same kernel
+    assert (c1.unroll, c1.grid, c1.finish) == (8, 64, 4)            # small: few blocks, finishes in the same kernel
+    assert redux.plan_sum(1 << 26, redux.F16, 0, 256).finish == 2   # 128 MiB: all blocks arrive together, a second kernel finishes
     assert redux.plan_sum(0, redux.I8, 0, 256).grid == 1
 
 
@@ -89,8 +91,10 @@ def test_slab_schedule_is_balanced_and_die_blocked():
        dtype=st.sampled_from(DTYPES), aligned=st.booleans(), cus=st.sampled_from([1, 104, 256]),
        seg_parts=st.sampled_from([0, 0, 0, 2, 8, 64, 4096]), rows_max=st.sampled_from([64, 64, 0, 5]),
        seg_bpc=st.integers(0, 16), unroll=st.sampled_from([0, 1, 2, 4, 8]), block_bytes=st.sampled_from([32768, 32768, 0, 1000]),
-       seg_short=st.sampled_from([1, 1, 0]), seg_ragged=st.sampled_from([1, 1, 0]))
-def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll, block_bytes, seg_short, seg_ragged):
+       seg_short=st.sampled_from([1, 1, 0]), seg_ragged=st.sampled_from([1, 1, 0]), seg_runs=st.sampled_from([1, 1, 0]),
+       run_len=st.sampled_from([0, 0, 0, 1, 5, 16]), runs_max=st.sampled_from([7999, 7999, 1 << 18]))
+def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll, block_bytes, seg_short, seg_ragged,
+                                   seg_runs, run_len, runs_max):
     es = ES[dtype]
     addr = 4096 if aligned else 4096 + es
     redux.set_param("seg_parts", seg_parts)
@@ -100,6 +104,9 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
     redux.set_param("seg_block_bytes", block_bytes)
     redux.set_param("seg_short", seg_short)
     redux.set_param("seg_ragged", seg_ragged)
+    redux.set_param("seg_runs", seg_runs)
+    redux.set_param("seg_run_len", run_len)
+    redux.set_param("seg_runs_max", runs_max)
     p = redux.plan_sum_segmented(nseg, seglen, dtype, addr, cus)
     assert 1 <= p.grid <= 16 * cus
     limit = 4096 if dtype not in (redux.F32, redux.F8E4M3, redux.F8E5M2) else 1024    # variant auto: MMA family except for the 8-bit floats
@@ -136,9 +143,20 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
         else:
             assert p.part_len == seglen and p.finish == 0
         assert p.grid <= nseg * p.parts
+    elif p.kernel == redux.KERNEL_RUNS:
+        sb = seglen * es
+        assert seg_runs and 1008 < sb <= runs_max and p.parts == 1 and p.unroll in (4, 8) and p.finish == 0
+        assert not (block_bytes and sb >= block_bytes)
+        assert 1 <= p.vectors <= 16 and (run_len == 0 or p.vectors == run_len)
+        assert run_len or p.vectors <= nseg
+        nruns = -(-nseg // p.vectors)
+        assert p.grid <= max(1, -(-nruns // 4))                 # never more wavefronts than runs
+        assert 15 + p.vectors * sb < 1 << 32                    # a run's byte positions fit 32 bits
     else:
         assert p.unroll in (1, 2, 4, 8)
         assert not (seg_ragged and seglen * es <= 1008)
+        if seg_runs and 1008 < seglen * es <= runs_max:          # whole segments of this size go to the run kernel
+            assert p.kernel == redux.KERNEL_PIECES
         if p.kernel == redux.KERNEL_PIECES:
             assert p.parts > 1 and p.parts & (p.parts - 1) == 0
             assert nseg * p.parts <= 16384                      # piece totals fit the workspace
@@ -159,9 +177,22 @@ def test_segmented_plan_defaults_on_mi355x():
     c5 = redux.plan_sum_segmented(65536, 4096, redux.F16, 0, 256)
     assert (c5.kernel, c5.unroll, c5.grid, c5.parts) == (redux.KERNEL_WAVE, 2, 1024, 1)           # 512 vectors: two loads per lane, four blocks per CU
     redux.set_param("seg_tiles", 1)
-    assert redux.plan_sum_segmented(1023, 4096, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE    # too few segments
-    assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE
-    assert redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE  # 3 tiles: not a power of two
+    assert redux.plan_sum_segmented(1023, 4096, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE    # too few segments for the whole-tile kernel
+    assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE   # 8208 B: above the run kernel's range
+    three = redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256)                           # 3 KiB: not a power of two
+    assert (three.kernel, three.vectors, three.unroll, three.grid) == (redux.KERNEL_RUNS, 11, 4, 768)   # runs of 11, 1.94 rounds on three blocks per CU
+    few = redux.plan_sum_segmented(40, 2050, redux.F16, 0, 256)
+    assert (few.kernel, few.vectors, few.grid) == (redux.KERNEL_RUNS, 1, 10)                      # few segments: one per run
+    redux.set_variant("classic")
+    three = redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256)
+    assert (three.kernel, three.unroll) == (redux.KERNEL_RUNS, 8) and three.grid in (4 * 256, 8 * 256)
+    redux.set_variant("auto")
+    redux.set_param("seg_runs", 0)
+    assert redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE
+    redux.set_param("seg_runs", 1)
+    redux.set_param("seg_runs_max", 1 << 18)
+    assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_RUNS
+    redux.set_param("seg_runs_max", 7999)
     short = redux.plan_sum_segmented(1 << 22, 64, redux.F16, 0, 256)
     assert (short.kernel, short.vectors, short.unroll, short.grid) == (redux.KERNEL_SHORT, 8, 8, 256)   # 128 B: contiguous stream
     assert redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256).kernel == redux.KERNEL_SHORT     # every dtype
@@ -183,14 +214,15 @@ def test_segmented_plan_defaults_on_mi355x():
     redux.set_param("seg_ragged", 1)
     redux.set_param("seg_short", 1)
     ragged = redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256)                                 # misaligned base: 9 vectors
-    assert (ragged.kernel, ragged.vectors, ragged.grid) == (redux.KERNEL_RAGGED, 16, 8 * 256)
+    assert (ragged.kernel, ragged.vectors, ragged.grid) == (redux.KERNEL_RAGGED, 16, 2 * 256)            # 9 of 16 lanes busy: two blocks per CU
     ragged = redux.plan_sum_segmented(1 << 20, 100, redux.BF16, 0, 256)                               # 200 B anywhere: 14 vectors
     assert (ragged.kernel, ragged.vectors) == (redux.KERNEL_RAGGED, 16)
     assert redux.plan_sum_segmented(1 << 20, 3, redux.F8E4M3, 0, 256).vectors == 2                    # 3 B can straddle two vectors
     assert redux.plan_sum_segmented(1 << 20, 2, redux.F16, 0, 256).vectors == 1                       # 4 B on a 4-byte boundary cannot
     assert redux.plan_sum_segmented(1 << 20, 2, redux.F16, 2, 256).vectors == 2
-    assert redux.plan_sum_segmented(1 << 20, 252, redux.F32, 0, 256).vectors == 64                    # 1008 B: the longest
-    assert redux.plan_sum_segmented(1 << 20, 253, redux.F32, 0, 256).kernel == redux.KERNEL_WAVE
+    longest = redux.plan_sum_segmented(1 << 20, 252, redux.F32, 0, 256)                               # 1008 B: the longest
+    assert (longest.vectors, longest.grid) == (64, 256)                                               # 63 of 64 lanes busy: one block per CU
+    assert redux.plan_sum_segmented(1 << 20, 253, redux.F32, 0, 256).kernel == redux.KERNEL_RUNS
     redux.set_param("seg_ragged", 0)
     assert redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256).kernel == redux.KERNEL_WAVE
     redux.set_param("seg_ragged", 1)
@@ -202,7 +234,7 @@ def test_segmented_plan_defaults_on_mi355x():
     assert (long_.kernel, long_.parts, long_.part_len) == (redux.KERNEL_PIECES, 8, 131072)
     redux.set_param("seg_block_bytes", 32768)
     assert redux.plan_sum_segmented(1, 100, redux.I8, 0, 256).kernel == redux.KERNEL_RAGGED
-    assert redux.plan_sum_segmented(1, 2000, redux.I8, 0, 256).kernel == redux.KERNEL_WAVE
+    assert redux.plan_sum_segmented(1, 2000, redux.I8, 0, 256).kernel == redux.KERNEL_RUNS
 
 
 def test_plan_argument_errors():
@@ -219,3 +251,33 @@ def test_plan_argument_errors():
         redux.plan_block_slabs(3, 10, 4, 0)
     with pytest.raises(redux.ReduxError):
         redux.plan_block_slabs(0, 10, 4, 4)
+
+
+@settings(max_examples=300, deadline=None)
+@given(max_chain=st.sampled_from([1, 100, 256, 4096, 16384, 32768, 65536]), unroll=st.sampled_from([0, 1, 2, 4, 8]),
+       variant=st.sampled_from(["mfma", "classic"]), n=st.integers(1, 1 << 36), seg=st.booleans(),
+       block_bytes=st.sampled_from([0, 32768]))
+def test_int8_chain_never_lets_an_int32_accumulator_wrap(max_chain, unroll, variant, n, seg, block_bytes):
+    """chain x (largest magnitude one loop iteration can add to an accumulator entry) stays below 2^31:
+    an int8 MFMA adds at most 64 x 128 per entry, the classic dot product at most 4 x 128 per running sum and vector."""
+    keep = redux.get_param("max_chain"), redux.get_variant()
+    redux.set_param("max_chain", max_chain)
+    redux.set_param("unroll", unroll)
+    redux.set_param("seg_block_bytes", block_bytes)
+    redux.set_variant(variant)
+    try:
+        if seg:
+            p = redux.plan_sum_segmented(3, n, redux.I8, 0, 256)
+            chains = 4 if p.kernel == redux.KERNEL_BLOCK else 1
+        else:
+            p = redux.plan_sum(n, redux.I8, 0, 256)
+            chains = 4
+        assert 1 <= p.chain <= max_chain
+        if p.kernel in (redux.KERNEL_FLAT, redux.KERNEL_BLOCK, redux.KERNEL_WAVE, redux.KERNEL_PIECES):
+            per_iter = 8192 * -(-p.unroll // chains) if variant == "mfma" else 512 * p.unroll
+            assert p.chain * per_iter < 2 ** 31
+        # floating point: the setting is taken as it is
+        assert redux.plan_sum(n, redux.F16, 0, 256).chain == max_chain
+    finally:
+        redux.set_param("max_chain", keep[0])
+        redux.set_variant(keep[1])
