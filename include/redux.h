@@ -62,7 +62,9 @@ typedef enum {
     REDUX_ERR_HIP   = -5, /* a HIP call failed; see redux_last_hip_error() */
     REDUX_ERR_NOMEM = -6, /* the workspace could not be allocated */
     REDUX_ERR_ALIAS = -7, /* out lies inside the input range */
-    REDUX_ERR_PARAM = -8  /* unknown name or out-of-range value in redux_set_param / redux_set_variant */
+    REDUX_ERR_PARAM = -8, /* unknown name or out-of-range value in redux_set_param / redux_set_variant */
+    REDUX_ERR_SCRATCH = -9 /* redux_sum_static: the launch would write more than 2048 block partials, or the current
+                              device's ordinal is 64 or higher */
 } redux_status;
 
 /* Which kernel family computes the sum. */
@@ -97,6 +99,27 @@ typedef enum {
  * dtypes) adds in binary32 and stays within 1e-4 of sum|x| like the others.
  */
 int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
+
+/*
+ * redux_sum_static -- redux_sum for callers that must not allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same result bit for bit as redux_sum with
+ * the same settings; the only difference is where the block partials and the ticket live: not in the per-stream
+ * workspace that redux_sum allocates on first use, but in a static array in device memory (16 640 bytes per device,
+ * held from the moment the library's code is loaded on a device until the process ends).
+ *
+ *   - Calls no hipMalloc, hipFree or any other allocating routine, on any call.  The first call on a device asks the
+ *     runtime for the array's address on that device (hipGetSymbolAddress); make that call outside stream capture.
+ *   - Limit: the launch may write at most 2048 block partials.  A default launch writes one per compute unit (256 on
+ *     an MI355X); more than 2048 can only come from "blocks_per_cu" above 8 on such a device.  A call beyond the limit
+ *     returns REDUX_ERR_SCRATCH and launches nothing ("max_grid" = 2048 keeps any setting inside it).  Device
+ *     ordinals 0 .. 63.
+ *   - The array is shared by every call on a device and keeps what the last call left in it.  Each call clears the
+ *     ticket with a small fill kernel ahead of the sum (no memset node, so it can be captured); the partials need no
+ *     clearing.  Calls on ONE stream are ordered by the stream and are safe back to back.  Calls that overlap on one
+ *     device -- different streams, or different host threads on different streams -- race on the array and give
+ *     wrong sums: use redux_sum there, which keeps one workspace per stream.
+ */
+int redux_sum_static(const void *x, size_t n, int dtype, void *out, void *stream);
 
 /*
  * redux_sum_segmented -- nseg independent reductions: out[s] = sum_{k<seglen} x[s*seglen + k]

@@ -16,6 +16,14 @@
 
 using namespace redux;
 
+// ---- scratch memory of redux_sum_static: nothing is ever allocated for it ------------------------------------------
+// Block partials (8 bytes each) followed by the ticket on its own 256-byte line.  Every device the library runs on
+// holds its own copy of this array from the moment the code object is loaded until the process ends.
+constexpr int kScratchSlots = 2048;                              // block partials a launch may write
+constexpr size_t kScratchTicketOffset = (size_t)kScratchSlots * sizeof(u64);
+constexpr size_t kScratchBytes = kScratchTicketOffset + 256;    // 16 640 bytes
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 // ---- process-wide settings --------------------------------------------------------------------
@@ -75,6 +83,12 @@ constexpr size_t kTicketOffset = (size_t)kMaxGrid * sizeof(u64);
 constexpr size_t kWorkspaceBytes = kTicketOffset + 256;
 
 std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
+
+// In host code `scratch` is only a handle for the symbol, not an address in device memory: what kernels and fills get
+// is the address hipGetSymbolAddress returns for the device that is current, asked for once per device and kept here.
+constexpr int kStaticDevices = 64;
+void *g_scratch_ptr[kStaticDevices] = {};
+int g_static_cus[kStaticDevices] = {};
 std::map<int, int> g_cus;
 
 int device_cus(int dev, int *cus)
@@ -665,6 +679,51 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream)
     return launch_sum(S, cus, ws, false, x, n, es, dtype, out, st);
 }
 
+int redux_sum_static(const void *x, size_t n, int dtype, void *out, void *stream)
+{
+    std::call_once(g_env_once, read_env);
+    size_t es = 0;
+    int rc = check_common(x, n, dtype, out, 1, &es);
+    if (rc != REDUX_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (n == 0) return launch_empty_sum(dtype, out, st);
+
+    Settings S;
+    int cus = 0;
+    Workspace ws;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        S = g_set;
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return hip_fail(e);
+        if (dev < 0 || dev >= kStaticDevices) return REDUX_ERR_SCRATCH;
+        if (g_static_cus[dev] == 0) {
+            int c = 0;
+            e = hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e != hipSuccess) return hip_fail(e);
+            g_static_cus[dev] = c > 0 ? c : 1;
+        }
+        cus = g_static_cus[dev];
+        if (!g_scratch_ptr[dev]) {          // first call on this device, which is the current one
+            void *ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return hip_fail(e);
+            if (!ptr) return hip_fail(hipErrorInvalidSymbol);
+            g_scratch_ptr[dev] = ptr;
+        }
+        ws.partials = (u64 *)g_scratch_ptr[dev];
+        ws.ticket = (unsigned *)((char *)g_scratch_ptr[dev] + kScratchTicketOffset);
+    }
+    // The launch writes one partial per block.  More blocks than the array has slots can only be asked for through
+    // "blocks_per_cu" / "max_grid" on a device with many compute units; such a call is refused, never truncated.
+    const Run run = es == 4 ? make_run<4>(x, n) : es == 2 ? make_run<2>(x, n) : make_run<1>(x, n);
+    if (plan_flat(S, run.nvec, cus, dtype).grid > (unsigned)kScratchSlots) return REDUX_ERR_SCRATCH;
+    // the array keeps what the last call left in it: the ticket is cleared by a fill kernel ahead of the sum (the
+    // partials need no clearing, every slot that is read has been written by this call's blocks)
+    return launch_sum(S, cus, ws, true, x, n, es, dtype, out, st);
+}
+
 int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, void *out, void *stream)
 {
     std::call_once(g_env_once, read_env);
@@ -1072,6 +1131,7 @@ const char *redux_strerror(int status)
     case REDUX_ERR_NOMEM: return "workspace allocation failed";
     case REDUX_ERR_ALIAS: return "output lies inside the input range";
     case REDUX_ERR_PARAM: return "unknown parameter name or value out of range";
+    case REDUX_ERR_SCRATCH: return "redux_sum_static: the call needs more block partials (or a higher device ordinal) than its static scratch array provides";
     default: return "unknown status";
     }
 }

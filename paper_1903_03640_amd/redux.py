@@ -18,7 +18,7 @@ VARIANTS = {"auto": 0, "mfma": 1, "classic": 2}
 
 # every symbol include/redux.h declares
 SYMBOLS = (
-    "redux_sum", "redux_sum_segmented", "redux_sum_multipass", "redux_mma_group_probe", "redux_calibration_copy",
+    "redux_sum", "redux_sum_static", "redux_sum_segmented", "redux_sum_multipass", "redux_mma_group_probe", "redux_calibration_copy",
     "redux_plan_sum", "redux_plan_sum_segmented", "redux_plan_block_slabs",
     "redux_set_variant", "redux_get_variant", "redux_resolved_variant", "redux_set_param", "redux_get_param",
     "redux_strerror", "redux_last_hip_error", "redux_shutdown", "redux_version",
@@ -55,6 +55,8 @@ def load():
         vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
         lib.redux_sum.restype = ci
         lib.redux_sum.argtypes = [vp, sz, ci, vp, vp]
+        lib.redux_sum_static.restype = ci
+        lib.redux_sum_static.argtypes = [vp, sz, ci, vp, vp]
         lib.redux_sum_segmented.restype = ci
         lib.redux_sum_segmented.argtypes = [vp, sz, sz, ci, vp, vp]
         lib.redux_sum_multipass.restype = ci
@@ -138,6 +140,10 @@ def shutdown() -> None:
 
 def sum_raw(x_ptr: int, n: int, dtype: int, out_ptr: int, stream: int = 0) -> int:
     return load().redux_sum(x_ptr, n, dtype, out_ptr, stream)
+
+
+def sum_static_raw(x_ptr: int, n: int, dtype: int, out_ptr: int, stream: int = 0) -> int:
+    return load().redux_sum_static(x_ptr, n, dtype, out_ptr, stream)
 
 
 def sum_segmented_raw(x_ptr: int, nseg: int, seglen: int, dtype: int, out_ptr: int, stream: int = 0) -> int:
