@@ -284,7 +284,17 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               four per compute unit, take the pipelined one-wavefront-per-segment kernel (default 1)
  *   "seg_parts"         0,1,2,4,...,4096  segmented sum: pieces a long segment is cut into; 0 = from the
  *                               shape (default 0); ignored if nseg * pieces exceeds the workspace (16384)
+ *   "compensated"       0/1     redux_sum, binary16, MMA family: the first MMA runs with C = 0 and its row sums are added to the
+ *                               running sums with a two-sum on the vector ALU, the lost parts kept in a second
+ *                               accumulator (for the precision study: it buys nothing once chains are bounded, and costs
+ *                               vector instructions) (default 0)
  *   "lit_m"             4,16,32 redux_sum_multipass, binary16: linear size m of the MMA matrices (default 16)
+ *   "lit_half"          0/1     redux_sum_multipass, binary16, m = 16 (REDUX_ERR_PARAM from the call otherwise): the result of
+ *                               each of the two MMAs is rounded to binary16 and the partial sums are stored as binary16,
+ *                               Section I-B's half-precision multiply-accumulate and Section IV-B's results written back
+ *                               into X, both taken literally; the
+ *                               final value is that binary16 number widened (an infinity once a partial sum passes
+ *                               65504).  For measuring what that reading costs in accuracy, nothing else (default 0)
  *   "lit_unroll"        0,1,2,4,8,16  redux_sum_multipass: wavefront steps per loop iteration; 0 = the
  *                               measured best for the shape (default 0)
  *   "lit_blocks_per_cu" 0..16   redux_sum_multipass: 256-thread blocks per compute unit; 0 = the measured

@@ -41,11 +41,16 @@ def mma(A: np.ndarray, B: np.ndarray, C: np.ndarray) -> np.ndarray:
 
 
 def group_reduce(group: np.ndarray, rows: int, depth: int | None = None, cols: int | None = None,
-                 acc_dtype=np.float64) -> Tuple[np.ndarray, np.ndarray]:
+                 acc_dtype=np.float64, mma_dtype=None) -> Tuple[np.ndarray, np.ndarray]:
     """Two-MMA reduction M(x_1 .. x_{rows*depth}) of one group.
 
     Returns (D, D') where D = A x 1 + 0 and D' = 1 x D + 0.  ``group`` may be
     shorter than rows*depth: the rest of A is zero.
+
+    ``mma_dtype``: the precision the result of an MMA is held in.  Section I-B says both that
+    the multiply-accumulate works at half precision and that D can be kept in single precision;
+    passing np.float16 replays the first statement literally (each of the two results is
+    rounded to binary16 before anything else is done with it), None keeps acc_dtype.
     """
     depth = rows if depth is None else depth
     cols = rows if cols is None else cols
@@ -58,13 +63,20 @@ def group_reduce(group: np.ndarray, rows: int, depth: int | None = None, cols: i
     ones_B = np.ones((depth, cols), dtype=acc_dtype)
     zero_C = np.zeros((rows, cols), dtype=acc_dtype)
     D = mma(A, ones_B, zero_C)                       # first MMA: row sums in every column
+    if mma_dtype is not None:
+        with np.errstate(over="ignore"):
+            D = D.astype(mma_dtype).astype(acc_dtype)
     ones_A = np.ones((rows, rows), dtype=acc_dtype)
-    Dp = mma(ones_A, D, zero_C)                      # second MMA: the group total everywhere
+    with np.errstate(invalid="ignore"):              # (an infinity in D times the ones stays an infinity)
+        Dp = mma(ones_A, D, zero_C)                  # second MMA: the group total everywhere
+    if mma_dtype is not None:
+        with np.errstate(over="ignore"):
+            Dp = Dp.astype(mma_dtype).astype(acc_dtype)
     return D, Dp
 
 
 def reduce_level(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=np.float64,
-                 store_dtype=None) -> np.ndarray:
+                 store_dtype=None, mma_dtype=None) -> np.ndarray:
     """One level: every group of rows*depth inputs is replaced by its D'[0, 0].
 
     ``store_dtype`` is the type of the array the partial sums are written to.  The paper writes
@@ -77,7 +89,7 @@ def reduce_level(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=n
     ngroups = (x.size + gsz - 1) // gsz
     out = np.zeros(ngroups, dtype=acc_dtype)
     for k in range(ngroups):
-        _, Dp = group_reduce(x[k * gsz: (k + 1) * gsz], rows, depth, acc_dtype=acc_dtype)
+        _, Dp = group_reduce(x[k * gsz: (k + 1) * gsz], rows, depth, acc_dtype=acc_dtype, mma_dtype=mma_dtype)
         out[k] = Dp[0, 0]
     if store_dtype is not None:
         with np.errstate(over="ignore"):
@@ -86,7 +98,7 @@ def reduce_level(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=n
 
 
 def reduce_tc(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=np.float64,
-              store_dtype=None) -> Tuple[float, int, List[int]]:
+              store_dtype=None, mma_dtype=None) -> Tuple[float, int, List[int]]:
     """R_tc(X): apply levels until one value is left.
 
     Returns (result, number of levels, problem size entering each level).
@@ -99,7 +111,7 @@ def reduce_tc(x: np.ndarray, rows: int, depth: int | None = None, acc_dtype=np.f
     cur = x
     while True:
         sizes.append(int(cur.size))
-        cur = reduce_level(cur, rows, depth, acc_dtype=acc_dtype, store_dtype=store_dtype)
+        cur = reduce_level(cur, rows, depth, acc_dtype=acc_dtype, store_dtype=store_dtype, mma_dtype=mma_dtype)
         if cur.size == 1:
             return cur[0].item(), len(sizes), sizes
 

@@ -50,6 +50,8 @@ struct Settings {
     long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
     long lit_blocks_per_cu = 0;
     long lit_m = 16;              // linear size m of the MMA matrices of the level-by-level form
+    long compensated = 0;         // flat sum, binary16, MMA family: two-sum compensated chain (precision study)
+    long lit_half = 0;            // level-by-level form, binary16, m = 16: both MMA results and the partial sums in binary16
     long finish = -1;             // -1 = from the input size
     long pause = -1;              // flat sum: 64-cycle sleeps at the end of every loop iteration (-1 = measured best)
 };
@@ -161,14 +163,22 @@ template <int M, int U>
 void launch_literal_f16(bool first, bool fast, const void *in, u64 n, void *outp, unsigned grid, hipStream_t st)
 {
     if (first) {
-        if (fast) hipLaunchKernelGGL((literal_level_kernel<M, true, U, true>), dim3(grid), dim3(kBlock), 0, st, in, n, (float *)outp);
-        else      hipLaunchKernelGGL((literal_level_kernel<M, true, U, false>), dim3(grid), dim3(kBlock), 0, st, in, n, (float *)outp);
+        if (fast) hipLaunchKernelGGL((literal_level_kernel<M, true, U, true>), dim3(grid), dim3(kBlock), 0, st, in, n, outp, 1);
+        else      hipLaunchKernelGGL((literal_level_kernel<M, true, U, false>), dim3(grid), dim3(kBlock), 0, st, in, n, outp, 1);
     } else {
         // (sixteen 32 x 32 tiles of binary32 per wavefront step would not fit the register file; the kernel loops over
         // its own batches, so any grid fits any U)
         constexpr int UL = (M == 32 && U > 8) ? 8 : U;
-        hipLaunchKernelGGL((literal_level_kernel<M, false, UL, true>), dim3(grid), dim3(kBlock), 0, st, in, n, (float *)outp);
+        hipLaunchKernelGGL((literal_level_kernel<M, false, UL, true>), dim3(grid), dim3(kBlock), 0, st, in, n, outp, 1);
     }
+}
+
+// the binary16-throughout form (m = 16): every level reads binary16; `last` says whether outp is the caller's binary32 result
+template <int U>
+void launch_literal_half(bool fast, bool last, const void *in, u64 n, void *outp, unsigned grid, hipStream_t st)
+{
+    if (fast) hipLaunchKernelGGL((literal_level_kernel<16, true, U, true, true>), dim3(grid), dim3(kBlock), 0, st, in, n, outp, last ? 1 : 0);
+    else      hipLaunchKernelGGL((literal_level_kernel<16, true, U, false, true>), dim3(grid), dim3(kBlock), 0, st, in, n, outp, last ? 1 : 0);
 }
 
 template <int U>
@@ -330,6 +340,8 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "seg_run_len")) { *lo = 0; *hi = 16; return &g_set.seg_run_len; }
     if (!std::strcmp(name, "seg_tiles")) { *lo = 0; *hi = 1; return &g_set.seg_tiles; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
+    if (!std::strcmp(name, "compensated")) { *lo = 0; *hi = 1; return &g_set.compensated; }
+    if (!std::strcmp(name, "lit_half")) { *lo = 0; *hi = 1; return &g_set.lit_half; }
     if (!std::strcmp(name, "lit_m")) { *lo = 4; *hi = 32; return &g_set.lit_m; }
     if (!std::strcmp(name, "lit_unroll")) { *lo = 0; *hi = 16; return &g_set.lit_unroll; }
     if (!std::strcmp(name, "lit_blocks_per_cu")) { *lo = 0; *hi = 16; return &g_set.lit_blocks_per_cu; }
@@ -633,7 +645,8 @@ static int launch_sum(const Settings &S, int cus, const Workspace &ws, bool clea
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
     }
-    with_flat_family(dtype, mfma, [&](auto family) { launch_flat<decltype(family)>(unroll, nt, grid, st, a); });
+    if (S.compensated && dtype == REDUX_F16 && mfma) launch_flat<F16MfmaCompensated>(unroll, nt, grid, st, a);
+    else with_flat_family(dtype, mfma, [&](auto family) { launch_flat<decltype(family)>(unroll, nt, grid, st, a); });
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     if (a.finish == 2) {
@@ -921,6 +934,8 @@ int redux_sum_multipass(const void *x, size_t n, int dtype, void *out, int *leve
 
     // group size m*m (m = 4, 16 or 32) for binary16; the int8 form has one shape (16 x 32, then 16 x 16)
     const int m = dtype == REDUX_F16 ? (int)S.lit_m : 16;
+    const bool half = S.lit_half != 0;                  // binary16 throughout: the measuring form for binary16 and m = 16
+    if (half && (dtype != REDUX_F16 || m != 16)) return REDUX_ERR_PARAM;
     const u64 group = (u64)m * m;
     const u64 first_group = dtype == REDUX_F16 ? group : (u64)kLitGroupI8;
     const u64 tile = m == 32 ? 1024 : 256;                                   // elements one wavefront step consumes
@@ -953,7 +968,11 @@ int redux_sum_multipass(const void *x, size_t n, int dtype, void *out, int *leve
         const bool fast = ((uintptr_t)in % (dtype == REDUX_F16 && m == 32 ? 16 : 8)) == 0;
 #define REDUX_LIT_U(CALL) switch (U) { case 16: CALL(16); break; case 8: CALL(8); break; case 4: CALL(4); break; \
                                        case 2: CALL(2); break; default: CALL(1); break; }
-        if (dtype == REDUX_F16) {
+        if (half) {
+#define REDUX_LIT_HALF(UU) launch_literal_half<UU>(fast, ngroups == 1, in, count, outp, grid, st)
+            REDUX_LIT_U(REDUX_LIT_HALF)
+#undef REDUX_LIT_HALF
+        } else if (dtype == REDUX_F16) {
 #define REDUX_LIT_M4(UU) launch_literal_f16<4, UU>(first, fast, in, count, outp, grid, st)
 #define REDUX_LIT_M16(UU) launch_literal_f16<16, UU>(first, fast, in, count, outp, grid, st)
 #define REDUX_LIT_M32(UU) launch_literal_f16<32, UU>(first, fast, in, count, outp, grid, st)

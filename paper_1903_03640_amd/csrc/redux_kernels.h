@@ -251,6 +251,46 @@ template <int NACC> using F16MfmaT = FloatMfmaT<kF16, NACC>;
 typedef F16MfmaT<4> F16Mfma;      // flat sum: four chains, folded once per wavefront
 typedef F16MfmaT<1> F16MfmaSeg;   // segmented sum: one chain, so the per-segment fold is four MFMAs
 
+// Compensated chain (binary16 only; for the precision study, not a default).  The matrix unit does not expose the
+// rounding error of its own accumulate, so the chain cannot be compensated inside the MMA.  What can be done: the first
+// MMA runs with C = 0 as the paper writes it, D = A x 1 gives the tile's sixteen row sums, and those are added to
+// the running sums on the vector ALU with Knuth's two-sum, whose second output is exactly what the addition lost;
+// the lost parts are collected in a second accumulator and both are folded by the second MMA.
+struct F16MfmaCompensated {
+    typedef double Total;
+    typedef float Out;
+    static constexpr int kElemSize = 2;
+    static constexpr bool kMfmaFinish = true;
+    struct Acc { f32x4 sum, lost; };
+
+    static __device__ __forceinline__ void clear(Acc &c)
+    {
+        c.sum = f32x4{0.f, 0.f, 0.f, 0.f};
+        c.lost = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    static __device__ __forceinline__ void consume(Acc &c, int U, u32x4 v)
+    {
+        const f32x4 r = mma1_chain<kF16>(v, f32x4{0.f, 0.f, 0.f, 0.f});      // D = A x 1 + 0
+        const f32x4 t = c.sum + r;
+        const f32x4 bb = t - c.sum;
+        c.lost += (c.sum - (t - bb)) + (r - bb);                             // two-sum: t + this term == sum + r exactly
+        c.sum = t;
+    }
+    static __device__ __forceinline__ Total fold(Acc &c)
+    {
+        f32x4 dp = {0.f, 0.f, 0.f, 0.f}, dl = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            dp = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, c.sum[r], dp, 0, 0, 0);
+            dl = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, c.lost[r], dl, 0, 0, 0);
+        }
+        clear(c);
+        return (double)uniform_f32(dp[0]) + (double)uniform_f32(dl[0]);
+    }
+    static __device__ __forceinline__ u32x4 edge(const void *p) { return edge_bits<kElemSize>(p); }
+    static __device__ __forceinline__ Out to_out(Total t) { return (float)t; }
+};
+
 template <int KIND>
 struct FloatClassic {
     typedef double Total;

@@ -21,6 +21,13 @@
 //                                   (v_mfma_f64_16x16x4_f64), which is exact below 2^53.
 // Element -> (row, k) placement inside a group follows the lane order above (coalesced); any placement
 // gives the same additions because B is all ones.
+//
+// Binary16 throughout (HALF, m = 16 only): Section I-B says that the multiply-accumulate itself works at half
+// precision, and Section IV-B has every group result written back into X, a binary16 array; this is both taken literally.  The result
+// of each of the two MMAs is rounded to binary16, the partial sums are stored as binary16 and every level reads
+// binary16.  The matrix unit has no binary16 accumulator, so the rounding is applied to what the MFMA returns: a
+// lower bound on the damage, since a true binary16 accumulate would also round inside the MMA.  It exists to be
+// measured (it overflows to infinity as soon as a partial sum passes 65504), not to be used.
 #pragma once
 #include "redux_kernels.h"
 
@@ -87,6 +94,9 @@ template <> struct LitShape<4> {
     }
 };
 
+// a binary32 value rounded to binary16 (to nearest even; above 65504 + 16 it becomes an infinity) and widened again
+__device__ __forceinline__ float through_binary16(float v) { return (float)(_Float16)v; }
+
 template <> struct LitShape<16> {
     static constexpr unsigned kGroup = 256, kTileElems = 256, kResults = 1;
     static __device__ __forceinline__ void mma_f16(const unsigned *raw, float *res)
@@ -95,6 +105,16 @@ template <> struct LitShape<16> {
         const f16x4 a = __builtin_bit_cast(f16x4, u32x2{raw[0], raw[1]});
         f32x4 d = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
         *res = lit_mma2_f32(d);
+    }
+    // the same with D and D' held in binary16
+    static __device__ __forceinline__ void mma_f16_half(const unsigned *raw, float *res)
+    {
+        const f16x4 ones = {1, 1, 1, 1};
+        const f16x4 a = __builtin_bit_cast(f16x4, u32x2{raw[0], raw[1]});
+        f32x4 d = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) d[r] = through_binary16(d[r]);
+        *res = through_binary16(lit_mma2_f32(d));
     }
     static __device__ __forceinline__ void mma_f32(const unsigned *raw, float *res)
     {
@@ -147,9 +167,17 @@ template <> struct LitShape<32> {
 // ---- one level: binary16 input (F16IN) or binary32 partial sums -------------------------------------------------
 // One wavefront reduces U tiles per iteration.  FAST: the input is aligned to the load width, so a lane's
 // words come from 8- or 16-byte loads; otherwise (and for the ragged last tile) element loads with zero padding.
-template <int M, bool F16IN, int U, bool FAST>
-__global__ void __launch_bounds__(kBlock) literal_level_kernel(const void *xin, u64 n, float *partial)
+// HALF (m = 16, binary16 input): both MMA results rounded to binary16, partial sums stored as binary16.
+template <int M, bool F16IN, int U, bool FAST, bool HALF = false>
+__global__ void __launch_bounds__(kBlock) literal_level_kernel(const void *xin, u64 n, void *pout, int out_is_binary32)
 {
+    static_assert(!HALF || (M == 16 && F16IN), "the binary16 form exists for m = 16 only and reads binary16 at every level");
+    // where group results go: the array of partial sums (binary32, or binary16 in the HALF form), or -- the last
+    // level -- the caller's binary32 result
+    auto put = [&](u64 g, float v) {
+        if (!HALF || out_is_binary32) ((float *)pout)[g] = v;
+        else ((_Float16 *)pout)[g] = (_Float16)v;       // (already a binary16 value: exact)
+    };
     typedef LitShape<M> S;
     constexpr unsigned kElemBytes = F16IN ? 2 : 4;
     constexpr unsigned kWords = S::kTileElems * kElemBytes / 4 / 64;      // raw 32-bit words per lane per tile
@@ -210,15 +238,17 @@ __global__ void __launch_bounds__(kBlock) literal_level_kernel(const void *xin, 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float res;
-            if (F16IN) S::mma_f16(raw[u], &res); else S::mma_f32(raw[u], &res);
+            if constexpr (HALF) S::mma_f16_half(raw[u], &res);
+            else if (F16IN) S::mma_f16(raw[u], &res);
+            else S::mma_f32(raw[u], &res);
             if (S::kResults == 1) {
                 if (lane == (unsigned)u) mine = res;           // lane u is in charge of tile t0 + u
             } else {                                           // m = 4: lane 4b is in charge of block b of the tile
                 const u64 g = (t0 + u) * S::kResults + (lane >> 2);
-                if ((lane & 3u) == 0 && g < ngroups) partial[g] = res;
+                if ((lane & 3u) == 0 && g < ngroups) put(g, res);
             }
         }
-        if (S::kResults == 1 && lane < (unsigned)U && t0 + lane < ngroups) partial[t0 + lane] = mine;
+        if (S::kResults == 1 && lane < (unsigned)U && t0 + lane < ngroups) put(t0 + lane, mine);
     }
 }
 

@@ -9,6 +9,10 @@ this library and (on the CPU) for the two ways the paper's text can be read:
                    single binary32 running sum over its whole share of the array
   gpu classic      redux_sum, classic family
   gpu multipass    redux_sum_multipass: groups of 256, binary32 partial sums in memory
+  gpu half         redux_sum_multipass with "lit_half": both MMA results rounded to binary16, partial sums stored as
+                   binary16 -- what the paper's wording describes when it is taken literally
+  gpu comp         redux_sum with "compensated": first MMA with C = 0, row sums added with a two-sum on the vector ALU
+  gpu comp long    the same with one block and no chain bound
   replay f32       numpy replay of the published algorithm with binary32 partial sums
   replay f16       the same with the partial sums written back into a binary16 array, as
                    Section IV-B literally says (small n only; it overflows above 65504)
@@ -59,6 +63,8 @@ def dev():
     redux.set_variant("auto")
     redux.set_param("max_chain", 256)
     redux.set_param("max_grid", 16384)
+    redux.set_param("lit_half", 0)
+    redux.set_param("compensated", 0)
 
 
 @pytest.mark.parametrize("dist", ["uniform01", "normal", "tenth", "wide"])
@@ -83,6 +89,19 @@ def test_precision_table(dev, dist):
         res["classic"] = redux.sum(xd).item()
         redux.set_variant("auto")
         res["multipass"] = redux.sum_multipass(xd)[0].item()
+        redux.set_param("lit_half", 1)
+        res["half"] = redux.sum_multipass(xd)[0].item()
+        redux.set_param("lit_half", 0)
+        redux.set_variant("mfma")
+        redux.set_param("compensated", 1)
+        res["comp"] = redux.sum(xd).item()
+        redux.set_param("max_chain", 65536)
+        redux.set_param("max_grid", 1)
+        res["comp long"] = redux.sum(xd).item()
+        redux.set_param("max_chain", 256)
+        redux.set_param("max_grid", 16384)
+        redux.set_param("compensated", 0)
+        redux.set_variant("auto")
         torch.cuda.synchronize()
         if lg <= 20:
             with np.errstate(invalid="ignore", over="ignore"):
@@ -93,8 +112,16 @@ def test_precision_table(dev, dist):
         # the default path: the derived first-order bound, and the library's stated tolerance
         assert rel["mfma"] <= (2 * 256 + 96) * U32
         assert rel["classic"] <= 1e-4 and rel["multipass"] <= 1e-4
+        # compensation: within two roundings of the binary32 result whatever the chain length is
+        assert rel["comp"] <= 2 * U32 and rel["comp long"] <= 2 * U32
+        # binary16 throughout: of binary16 size while everything fits, infinite (or NaN: inf - inf) once a partial sum does not
+        if math.isfinite(res["half"]):
+            assert rel["half"] <= 4 * 2.0 ** -11, (dist, lg, rel["half"])
+            assert rel["half"] >= rel["multipass"]
+        else:
+            assert dist != "normal" and sum_abs > 65504
     print("\n%s: |error| / sum|x|   (2^-24 = %.2e)" % (dist, U32))
-    names = ["mfma", "mfma long", "classic", "multipass", "replay f32", "replay f16"]
+    names = ["mfma", "mfma long", "comp", "comp long", "classic", "multipass", "half", "replay f32", "replay f16"]
     print("  log2 n  sum|x|      exact sum      " + "".join("%-12s" % k for k in names))
     for lg, sum_abs, exact, rel in rows:
         print("  %-6d  %-10.4g  %-13.6g  " % (lg, sum_abs, exact) +
@@ -141,3 +168,74 @@ def test_error_vs_chain_length(dev):
         assert rels[0] <= 2 * U32                          # folded every iteration: only the final rounding is left
     redux.set_param("max_chain", 256)
     redux.set_param("max_grid", 16384)
+
+
+def test_binary16_throughout_pins_and_replay(dev):
+    """The binary16-throughout form of the level-by-level sum: closed forms with exact partial sums, the overflow at
+    65504, and agreement with the numpy replay of the same reading (both round each MMA result and each stored partial
+    sum to binary16; the matrix unit adds a row's sixteen products in binary32 in its own order, the replay in numpy's,
+    so the two can differ by one binary16 rounding per level where a sum falls next to a rounding boundary)."""
+    redux.set_param("lit_half", 1)
+    ones = lambda n, v=1.0: torch.full((n,), v, dtype=torch.float16, device=dev)
+    assert redux.sum_multipass(ones(65280))[0].item() == 65280.0          # 255 x 256: representable (spacing 32)
+    assert redux.sum_multipass(ones(25607))[0].item() == 25600.0          # rounds down (spacing 16)
+    assert redux.sum_multipass(ones(65536))[0].item() == math.inf         # 65520 and above round to infinity
+    assert redux.sum_multipass(ones(1 << 24))[0].item() == math.inf
+    assert redux.sum_multipass(ones(1 << 17, -1.0))[0].item() == -math.inf
+    out, levels = redux.sum_multipass(ones(1 << 17, 0.25))
+    assert out.item() == 32768.0 and levels == 3                          # same level count as the binary32 form
+    g = np.full(256, 8.0, np.float16)
+    g[0] = 8.0078125                                                      # the row sum 128.0078125 does not fit binary16
+    assert redux.sum_multipass(torch.from_numpy(g).to(dev))[0].item() == 2048.0
+    redux.set_param("lit_half", 0)
+    assert redux.sum_multipass(torch.from_numpy(g).to(dev))[0].item() == 2048.0078125
+    for n, seed in ((300, 1), (4096, 2), (1 << 14, 3), ((1 << 16) + 77, 4)):
+        x = workloads.uniform_f16(seed, n)
+        redux.set_param("lit_half", 1)
+        got = redux.sum_multipass(torch.from_numpy(x).to(dev))[0].item()
+        redux.set_param("lit_half", 0)
+        want = mr.reduce_tc(x, 16, acc_dtype=np.float32, store_dtype=np.float16, mma_dtype=np.float16)[0]
+        exact = float(x.astype(np.float64).sum())
+        assert abs(got - want) <= 2 * 2.0 ** -11 * exact, (n, got, want)
+        assert abs(got - exact) <= 4 * 2.0 ** -11 * exact
+    # the form is for binary16 and m = 16 only
+    redux.set_param("lit_half", 1)
+    redux.set_param("lit_m", 4)
+    with pytest.raises(redux.ReduxError):
+        redux.sum_multipass(ones(1000))
+    redux.set_param("lit_m", 16)
+    with pytest.raises(redux.ReduxError):
+        redux.sum_multipass(torch.ones(1000, dtype=torch.int8, device=dev))
+    redux.set_param("lit_half", 0)
+
+
+def test_compensation_gains_nothing_once_chains_are_bounded(dev):
+    """|error| in units of the binary32 result's last place, against the exact sum: the bounded chain with its binary64
+    cascade is already within one rounding of the output format, so a compensated chain has nothing left to gain; it
+    only matters where the chain is not bounded (one block, 2^27 elements).  Run with -s for the table."""
+    n = 1 << 27
+    print("\n|error| / ulp(binary32 result), n = 2^27")
+    print("  dist       default   compensated   one block, unbounded   one block, unbounded, compensated")
+    for dist in ("uniform01", "tenth", "normal", "wide"):
+        x = make(dist, n, 99)
+        _, sum_abs, units, nonfinite = oracle.sum_f16_exact(x)
+        assert not nonfinite
+        exact = units / float(1 << 24)
+        ulp = float(np.spacing(np.float32(abs(exact)))) if exact != 0 else 2.0 ** -149
+        xd = torch.from_numpy(x).to(dev)
+        redux.set_variant("mfma")
+        res = []
+        for comp, chain, grid in ((0, 256, 16384), (1, 256, 16384), (0, 65536, 1), (1, 65536, 1)):
+            redux.set_param("compensated", comp)
+            redux.set_param("max_chain", chain)
+            redux.set_param("max_grid", grid)
+            res.append(abs(redux.sum(xd).item() - exact) / ulp)
+        redux.set_param("compensated", 0)
+        redux.set_param("max_chain", 256)
+        redux.set_param("max_grid", 16384)
+        print("  %-10s %-9.2f %-13.2f %-22.1f %.2f" % (dist, res[0], res[1], res[2], res[3]))
+        if dist != "normal" and dist != "wide":              # (cancelling sums: the result's ulp is far below sum|x| * 2^-24)
+            assert res[0] <= 1.0 and res[1] <= 1.0           # one rounding of the output
+            assert res[3] <= 1.0
+        assert res[3] <= res[2] + 0.51
+    redux.set_variant("auto")

@@ -2,6 +2,8 @@
 import os
 from fractions import Fraction
 
+import math
+
 import numpy as np
 import pytest
 
@@ -113,3 +115,38 @@ def test_partial_sums_stored_as_binary16_lose_precision_and_overflow():
     big = np.ones(1 << 17, dtype=np.float16)            # true sum 131072 > 65504
     assert mr.reduce_tc(big, 16, acc_dtype=np.float32)[0] == float(1 << 17)
     assert np.isinf(mr.reduce_tc(big, 16, acc_dtype=np.float32, store_dtype=np.float16)[0])
+
+
+# ---- binary16 throughout: both MMA results and the stored partial sums rounded to binary16 ----------------------
+
+HALF = dict(acc_dtype=np.float32, store_dtype=np.float16, mma_dtype=np.float16)
+
+
+def test_binary16_throughout_closed_forms_and_overflow():
+    """All-ones arrays have exact partial sums as long as they fit binary16: 65280 = 255 groups of 256 is representable
+    (spacing 32 between 2^15 and 2^16), so the replay is exact there; 65520 and everything above rounds to infinity
+    (the largest finite binary16 is 65504), so n = 65536 ones gives inf, and so does any longer array."""
+    assert mr.reduce_tc(np.ones(65280, np.float16), 16, **HALF)[0] == 65280.0
+    assert mr.reduce_tc(np.ones(256 * 100 + 7, np.float16), 16, **HALF)[0] == 25600.0    # 25607 rounds to 25600 (spacing 16 from 2^14 to 2^15)
+    assert mr.reduce_tc(np.ones(65536, np.float16), 16, **HALF)[0] == math.inf
+    assert mr.reduce_tc(np.ones(1 << 20, np.float16), 16, **HALF)[0] == math.inf
+    assert mr.reduce_tc(-np.ones(1 << 17, np.float16), 16, **HALF)[0] == -math.inf
+    # a group whose row sums are representable but whose total is not: 16 rows of 16 x 2049/2048-ish values
+    g = np.full(256, 8.0, np.float16)
+    g[0] = 8.0078125                                              # 8 + 2^-7: the row sum 128.0078125 needs 15 bits, rounds to 128
+    D, Dp = mr.group_reduce(g, 16, acc_dtype=np.float32, mma_dtype=np.float16)
+    assert D[0, 0] == 128.0 and Dp[0, 0] == 2048.0
+    D, Dp = mr.group_reduce(g, 16, acc_dtype=np.float32)
+    assert D[0, 0] == 128.0078125 and Dp[0, 0] == 2048.0078125
+
+
+def test_binary16_throughout_error_is_of_binary16_size():
+    rng = np.random.default_rng(3)
+    for n in (300, 4096, 1 << 14):
+        x = rng.random(n).astype(np.float16)
+        exact = float(x.astype(np.float64).sum())
+        half = mr.reduce_tc(x, 16, **HALF)[0]
+        single = mr.reduce_tc(x, 16, acc_dtype=np.float32)[0]
+        assert abs(single - exact) <= 4 * 2.0 ** -24 * exact
+        assert abs(half - exact) <= 3 * 2.0 ** -11 * exact       # three roundings to 11 bits per level, two levels
+        assert abs(half - exact) > abs(single - exact)
