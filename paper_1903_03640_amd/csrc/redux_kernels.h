@@ -231,15 +231,17 @@ struct FloatMfmaT {
     {
         c.d[U % kNumAcc] = mma1_chain<KIND>(v, c.d[U % kNumAcc]);
     }
-    // second MMA: D' <- 1 x D, chained over the four register slices of every accumulator
+    // second MMA: D' <- 1 x D, chained over the four register slices of D.  The independent chains hold D_1 .. D_k with
+    // D = D_1 + ... + D_k; the MMA is linear, so they are added entry by entry first and folded once (four dependent
+    // MFMAs instead of 4 k at the end of every wavefront).
     static __device__ __forceinline__ Total fold(Acc &c)
     {
+        f32x4 d = c.d[0];
+#pragma unroll
+        for (int i = 1; i < kNumAcc; ++i) d += c.d[i];
         f32x4 dp = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < kNumAcc; ++i)
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                dp = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, c.d[i][r], dp, 0, 0, 0);
+        for (int r = 0; r < 4; ++r) dp = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, d[r], dp, 0, 0, 0);
         clear(c);
         return (double)uniform_f32(dp[0]);
     }
@@ -484,7 +486,7 @@ struct FlatArgs {
     int layout;         // which slabs a block takes (see slab_schedule)
     int finish;         // 0/1/4: the last block to arrive sums the partials; 2: a second kernel does; 3: atomic additions
     unsigned stagger;   // start of wavefront w delayed by w x stagger x 64 cycles (long runs only)
-    unsigned pause;     // every loop iteration ends with this many 64-cycle sleeps (experiment)
+    unsigned pause;     // every loop iteration ends with this many 64-cycle sleeps
 };
 
 constexpr int kXcds = 8;  // workgroup b is dispatched to accelerator die b % 8

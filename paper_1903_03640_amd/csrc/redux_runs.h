@@ -76,7 +76,10 @@ __device__ __forceinline__ void run_load(u32x4 *cur, const RunGeometry &g, unsig
 {
     if (v0 + 64u * U <= g.nvec) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) cur[u] = load16<NT>(g.base + v0 + 64u * (unsigned)u + lane);
+        for (int u = 0; u < U; ++u) {              // issued in the order they are used in: the waits count on it
+            cur[u] = load16<NT>(g.base + v0 + 64u * (unsigned)u + lane);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     } else {
 #pragma unroll
         for (int u = 0; u < U; ++u) {

@@ -80,7 +80,22 @@ def test_streaming_loops_issue_all_loads_before_the_first_wait(kernels):
         assert runs, name
 
 
+def test_run_kernels_wait_for_the_oldest_load_first(kernels):
+    # run-of-segments kernels: U loads per iteration, and the first use waits for the oldest of them only
+    # (vmcnt(U - 1)): everything about a run is wavefront-uniform, so no load sits under a lane-dependent branch
+    for u in (4, 8):
+        for name in pick(kernels, "sum_segment_runs_mfma_kernel", "Li%dELb1E" % u):
+            body = kernels[name][0]
+            assert re.search(r"s_waitcnt vmcnt\(%d\)" % (u - 1), body), name
+            # the boundaries are walked in scalar registers: scalar branches outnumber the lane-mask ones (the classic
+            # family's "lane 0 stores" among them) by far
+            assert body.count("s_cbranch_scc") > 2 * body.count("s_cbranch_exec"), name
+
+
 def test_register_counts(kernels):
+    for name in pick(kernels, "sum_segment_runs_"):
+        assert kernels[name][1] <= 128, (name, kernels[name][1])       # four blocks per compute unit fit
+
     for name in pick(kernels, "sum_flat_kernel"):
         assert kernels[name][1] <= 128, (name, kernels[name][1])
     for name in pick(kernels, "sum_short_classic_kernel"):
