@@ -7,7 +7,7 @@ Prints ONE JSON line (see the keys below).  Usage:
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--settle SECONDS] [--workload C1..C5]
                     [--variant auto|mfma|classic|multipass] [--seglen L] [--set NAME=VALUE] [--no-cpu-baseline]
-                    [--no-by-variant]
+                    [--no-by-variant] [--ab-rounds R] [--lean]
 
 Order of events
     settle   `--settle` seconds (default 0.25) of untimed calls: after an idle period -- and generating the input on the
@@ -48,6 +48,16 @@ HBM_PEAK_GBPS = 8000.0
 # FETCH_SIZE + WRITE_SIZE, scaled by what the same counters read for a plain copy of known size, for the HBM bytes).
 # (workload, family actually run): (HBM bytes per launch, kernel, average kernel duration in us, summary).  Absent = not profiled.
 PROFILED = {
+    ('C1', 'classic'): (2218963, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 5.44, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C1', 'mfma'): (2219987, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 4.98, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C2', 'classic'): (134348897, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 19.75, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C2', 'mfma'): (134349292, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 19.16, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C3', 'classic'): (2147631491, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 288.99, 'profiles/redux_sum_f16_C3.md'),
+    ('C3', 'mfma'): (2147632558, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 289.79, 'profiles/redux_sum_f16_C3.md'),
+    ('C4', 'classic'): (1073873164, 'sum_flat_kernel<I8Classic, 8, true>', 147.29, 'profiles/redux_sum_i8_C4.md'),
+    ('C4', 'mfma'): (1073876236, 'sum_flat_kernel<I8MfmaT<4>, 8, true>', 144.86, 'profiles/redux_sum_i8_C4.md'),
+    ('C5', 'classic'): (537428756, 'sum_segments_tiles_kernel<FloatClassic<0>, 8, true, 0>', 74.66, 'profiles/redux_sum_segmented_f16_C5.md'),
+    ('C5', 'mfma'): (537425734, 'sum_segments_tiles_kernel<FloatMfmaT<0, 1>, 8, true, 1>', 74.32, 'profiles/redux_sum_segmented_f16_C5.md'),
 }
 
 
@@ -66,6 +76,12 @@ def main() -> int:
                          "(to time and profile the short- and ragged-segment kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-by-variant", action="store_true", help="skip the pass that times both kernel families")
+    ap.add_argument("--ab-rounds", type=int, default=2, metavar="R",
+                    help="rounds of the pass that times both kernel families, alternating, K calls per family and round "
+                         "(mean and standard deviation over the rounds are reported)")
+    ap.add_argument("--lean", action="store_true",
+                    help="for runs under a profiler: warm-up and the K timed calls only (no settle phase, no per-call pass, "
+                         "no families pass, no CPU baseline)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the reduction, run --steps plain copies of MIB MiB (known traffic) "
                          "so that hardware byte counters can be calibrated under rocprofv3 --pmc")
@@ -73,6 +89,8 @@ def main() -> int:
                     help="library launch parameter (see redux_set_param), may be repeated")
     args = ap.parse_args()
 
+    if args.lean:
+        args.settle, args.no_by_variant, args.no_cpu_baseline = 0.0, True, True
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one reduction = one device's share); "
               "run it with --gpus 1", file=sys.stderr)
@@ -175,14 +193,16 @@ def main() -> int:
     achieved = nbytes / (call_us * 1e-6) / 1e9
 
     # ---- per-call durations: one event between every two calls ------------------------------------------------
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    torch.cuda.synchronize()
-    evs[0].record(stream)
-    for i in range(args.steps):
-        step()
-        evs[i + 1].record(stream)
-    torch.cuda.synchronize()
-    per_call = [evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(args.steps)]
+    per_call = None
+    if not args.lean:
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        torch.cuda.synchronize()
+        evs[0].record(stream)
+        for i in range(args.steps):
+            step()
+            evs[i + 1].record(stream)
+        torch.cuda.synchronize()
+        per_call = [evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(args.steps)]
 
     variant_run = "multipass" if multipass else redux.resolved_variant(dt, cfg.segmented)
     prof = None if args.seglen or args.set else PROFILED.get((args.workload, variant_run))
@@ -193,8 +213,8 @@ def main() -> int:
     by_variant = None
     if not multipass and not args.no_by_variant:
         samples = {"mfma": [], "classic": []}
-        for rnd in range(2):
-            for v in (("mfma", "classic") if rnd == 0 else ("classic", "mfma")):
+        for rnd in range(max(1, args.ab_rounds)):
+            for v in (("mfma", "classic") if rnd % 2 == 0 else ("classic", "mfma")):
                 redux.set_variant(v)
                 for _ in range(max(5, args.warmup)):
                     step()
@@ -202,6 +222,7 @@ def main() -> int:
         redux.set_variant(args.variant)
         by_variant = {v: {"us_per_call": round(statistics.mean(s), 3), "gbps": round(nbytes / (statistics.mean(s) * 1e-6) / 1e9, 1),
                           "pct_of_hbm_peak": round(100.0 * nbytes / (statistics.mean(s) * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
+                          "sd_us": round(statistics.stdev(s), 3) if len(s) > 1 else None,
                           "rounds_us": [round(q, 3) for q in s]} for v, s in samples.items()}
 
     line = {
@@ -229,8 +250,8 @@ def main() -> int:
             "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
             "settle_s": args.settle,
             "settle_calls": settle_calls,
-            "median_us": round(statistics.median(per_call), 3),
-            "min_us": round(min(per_call), 3),
+            "median_us": round(statistics.median(per_call), 3) if per_call else None,
+            "min_us": round(min(per_call), 3) if per_call else None,
             "launches_per_call": 1 + (1 if plan.finish == 2 else 0) if not multipass else None,
             "by_variant": by_variant,
         },
