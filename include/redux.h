@@ -214,7 +214,8 @@ typedef enum {
                                 shortened lane butterfly) yield every segment's sum */
     REDUX_KERNEL_RAGGED = 7, /* redux_sum_segmented, any other segment of up to 1008 bytes: the same kernel, each group
                                 of `vectors` lanes reading the aligned vectors that overlap its segment */
-    REDUX_KERNEL_RUNS   = 8  /* redux_sum_segmented, segments from 1009 to 7999 bytes of any length and alignment: one
+    REDUX_KERNEL_RUNS   = 8  /* redux_sum_segmented, segments from 1009 to 7999 bytes (and from 32769 to 49151 when there
+                                are many) of any length and alignment: one
                                 wavefront streams a run of `vectors` (1 .. 16) consecutive whole segments, every lane of
                                 every load busy; each segment of the run owns one column of the MMA accumulator */
 } redux_kernel;
@@ -240,6 +241,12 @@ int redux_plan_sum_segmented(size_t nseg, size_t seglen, int dtype, uintptr_t x_
  * start, start + stride, ... (count of them).  Over all blocks they cover 0 .. nslab-1 exactly once. */
 int redux_plan_block_slabs(int layout, uint64_t nslab, uint64_t grid, uint64_t block,
                            uint64_t *start, uint64_t *stride, uint64_t *count);
+/* The segments that wavefront `wave` (0 .. 3) of block `block` of `grid` sums in the RUNS kernel under `layout`:
+ * `rounds` whole runs of per_run (1 .. 16) segments starting at first, first + stride, ..., then one last run of
+ * tail_count (0 .. per_run) segments starting at tail_first.  Over all wavefronts they cover 0 .. nseg-1 exactly once,
+ * and no two wavefronts differ by more than one run of the same length plus one segment. */
+int redux_plan_run_share(int layout, uint64_t nseg, unsigned per_run, uint64_t grid, uint64_t block, unsigned wave,
+                         uint64_t *first, uint64_t *stride, uint64_t *rounds, uint64_t *tail_first, unsigned *tail_count);
 
 /* Select the kernel family for subsequent calls (process-wide). Also read once from the
  * environment variable REDUX_VARIANT = auto | mfma | classic. */
@@ -275,9 +282,12 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               wavefront per segment instead (default 1)
  *   "seg_runs_max"      1009..2^18  largest segment in bytes that kernel takes (default 7999: measured, from 8000 bytes
  *                               on one wavefront per segment is faster)
- *   "seg_run_len"       0..16   that kernel: segments per run; 0 = the length with the most bytes per cost (iterations, of
- *                               which the last is partly idle, plus a fixed cost per run) on a grid whose last round
- *                               of runs is as full as possible (default 0)
+ *   "seg_runs_long"     0..2^18 that kernel also takes segments of more than 32768 bytes up to this size when there are
+ *                               at least eight per compute unit (default 49151: measured, one block per segment leaves
+ *                               most of its second 32 KiB pass idle there; 0 = none)
+ *   "seg_run_len"       0..16   that kernel: segments per run; 0 = the length with the lowest cost per wavefront
+ *                               (iterations, of which a run's last is partly idle, plus a fixed cost per run; every
+ *                               wavefront takes the same number of whole runs and a share of what is left) (default 0)
  *   "seg_short_pipe"    -1,0,1  that kernel: 1 = every register is reloaded from the block's next 32 KiB as soon as it has
  *                               been consumed, 0 = plain load-then-work loop, -1 = the measured best for the shape (default -1)
  *   "seg_tiles"         0/1     segmented sum: 16-byte aligned segments of exactly 1, 2, 4 or 8 KiB, at least

@@ -46,6 +46,7 @@ struct Settings {
     long seg_runs = 1;            // use the run-of-segments kernel for segments above 1008 bytes that are not cut into pieces
     long seg_run_len = 0;         // segments per run (0 = from the shape)
     long seg_runs_max = 7999;     // largest segment (bytes) that kernel takes
+    long seg_runs_long = 49151;   // it also takes segments of more than 32 KiB up to this size (0 = none)
     long seg_block_bytes = 32768; // segments of at least this many bytes take one block each (0 = never)
     long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
     long lit_blocks_per_cu = 0;
@@ -337,6 +338,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "seg_short")) { *lo = 0; *hi = 1; return &g_set.seg_short; }
     if (!std::strcmp(name, "seg_runs")) { *lo = 0; *hi = 1; return &g_set.seg_runs; }
     if (!std::strcmp(name, "seg_runs_max")) { *lo = 1009; *hi = 1 << 18; return &g_set.seg_runs_max; }
+    if (!std::strcmp(name, "seg_runs_long")) { *lo = 0; *hi = 1 << 18; return &g_set.seg_runs_long; }
     if (!std::strcmp(name, "seg_run_len")) { *lo = 0; *hi = 16; return &g_set.seg_run_len; }
     if (!std::strcmp(name, "seg_tiles")) { *lo = 0; *hi = 1; return &g_set.seg_tiles; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
@@ -442,6 +444,10 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
     // (only when the ragged form below is switched off: measured, that form is as fast or faster at every size)
     const auto ragged_lanes = [](u64 cover) { u64 l = 1; while (l < cover) l *= 2; return l; };
     const bool runs_fit = S.seg_runs && seg_bytes > 1008 && seg_bytes <= (u64)S.seg_runs_max;
+    // Segments a little longer than the 32 KiB that a block reads at a time leave most of its second pass idle
+    // (measured, 36000 and 40000 bytes: 5.7 and 6.0 TB/s by one block per segment, 6.7 as runs; from 50000 bytes on the
+    // block is level or ahead), so while there are enough of them to give every wavefront its own they go as runs too.
+    const bool runs_long = S.seg_runs && seg_bytes > 32768 && seg_bytes <= (u64)S.seg_runs_long && nseg >= (u64)cus * 8;
     const bool ragged_fit = S.seg_ragged && seg_bytes <= 1008 && nseg <= ((u64)1 << 56);
     if (!ragged_fit && (dtype == REDUX_F16 || dtype == REDUX_I8) && S.rows_max_vec > 0 && seg_bytes % 16 == 0 &&
         x_addr % 16 == 0 && seg_bytes / 16 <= (u64)S.rows_max_vec) {
@@ -499,7 +505,7 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
     }
     // long segments (32 KiB and up): one block per segment, cut into pieces of at least 32 KiB while there are
     // fewer than two pieces per compute unit, as far as the workspace allows
-    if (S.seg_block_bytes > 0 && seg_bytes >= (u64)S.seg_block_bytes) {
+    if (S.seg_block_bytes > 0 && seg_bytes >= (u64)S.seg_block_bytes && !runs_long) {
         const u64 want_blocks = (u64)cus * 2;
         u64 parts = 1;
         if (S.seg_parts > 0) parts = (u64)S.seg_parts;
@@ -534,9 +540,9 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
         p.part_len = ((seglen + parts - 1) / parts + 511) / 512 * 512;
     }
     // Whole segments of more than 1008 bytes and less than 8000 (measured: from there on one wavefront per segment is
-    // ahead, 6.8 against 6.6 TB/s at 8000 B, 7.0 against 6.8 at 12000 B): a wavefront streams a run of up to sixteen
-    // of them as one contiguous piece.
-    if (p.kernel == REDUX_KERNEL_WAVE && runs_fit) {
+    // level or ahead, 6.8 against 6.7 TB/s at 8000 B, 6.9 against 6.5 at 12000 B), and those just above 32 KiB: a
+    // wavefront streams a run of up to sixteen of them as one contiguous piece.
+    if (p.kernel == REDUX_KERNEL_WAVE && (runs_fit || runs_long)) {
         p.kernel = REDUX_KERNEL_RUNS;
         const bool mfma = effective_variant(S, dtype) == REDUX_VARIANT_MFMA;
         // measured: the MMA family runs best with four loads per lane in flight and three blocks per compute unit (the
@@ -548,25 +554,28 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
         u64 gmax = (u64)cus * (u64)bpc;
         if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
         if (gmax < 1) gmax = 1;
-        // Segments per run: a run costs its iterations (whole ones: the lanes of the last one that lie behind the run's
-        // end idle) plus a fixed amount for the fold, the store and the set-up of the next run, taken as one
-        // iteration of four loads.  Blocks take groups of four runs in rounds, and the last round is only partly
-        // filled: with g groups on b blocks the machine is busy for g / (b x ceil(g / b)) of the time (measured: 8200-byte
-        // segments in runs of 7 on 768 blocks, 2.08 rounds, 5.97 TB/s; in runs of 11, 1.3 rounds... 6.69).  The length
-        // with the most bytes per cost, times that share, wins.
+        // Segments per run.  A run costs its iterations (whole ones: the lanes of the last one that lie behind the run's
+        // end idle) plus a fixed amount for the fold, the store and the set-up of the next run, taken as one iteration
+        // of four loads.  Every wavefront takes the same number of whole runs and then one shorter run, its share of
+        // what is left (run_share), so the cost of a wavefront is known exactly and the length with the lowest one wins
+        // (measured before the last run was shared out: 8200-byte segments in runs of 7 on 768 blocks, 2.08 rounds of
+        // whole runs, 5.97 TB/s; in runs of 11, 1.3 rounds, 6.69).
+        const auto run_cost = [&](u64 c) {
+            const u64 slots = (15 + c * seg_bytes + 15) / 16;                  // worst alignment of the run's first byte
+            return (double)(((slots + step - 1) / step) * step * 16 + 4096);
+        };
         u64 len = 1;
         if (S.seg_run_len > 0) {
             len = (u64)S.seg_run_len;
         } else {
             double best = 0.0;
             for (u64 c = 1; c <= 16 && c <= nseg; ++c) {
-                const u64 slots = (15 + c * seg_bytes + 15) / 16;              // worst alignment of the run's first byte
-                const u64 iters = (slots + step - 1) / step;
-                const u64 groups = ((nseg + c - 1) / c + kWaves - 1) / kWaves;
-                const u64 rounds = (groups + gmax - 1) / gmax;
-                const double busy = (double)groups / (double)(gmax * rounds);
-                const double value = busy * (double)(c * seg_bytes) / (double)(iters * step * 16 + 4096);
-                if (value >= best) { best = value; len = c; }
+                const u64 blocks = ((nseg + c - 1) / c + kWaves - 1) / kWaves;
+                const u64 waves = (blocks < gmax ? blocks : gmax) * kWaves;
+                const u64 full = nseg / (waves * c);
+                const u64 tail = (nseg - full * waves * c + waves - 1) / waves;
+                const double cost = (double)full * run_cost(c) + (tail ? run_cost(tail) : 0.0);
+                if (c == 1 || cost <= best) { best = cost; len = c; }
             }
         }
         p.nvec = (unsigned)len;
@@ -1090,6 +1099,21 @@ int redux_plan_block_slabs(int layout, uint64_t nslab, uint64_t grid, uint64_t b
     *start = s;
     *stride = st;
     *count = c;
+    return REDUX_OK;
+}
+
+int redux_plan_run_share(int layout, uint64_t nseg, unsigned per_run, uint64_t grid, uint64_t block, unsigned wave,
+                         uint64_t *first, uint64_t *stride, uint64_t *rounds, uint64_t *tail_first, unsigned *tail_count)
+{
+    if (!first || !stride || !rounds || !tail_first || !tail_count) return REDUX_ERR_NULL;
+    if (layout < 0 || layout > 2 || per_run < 1 || per_run > 16 || grid < 1 || grid > (uint64_t)kMaxGrid || block >= grid ||
+        wave >= (unsigned)kWaves) return REDUX_ERR_PARAM;
+    const RunShare r = run_share(layout, nseg, per_run, grid, block, wave);
+    *first = r.first;
+    *stride = r.stride;
+    *rounds = r.full;
+    *tail_first = r.tail_first;
+    *tail_count = r.tail_count;
     return REDUX_OK;
 }
 

@@ -825,6 +825,11 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
         unsigned chain = 0;
         const u64 nslab = run.nvec / kSlab;
         const u32x4 *p = run.body + tid;
+        // the elements in front of the first and behind the last aligned vector are loaded ahead of the stream, so that
+        // their latency is not paid on its own at the end of every piece
+        const bool has_edge = wave == 0 && (run.nhead | run.ntail);
+        u32x4 edge = {0u, 0u, 0u, 0u};
+        if (has_edge) edge = edge_vector<F>(run, (int)lane);
         for (u64 k = 0; k < nslab; ++k, p += kSlab) {
             u32x4 cur[U];
 #pragma unroll
@@ -835,15 +840,23 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
             if (++chain >= a.max_chain) { wave_total += F::fold(acc); chain = 0; }
         }
         if (nslab * kSlab < run.nvec) {                    // the rest of the piece, lanes past its end add zeros
+            // (every lane loads, those past the end the piece's last vector again, so that no load sits under a
+            // branch and all of them are in flight together; what they loaded is replaced by zeros afterwards)
+            u32x4 cur[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const u64 idx = nslab * kSlab + (u64)u * kBlock + tid;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (idx < run.nvec) v = load16<NT>(run.body + idx);
-                F::consume(acc, u, v);
+                cur[u] = load16<NT>(run.body + (idx < run.nvec ? idx : run.nvec - 1));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const u64 idx = nslab * kSlab + (u64)u * kBlock + tid;
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                F::consume(acc, u, idx < run.nvec ? cur[u] : zero);
             }
         }
-        if (wave == 0 && (run.nhead | run.ntail)) F::consume(acc, 0, edge_vector<F>(run, (int)lane));
+        if (has_edge) F::consume(acc, 0, edge);
         wave_total += F::fold(acc);
         if (lane == 0) lds[wave] = wave_total;
         __syncthreads();

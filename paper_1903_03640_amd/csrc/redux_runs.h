@@ -31,8 +31,43 @@ struct RunArgs {
     unsigned seg_bytes;      // bytes per segment: 16 .. 2^18 (the run's byte positions are kept in 32 bits)
     unsigned per_run;        // segments per run: 1 .. 16
     void *out;
-    int layout;              // which runs a block takes (see slab_schedule; a block takes four consecutive runs at a time)
+    int layout;              // 2: every accelerator die takes a contiguous eighth of the segments (see run_share)
 };
+
+// Which segments a wavefront takes.  The segments of a part (the whole array, or the eighth of it that belongs to one
+// accelerator die: workgroup b runs on die b % 8) are dealt out in rounds: in round k wavefront j of the part's W
+// takes the per_run segments from k x W x per_run + j x per_run on, so that at any time the part reads one contiguous
+// moving window.  What is left after the last whole round is fewer than W x per_run segments: it is split into W
+// nearly equal shares, one last, shorter run for every wavefront, so that all of them finish together whatever the
+// number of segments is (dealing out whole runs to the end would leave most wavefronts idle for up to a round).
+struct RunShare {
+    u64 first;           // first segment of this wavefront's run of round 0
+    u64 stride;          // segments from one round to the next
+    u64 full;            // whole rounds
+    u64 tail_first;      // the last, shorter run ...
+    unsigned tail_count; // ... and its segments (0 .. per_run)
+};
+
+__host__ __device__ __forceinline__ RunShare run_share(int layout, u64 nseg, unsigned per_run, u64 G, u64 b, unsigned wave)
+{
+    const bool by_die = layout == 2 && G % (u64)kXcds == 0;      // (equal numbers of workgroups on every die)
+    const u64 x = by_die ? b % kXcds : 0, l = by_die ? b / kXcds : b;
+    const u64 lo = by_die ? (nseg >> 3) * x + (((nseg & 7u) * x) >> 3) : 0;              // floor(nseg x / 8)
+    const u64 hi = by_die ? (nseg >> 3) * (x + 1) + (((nseg & 7u) * (x + 1)) >> 3) : nseg;
+    const u64 W = (by_die ? G / kXcds : G) * kWaves;             // wavefronts of the part
+    const u64 j = l * kWaves + wave;                             // this one among them
+    RunShare r;
+    r.stride = W * per_run;
+    r.full = (hi - lo) / r.stride;
+    const unsigned rest = (unsigned)((hi - lo) - r.full * r.stride);   // < W x per_run <= 2^20
+    // floor(rest x j / W) in 32 bits: j <= W <= 2^16, so j x (rest mod W) < 2^32
+    const unsigned w = (unsigned)W, q = rest / w, m = rest % w, jj = (unsigned)j;
+    const unsigned t0 = jj * q + jj * m / w, t1 = (jj + 1u) * q + (jj + 1u) * m / w;
+    r.first = lo + j * per_run;
+    r.tail_first = lo + r.full * r.stride + t0;
+    r.tail_count = (unsigned)(t1 - t0);                          // <= ceil(rest / W) <= per_run
+    return r;
+}
 
 // U = 16-byte loads per lane per iteration (4 or 8); an iteration of a wavefront takes 64 x U vectors
 
@@ -49,16 +84,15 @@ struct RunGeometry {
     unsigned off;        // first byte of the run's first segment, from base (0 .. 15)
     unsigned total;      // first byte behind the run's last segment, from base
     unsigned nvec;       // aligned vectors that overlap the run
-    unsigned count;      // segments in this run (the array's last run may be short)
+    unsigned count;      // segments in this run
     u64 first;           // index of the run's first segment
 };
 
-__device__ __forceinline__ RunGeometry run_geometry(const RunArgs &a, u64 run)
+__device__ __forceinline__ RunGeometry run_geometry(const RunArgs &a, u64 first, unsigned count)
 {
     RunGeometry g;
-    g.first = run * a.per_run;
-    const u64 left = a.nseg - g.first;
-    g.count = left < (u64)a.per_run ? (unsigned)left : a.per_run;
+    g.first = first;
+    g.count = count;
     // (pointer arithmetic on the kernel argument keeps the loads in the global address space)
     const unsigned char *start = a.x + g.first * a.seg_bytes;
     g.off = (unsigned)(uintptr_t)start & 15u;
@@ -162,14 +196,9 @@ __global__ void __launch_bounds__(kBlock) sum_segment_runs_classic_kernel(RunArg
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     __shared__ u32x4 low[17];
     fill_low_masks(low);
-    const u64 nruns = (a.nseg + a.per_run - 1) / a.per_run;
-    // the block takes groups of four consecutive runs, one per wavefront, in the order the flat sum takes its slabs
-    u64 g0, stride, count;
-    slab_schedule(a.layout, (nruns + kWaves - 1) / kWaves, gridDim.x, blockIdx.x, &g0, &stride, &count);
-    for (u64 k = 0; k < count; ++k) {
-        const u64 run = (g0 + k * stride) * kWaves + wave;
-        if (run < nruns) run_classic<E, U, NT>(a, run_geometry(a, run), low, lane);
-    }
+    const RunShare sh = run_share(a.layout, a.nseg, a.per_run, gridDim.x, blockIdx.x, wave);
+    for (u64 k = 0; k < sh.full; ++k) run_classic<E, U, NT>(a, run_geometry(a, sh.first + k * sh.stride, a.per_run), low, lane);
+    if (sh.tail_count != 0u) run_classic<E, U, NT>(a, run_geometry(a, sh.tail_first, sh.tail_count), low, lane);
 }
 
 // ---- MMA family ------------------------------------------------------------------------------------------------------
@@ -203,15 +232,12 @@ __global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_kernel(RunArgs a
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     __shared__ u32x4 low[17];
     fill_low_masks(low);
-    const u64 nruns = (a.nseg + a.per_run - 1) / a.per_run;
-    // the block takes groups of four consecutive runs, one per wavefront, in the order the flat sum takes its slabs
-    u64 g0, stride, count;
-    slab_schedule(a.layout, (nruns + kWaves - 1) / kWaves, gridDim.x, blockIdx.x, &g0, &stride, &count);
+    const RunShare sh = run_share(a.layout, a.nseg, a.per_run, gridDim.x, blockIdx.x, wave);
 
-    for (u64 k = 0; k < count; ++k) {
-        const u64 run = (g0 + k * stride) * kWaves + wave;
-        if (run >= nruns) break;                   // (only in the block's last group)
-        const RunGeometry g = run_geometry(a, run);
+    for (u64 k = 0; k <= sh.full; ++k) {
+        const bool last = k == sh.full;            // the shorter run behind the whole rounds
+        if (last && sh.tail_count == 0u) break;
+        const RunGeometry g = run_geometry(a, last ? sh.tail_first : sh.first + k * sh.stride, last ? sh.tail_count : a.per_run);
         typename E::Acc acc = E::zero();           // column k: the sixteen row sums of segment k of the run
         RunCursor c;
         c.start(g);

@@ -19,7 +19,7 @@ VARIANTS = {"auto": 0, "mfma": 1, "classic": 2}
 # every symbol include/redux.h declares
 SYMBOLS = (
     "redux_sum", "redux_sum_static", "redux_sum_segmented", "redux_sum_multipass", "redux_mma_group_probe", "redux_calibration_copy",
-    "redux_plan_sum", "redux_plan_sum_segmented", "redux_plan_block_slabs",
+    "redux_plan_sum", "redux_plan_sum_segmented", "redux_plan_block_slabs", "redux_plan_run_share",
     "redux_set_variant", "redux_get_variant", "redux_resolved_variant", "redux_set_param", "redux_get_param",
     "redux_strerror", "redux_last_hip_error", "redux_shutdown", "redux_version",
 )
@@ -72,6 +72,9 @@ def load():
         lib.redux_plan_sum_segmented.argtypes = [sz, sz, ci, ctypes.c_size_t, ci, ctypes.POINTER(Plan)]
         lib.redux_plan_block_slabs.restype = ci
         lib.redux_plan_block_slabs.argtypes = [ci, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, u64p, u64p, u64p]
+        lib.redux_plan_run_share.restype = ci
+        lib.redux_plan_run_share.argtypes = [ci, ctypes.c_uint64, ctypes.c_uint, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint,
+                                             u64p, u64p, u64p, u64p, ctypes.POINTER(ctypes.c_uint)]
         lib.redux_set_variant.restype = ci
         lib.redux_set_variant.argtypes = [ci]
         lib.redux_get_variant.restype = ci
@@ -184,6 +187,14 @@ def plan_block_slabs(layout: int, nslab: int, grid: int, block: int):
     _check(load().redux_plan_block_slabs(layout, nslab, grid, block, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)),
            "redux_plan_block_slabs")
     return a.value, b.value, c.value
+
+
+def plan_run_share(layout: int, nseg: int, per_run: int, grid: int, block: int, wave: int):
+    """(first, stride, rounds, tail_first, tail_count) of the segments one wavefront of the RUNS kernel sums."""
+    a, b, c, d, e = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint()
+    _check(load().redux_plan_run_share(layout, nseg, per_run, grid, block, wave, ctypes.byref(a), ctypes.byref(b),
+                                       ctypes.byref(c), ctypes.byref(d), ctypes.byref(e)), "redux_plan_run_share")
+    return a.value, b.value, c.value, d.value, e.value
 
 
 # ---- torch conveniences: allocate the output, pass the current stream --------------------------------

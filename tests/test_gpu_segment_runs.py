@@ -32,6 +32,7 @@ def reset():
     redux.set_param("seg_runs_max", 1 << 18)                     # every size here through this kernel, not only what it takes by default
     yield
     redux.set_param("seg_runs_max", 7999)
+    redux.set_param("seg_runs_long", 49151)
     for name, val in (("max_grid", 16384), ("seg_blocks_per_cu", 0), ("nontemporal", 1), ("seg_runs", 1), ("seg_run_len", 0),
                       ("seg_block_bytes", 32768), ("seg_parts", 0), ("seg_short", 1), ("seg_tiles", 1)):
         redux.set_param(name, val)
@@ -168,3 +169,22 @@ def test_runs_int8_extremes_and_largest_segment(dev, variant):
     want, want_abs = oracle.sum_segmented_f16(pats, 300, 4100)
     for got in (a, c):
         assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("kind", ("f16", "i8"))
+def test_runs_take_segments_just_above_32_kib_by_default(dev, kind, variant):
+    """With every setting at its default, many segments of a little more than 32 KiB go through this kernel (few of them, or
+    longer ones, through one block per segment); the wavefronts' last, shorter runs are part of what is checked."""
+    redux.set_variant(variant)
+    redux.set_param("seg_runs_max", 7999)
+    es = ESIZE[kind]
+    for seg_bytes, nseg, offset, kernel in ((36002, 2100, 1, redux.KERNEL_RUNS), (40000, 2048, 0, redux.KERNEL_RUNS),
+                                            (36002, 2047, 1, redux.KERNEL_BLOCK), (49152, 2100, 0, redux.KERNEL_BLOCK)):
+        seglen = seg_bytes // es
+        pats = patterns(kind, seg_bytes + nseg, nseg * seglen)
+        xd = to_dev_at(pats, kind, dev, offset)
+        assert redux.plan_sum_segmented(nseg, seglen, CODE[kind], x_address=xd.data_ptr() % 16, compute_units=256).kernel == kernel
+        got = redux.sum_segmented(xd, nseg, seglen)
+        torch.cuda.synchronize()
+        check(got, pats, kind, nseg, seglen, TOL, (kind, seg_bytes, nseg, offset))

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(redux.LIB_PATH), reason="libr
 
 ES = {redux.F16: 2, redux.I8: 1, redux.BF16: 2, redux.F32: 4, redux.F8E4M3: 1, redux.F8E5M2: 1}
 DTYPES = sorted(ES)
-PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short", "seg_ragged", "seg_runs", "seg_run_len", "seg_runs_max")
+PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short", "seg_ragged", "seg_runs", "seg_run_len", "seg_runs_max", "seg_runs_long")
 
 
 @pytest.fixture(autouse=True)
@@ -86,15 +86,56 @@ def test_slab_schedule_is_balanced_and_die_blocked():
         assert lo <= start and start + (count - 1) * stride < hi
 
 
+@settings(max_examples=200, deadline=None)
+@given(layout=st.integers(0, 2), nseg=st.one_of(st.integers(1, 40), st.integers(1, 60000)), per_run=st.integers(1, 16),
+       grid=st.one_of(st.integers(1, 40), st.sampled_from([8, 16, 64, 256])))
+def test_run_share_covers_every_segment_once_and_is_balanced(layout, nseg, per_run, grid):
+    seen = bytearray(nseg)
+    work = []
+    for b in range(grid):
+        for w in range(4):
+            first, stride, rounds, tail_first, tail_count = redux.plan_run_share(layout, nseg, per_run, grid, b, w)
+            assert 0 <= tail_count <= per_run
+            runs = [(first + k * stride, per_run) for k in range(rounds)] + ([(tail_first, tail_count)] if tail_count else [])
+            for s0, c in runs:
+                assert s0 + c <= nseg and not any(seen[s0:s0 + c])
+                seen[s0:s0 + c] = b"\x01" * c
+            work.append(rounds * per_run + tail_count)
+    assert all(seen)
+    # the eight dies differ by at most one segment in what they own, the wavefronts of a die by one more
+    assert max(work) - min(work) <= (2 if layout == 2 and grid % 8 == 0 else 1)
+
+
+def test_run_share_extremes():
+    # the largest grid (65536 wavefronts) and the longest runs: the 32-bit arithmetic of the last run's share holds
+    nseg, per_run, grid = (1 << 20) * 16 - 1, 16, 16384
+    for b in (0, 1, 7, 8191, 16383):
+        for w in range(4):
+            first, stride, rounds, tail_first, tail_count = redux.plan_run_share(0, nseg, per_run, grid, b, w)
+            assert stride == grid * 4 * per_run and rounds == nseg // stride and tail_count in (15, 16)
+            j = b * 4 + w
+            rest = nseg - rounds * stride
+            assert tail_first == rounds * stride + rest * j // (grid * 4) and first == j * per_run
+    # a part gets whole rounds only while it has enough segments; 2^40 segments do not overflow anything
+    first, stride, rounds, tail_first, tail_count = redux.plan_run_share(2, 1 << 40, 16, 768, 767, 3)
+    lo, hi = (1 << 40) * 7 // 8, 1 << 40
+    assert lo <= first < hi and stride == 96 * 4 * 16 and rounds == (hi - lo) // stride and tail_first + tail_count <= hi
+    with pytest.raises(redux.ReduxError):
+        redux.plan_run_share(0, 10, 17, 4, 0, 0)
+    with pytest.raises(redux.ReduxError):
+        redux.plan_run_share(0, 10, 4, 4, 0, 4)
+
+
 @settings(max_examples=500, deadline=None)
 @given(nseg=st.one_of(st.integers(1, 300), st.integers(1, 1 << 24)), seglen=st.one_of(st.integers(1, 3000), st.integers(1, 1 << 26), st.sampled_from([4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048])),
        dtype=st.sampled_from(DTYPES), aligned=st.booleans(), cus=st.sampled_from([1, 104, 256]),
        seg_parts=st.sampled_from([0, 0, 0, 2, 8, 64, 4096]), rows_max=st.sampled_from([64, 64, 0, 5]),
        seg_bpc=st.integers(0, 16), unroll=st.sampled_from([0, 1, 2, 4, 8]), block_bytes=st.sampled_from([32768, 32768, 0, 1000]),
        seg_short=st.sampled_from([1, 1, 0]), seg_ragged=st.sampled_from([1, 1, 0]), seg_runs=st.sampled_from([1, 1, 0]),
-       run_len=st.sampled_from([0, 0, 0, 1, 5, 16]), runs_max=st.sampled_from([7999, 7999, 1 << 18]))
+       run_len=st.sampled_from([0, 0, 0, 1, 5, 16]), runs_max=st.sampled_from([7999, 7999, 1 << 18]),
+       runs_long=st.sampled_from([49151, 49151, 0, 1 << 18]))
 def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll, block_bytes, seg_short, seg_ragged,
-                                   seg_runs, run_len, runs_max):
+                                   seg_runs, run_len, runs_max, runs_long):
     es = ES[dtype]
     addr = 4096 if aligned else 4096 + es
     redux.set_param("seg_parts", seg_parts)
@@ -107,6 +148,7 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
     redux.set_param("seg_runs", seg_runs)
     redux.set_param("seg_run_len", run_len)
     redux.set_param("seg_runs_max", runs_max)
+    redux.set_param("seg_runs_long", runs_long)
     p = redux.plan_sum_segmented(nseg, seglen, dtype, addr, cus)
     assert 1 <= p.grid <= 16 * cus
     limit = 4096 if dtype not in (redux.F32, redux.F8E4M3, redux.F8E5M2) else 1024    # variant auto: MMA family except for the 8-bit floats
@@ -145,8 +187,9 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
         assert p.grid <= nseg * p.parts
     elif p.kernel == redux.KERNEL_RUNS:
         sb = seglen * es
-        assert seg_runs and 1008 < sb <= runs_max and p.parts == 1 and p.unroll in (4, 8) and p.finish == 0
-        assert not (block_bytes and sb >= block_bytes)
+        long_range = 32768 < sb <= runs_long and nseg >= 8 * cus
+        assert seg_runs and (1008 < sb <= runs_max or long_range) and p.parts == 1 and p.unroll in (4, 8) and p.finish == 0
+        assert long_range or not (block_bytes and sb >= block_bytes)
         assert 1 <= p.vectors <= 16 and (run_len == 0 or p.vectors == run_len)
         assert run_len or p.vectors <= nseg
         nruns = -(-nseg // p.vectors)
@@ -180,7 +223,7 @@ def test_segmented_plan_defaults_on_mi355x():
     assert redux.plan_sum_segmented(1023, 4096, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE    # too few segments for the whole-tile kernel
     assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE   # 8208 B: above the run kernel's range
     three = redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256)                           # 3 KiB: not a power of two
-    assert (three.kernel, three.vectors, three.unroll, three.grid) == (redux.KERNEL_RUNS, 11, 4, 768)   # runs of 11, 1.94 rounds on three blocks per CU
+    assert (three.kernel, three.vectors, three.unroll, three.grid) == (redux.KERNEL_RUNS, 13, 4, 768)   # 21.3 segments per wavefront on three blocks per CU: a run of 13 and a last one of 8 or 9
     few = redux.plan_sum_segmented(40, 2050, redux.F16, 0, 256)
     assert (few.kernel, few.vectors, few.grid) == (redux.KERNEL_RUNS, 1, 10)                      # few segments: one per run
     redux.set_variant("classic")
@@ -193,6 +236,14 @@ def test_segmented_plan_defaults_on_mi355x():
     redux.set_param("seg_runs_max", 1 << 18)
     assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_RUNS
     redux.set_param("seg_runs_max", 7999)
+    # just above 32 KiB a block's second pass would be mostly idle: runs, while every wavefront can have a segment of its own
+    assert redux.plan_sum_segmented(2048, 18000, redux.F16, 0, 256).kernel == redux.KERNEL_RUNS
+    assert redux.plan_sum_segmented(2047, 18000, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK
+    assert redux.plan_sum_segmented(2048, 16384, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK     # 32 KiB exactly
+    assert redux.plan_sum_segmented(4096, 24576, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK     # 48 KiB and up
+    redux.set_param("seg_runs_long", 0)
+    assert redux.plan_sum_segmented(2048, 18000, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK
+    redux.set_param("seg_runs_long", 49151)
     short = redux.plan_sum_segmented(1 << 22, 64, redux.F16, 0, 256)
     assert (short.kernel, short.vectors, short.unroll, short.grid) == (redux.KERNEL_SHORT, 8, 8, 256)   # 128 B: contiguous stream
     assert redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256).kernel == redux.KERNEL_SHORT     # every dtype
