@@ -263,6 +263,26 @@ def test_variants_agree_and_runs_are_bit_identical(dev):
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
+def test_every_ordered_finish_gives_the_same_bits(dev, variant):
+    """The block partials are the same whoever adds them up, and every finish but the atomic additions adds them in
+    block order: the second kernel and the last block to arrive must agree bit for bit, call after call."""
+    redux.set_variant(variant)
+    n = (1 << 24) + 12345
+    x = to_dev(workloads.normal_f16(5, n), dev)
+    bits = {}
+    for finish in (2, 1, 4):
+        redux.set_param("finish", finish)
+        outs = torch.empty(100, dtype=torch.float32, device=dev)
+        for k in range(100):
+            redux.sum(x, out=outs[k:k + 1])
+        torch.cuda.synchronize()
+        got = outs.cpu().numpy().view(np.uint32)
+        assert np.all(got == got[0]), finish
+        bits[finish] = int(got[0])
+    assert bits[1] == bits[2] == bits[4], bits
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("finish", [0, 1, 4])
 def test_in_kernel_finish_sees_this_call_not_the_last(dev, variant, finish):
     """Back-to-back calls alternate between two different arrays: a block partial left over from the previous
