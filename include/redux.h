@@ -214,7 +214,7 @@ typedef enum {
                                 shortened lane butterfly) yield every segment's sum */
     REDUX_KERNEL_RAGGED = 7, /* redux_sum_segmented, any other segment of up to 1008 bytes: the same kernel, each group
                                 of `vectors` lanes reading the aligned vectors that overlap its segment */
-    REDUX_KERNEL_RUNS   = 8  /* redux_sum_segmented, segments from 1009 to 7999 bytes (and from 32769 to 49151 when there
+    REDUX_KERNEL_RUNS   = 8  /* redux_sum_segmented, segments from 1009 to 7999 bytes (and from 32769 to 36863 when there
                                 are many) of any length and alignment: one
                                 wavefront streams a run of `vectors` (1 .. 16) consecutive whole segments, every lane of
                                 every load busy; each segment of the run owns one column of the MMA accumulator */
@@ -283,8 +283,10 @@ int redux_resolved_variant(int dtype, int segmented);
  *   "seg_runs_max"      1009..2^18  largest segment in bytes that kernel takes (default 7999: measured, from 8000 bytes
  *                               on one wavefront per segment is faster)
  *   "seg_runs_long"     0..2^18 that kernel also takes segments of more than 32768 bytes up to this size when there are
- *                               at least eight per compute unit (default 49151: measured, one block per segment leaves
+ *                               at least eight per compute unit (default 36863: measured, one block per segment leaves
  *                               most of its second 32 KiB pass idle there; 0 = none)
+ *   "seg_balance"       0/1     segmented sum, one block per segment: segments are cut into (more) pieces of at least 64 KiB
+ *                               while the last round of pieces over the grid would leave more than 15 % of it idle (default 1)
  *   "seg_run_len"       0..16   that kernel: segments per run; 0 = the length with the lowest cost per wavefront
  *                               (iterations, of which a run's last is partly idle, plus a fixed cost per run; every
  *                               wavefront takes the same number of whole runs and a share of what is left) (default 0)

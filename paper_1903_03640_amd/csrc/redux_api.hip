@@ -46,7 +46,8 @@ struct Settings {
     long seg_runs = 1;            // use the run-of-segments kernel for segments above 1008 bytes that are not cut into pieces
     long seg_run_len = 0;         // segments per run (0 = from the shape)
     long seg_runs_max = 7999;     // largest segment (bytes) that kernel takes
-    long seg_runs_long = 49151;   // it also takes segments of more than 32 KiB up to this size (0 = none)
+    long seg_balance = 1;         // long segments are cut into more pieces when the last round of pieces would be mostly empty
+    long seg_runs_long = 36863;   // it also takes segments of more than 32 KiB up to this size (0 = none)
     long seg_block_bytes = 32768; // segments of at least this many bytes take one block each (0 = never)
     long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
     long lit_blocks_per_cu = 0;
@@ -339,6 +340,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "seg_runs")) { *lo = 0; *hi = 1; return &g_set.seg_runs; }
     if (!std::strcmp(name, "seg_runs_max")) { *lo = 1009; *hi = 1 << 18; return &g_set.seg_runs_max; }
     if (!std::strcmp(name, "seg_runs_long")) { *lo = 0; *hi = 1 << 18; return &g_set.seg_runs_long; }
+    if (!std::strcmp(name, "seg_balance")) { *lo = 0; *hi = 1; return &g_set.seg_balance; }
     if (!std::strcmp(name, "seg_run_len")) { *lo = 0; *hi = 16; return &g_set.seg_run_len; }
     if (!std::strcmp(name, "seg_tiles")) { *lo = 0; *hi = 1; return &g_set.seg_tiles; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
@@ -445,8 +447,8 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
     const auto ragged_lanes = [](u64 cover) { u64 l = 1; while (l < cover) l *= 2; return l; };
     const bool runs_fit = S.seg_runs && seg_bytes > 1008 && seg_bytes <= (u64)S.seg_runs_max;
     // Segments a little longer than the 32 KiB that a block reads at a time leave most of its second pass idle
-    // (measured, 36000 and 40000 bytes: 5.7 and 6.0 TB/s by one block per segment, 6.7 as runs; from 50000 bytes on the
-    // block is level or ahead), so while there are enough of them to give every wavefront its own they go as runs too.
+    // (measured, 33000 and 36000 bytes: 6.4 and 6.5 TB/s by one block per segment, 6.7 as runs; from 40000 bytes on the
+    // block is ahead, 6.8 against 6.5), so while there are enough of them to give every wavefront its own they go as runs too.
     const bool runs_long = S.seg_runs && seg_bytes > 32768 && seg_bytes <= (u64)S.seg_runs_long && nseg >= (u64)cus * 8;
     const bool ragged_fit = S.seg_ragged && seg_bytes <= 1008 && nseg <= ((u64)1 << 56);
     if (!ragged_fit && (dtype == REDUX_F16 || dtype == REDUX_I8) && S.rows_max_vec > 0 && seg_bytes % 16 == 0 &&
@@ -509,7 +511,22 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
         const u64 want_blocks = (u64)cus * 2;
         u64 parts = 1;
         if (S.seg_parts > 0) parts = (u64)S.seg_parts;
-        else while (nseg * parts < want_blocks && nseg * parts * 2 <= (u64)kMaxGrid && seg_bytes / (parts * 2) >= 32768) parts *= 2;
+        else {
+            while (nseg * parts < want_blocks && nseg * parts * 2 <= (u64)kMaxGrid && seg_bytes / (parts * 2) >= 32768) parts *= 2;
+            // Blocks take pieces in rounds, and a last round that is only partly filled leaves the rest of the chip idle
+            // (measured: 1073 segments of 500000 bytes on 512 blocks, 2.1 rounds, 6.1 TB/s against 6.9 for a whole number
+            // of rounds): pieces are halved while less than 85 % of the rounds' slots are used and a piece stays above 64 KiB.
+            const auto used = [&](u64 pr) {
+                const u64 pieces = nseg * pr;
+                const u64 piece_bytes = (seg_bytes + pr - 1) / pr;
+                u64 g = (u64)cus * (u64)(S.seg_blocks_per_cu ? S.seg_blocks_per_cu : (piece_bytes >= ((u64)512 << 10) ? 1 : 2));
+                if (g > (u64)S.max_grid) g = (u64)S.max_grid;
+                if (g < 1) g = 1;
+                if (g > pieces) g = pieces;
+                return (double)pieces / (double)(g * ((pieces + g - 1) / g));
+            };
+            while (S.seg_balance && used(parts) < 0.85 && nseg * parts * 2 <= (u64)kMaxGrid && seg_bytes / (parts * 2) >= 65536) parts *= 2;
+        }
         if (parts > 1 && nseg <= (u64)kMaxGrid / parts) {
             p.parts = parts;
             p.part_len = ((seglen + parts - 1) / parts + 511) / 512 * 512;

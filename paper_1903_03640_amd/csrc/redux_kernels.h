@@ -825,11 +825,22 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
         unsigned chain = 0;
         const u64 nslab = run.nvec / kSlab;
         const u32x4 *p = run.body + tid;
-        // the elements in front of the first and behind the last aligned vector are loaded ahead of the stream, so that
-        // their latency is not paid on its own at the end of every piece
+        // What does not fill a whole slab -- the vectors behind the last whole slab, and the elements in front of the
+        // first and behind the last aligned vector -- is loaded ahead of the stream and added behind it, so that its
+        // latency is not paid on its own at the end of every piece.  Every lane loads (those past the end the piece's
+        // last vector again), so no load sits under a per-lane branch; what such a lane loaded is replaced by zeros.
         const bool has_edge = wave == 0 && (run.nhead | run.ntail);
         u32x4 edge = {0u, 0u, 0u, 0u};
         if (has_edge) edge = edge_vector<F>(run, (int)lane);
+        const bool has_rest = nslab * kSlab < run.nvec;    // (the same for the whole block)
+        u32x4 rest[U];
+        if (has_rest) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const u64 idx = nslab * kSlab + (u64)u * kBlock + tid;
+                rest[u] = load16<NT>(run.body + (idx < run.nvec ? idx : run.nvec - 1));
+            }
+        }
         for (u64 k = 0; k < nslab; ++k, p += kSlab) {
             u32x4 cur[U];
 #pragma unroll
@@ -839,21 +850,12 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
             for (int u = 0; u < U; ++u) F::consume(acc, u, cur[u]);
             if (++chain >= a.max_chain) { wave_total += F::fold(acc); chain = 0; }
         }
-        if (nslab * kSlab < run.nvec) {                    // the rest of the piece, lanes past its end add zeros
-            // (every lane loads, those past the end the piece's last vector again, so that no load sits under a
-            // branch and all of them are in flight together; what they loaded is replaced by zeros afterwards)
-            u32x4 cur[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const u64 idx = nslab * kSlab + (u64)u * kBlock + tid;
-                cur[u] = load16<NT>(run.body + (idx < run.nvec ? idx : run.nvec - 1));
-            }
-            __builtin_amdgcn_sched_barrier(0);
+        if (has_rest) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const u64 idx = nslab * kSlab + (u64)u * kBlock + tid;
                 const u32x4 zero = {0u, 0u, 0u, 0u};
-                F::consume(acc, u, idx < run.nvec ? cur[u] : zero);
+                F::consume(acc, u, idx < run.nvec ? rest[u] : zero);
             }
         }
         if (has_edge) F::consume(acc, 0, edge);

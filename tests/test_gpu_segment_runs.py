@@ -32,7 +32,7 @@ def reset():
     redux.set_param("seg_runs_max", 1 << 18)                     # every size here through this kernel, not only what it takes by default
     yield
     redux.set_param("seg_runs_max", 7999)
-    redux.set_param("seg_runs_long", 49151)
+    redux.set_param("seg_runs_long", 36863)
     for name, val in (("max_grid", 16384), ("seg_blocks_per_cu", 0), ("nontemporal", 1), ("seg_runs", 1), ("seg_run_len", 0),
                       ("seg_block_bytes", 32768), ("seg_parts", 0), ("seg_short", 1), ("seg_tiles", 1)):
         redux.set_param(name, val)
@@ -179,8 +179,8 @@ def test_runs_take_segments_just_above_32_kib_by_default(dev, kind, variant):
     redux.set_variant(variant)
     redux.set_param("seg_runs_max", 7999)
     es = ESIZE[kind]
-    for seg_bytes, nseg, offset, kernel in ((36002, 2100, 1, redux.KERNEL_RUNS), (40000, 2048, 0, redux.KERNEL_RUNS),
-                                            (36002, 2047, 1, redux.KERNEL_BLOCK), (49152, 2100, 0, redux.KERNEL_BLOCK)):
+    for seg_bytes, nseg, offset, kernel in ((36002, 2100, 1, redux.KERNEL_RUNS), (33000, 2048, 0, redux.KERNEL_RUNS),
+                                            (36002, 2047, 1, redux.KERNEL_BLOCK), (36864, 2100, 0, redux.KERNEL_BLOCK), (40000, 2100, 1, redux.KERNEL_BLOCK)):
         seglen = seg_bytes // es
         pats = patterns(kind, seg_bytes + nseg, nseg * seglen)
         xd = to_dev_at(pats, kind, dev, offset)

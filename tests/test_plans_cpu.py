@@ -12,7 +12,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(redux.LIB_PATH), reason="libr
 
 ES = {redux.F16: 2, redux.I8: 1, redux.BF16: 2, redux.F32: 4, redux.F8E4M3: 1, redux.F8E5M2: 1}
 DTYPES = sorted(ES)
-PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short", "seg_ragged", "seg_runs", "seg_run_len", "seg_runs_max", "seg_runs_long")
+PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short", "seg_ragged", "seg_runs", "seg_run_len", "seg_runs_max", "seg_runs_long", "seg_balance")
 
 
 @pytest.fixture(autouse=True)
@@ -133,7 +133,7 @@ def test_run_share_extremes():
        seg_bpc=st.integers(0, 16), unroll=st.sampled_from([0, 1, 2, 4, 8]), block_bytes=st.sampled_from([32768, 32768, 0, 1000]),
        seg_short=st.sampled_from([1, 1, 0]), seg_ragged=st.sampled_from([1, 1, 0]), seg_runs=st.sampled_from([1, 1, 0]),
        run_len=st.sampled_from([0, 0, 0, 1, 5, 16]), runs_max=st.sampled_from([7999, 7999, 1 << 18]),
-       runs_long=st.sampled_from([49151, 49151, 0, 1 << 18]))
+       runs_long=st.sampled_from([36863, 36863, 0, 1 << 18]))
 def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll, block_bytes, seg_short, seg_ragged,
                                    seg_runs, run_len, runs_max, runs_long):
     es = ES[dtype]
@@ -240,10 +240,17 @@ def test_segmented_plan_defaults_on_mi355x():
     assert redux.plan_sum_segmented(2048, 18000, redux.F16, 0, 256).kernel == redux.KERNEL_RUNS
     assert redux.plan_sum_segmented(2047, 18000, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK
     assert redux.plan_sum_segmented(2048, 16384, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK     # 32 KiB exactly
-    assert redux.plan_sum_segmented(4096, 24576, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK     # 48 KiB and up
+    assert redux.plan_sum_segmented(4096, 18432, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK     # 36 KiB and up
     redux.set_param("seg_runs_long", 0)
     assert redux.plan_sum_segmented(2048, 18000, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK
-    redux.set_param("seg_runs_long", 49151)
+    redux.set_param("seg_runs_long", 36863)
+    # 1072 segments of 500000 bytes on 512 blocks would be 2.1 rounds: four pieces each make it 8.4
+    cut = redux.plan_sum_segmented(1072, 250000, redux.F16, 0, 256)
+    assert (cut.kernel, cut.parts, cut.grid, cut.finish) == (redux.KERNEL_BLOCK, 4, 512, 2) and cut.part_len * 2 >= 65536
+    redux.set_param("seg_balance", 0)
+    assert redux.plan_sum_segmented(1072, 250000, redux.F16, 0, 256).parts == 1
+    redux.set_param("seg_balance", 1)
+    assert redux.plan_sum_segmented(1024, 250000, redux.F16, 0, 256).parts == 1                  # two whole rounds: nothing to gain
     short = redux.plan_sum_segmented(1 << 22, 64, redux.F16, 0, 256)
     assert (short.kernel, short.vectors, short.unroll, short.grid) == (redux.KERNEL_SHORT, 8, 8, 256)   # 128 B: contiguous stream
     assert redux.plan_sum_segmented(1 << 22, 64, redux.BF16, 0, 256).kernel == redux.KERNEL_SHORT     # every dtype
