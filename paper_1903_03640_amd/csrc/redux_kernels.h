@@ -520,7 +520,11 @@ template <class F, int U, bool NT>
 __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
 {
     typedef typename F::Total Total;
-    const unsigned tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const unsigned tid = threadIdx.x, lane = tid & 63u;
+    // The wavefront's number, read into a scalar register: a branch on it is then a real branch.  As a per-lane value
+    // it would only mask lanes off, and a matrix instruction ignores that mask: a wavefront that was meant to skip an
+    // MMA would execute it on whatever its registers hold.
+    const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
     const u64 G = gridDim.x;
     constexpr u64 kSlab = (u64)kBlock * U;         // vectors per block iteration
     const u64 nslab = a.run.nvec / kSlab;
@@ -540,6 +544,23 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
     // gain nothing from it.
     if (count >= 32)
         for (unsigned i = 0; i < wave * a.stagger; ++i) __builtin_amdgcn_s_sleep(1);
+    // What does not fill a whole slab -- the vectors behind the last whole slab (one block's), the elements in front of
+    // the first and behind the last aligned vector (block 0's) -- is loaded ahead of the stream and added behind it, so
+    // that its latency is not paid on its own at the end of the block's work.  Every lane loads (those past the end
+    // the array's last vector again), so no load sits under a per-lane branch; such a lane then adds zeros.
+    const bool has_rest = blockIdx.x == (unsigned)(nslab % G) && nslab * kSlab < a.run.nvec;
+    const bool has_edge = blockIdx.x == 0 && wave == 0 && (a.run.nhead | a.run.ntail);
+    u32x4 rest[U];
+    u32x4 edge = {0u, 0u, 0u, 0u};
+    if (has_rest) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const u64 idx = nslab * kSlab + (u64)u * kBlock + tid;
+            rest[u] = load16<NT>(a.run.body + (idx < a.run.nvec ? idx : a.run.nvec - 1));
+        }
+    }
+    if (has_edge) edge = edge_vector<F>(a.run, (int)lane);
+
     // load u of a block covers 4 KiB contiguous: every wavefront reads whole 1-KiB tiles
     const u32x4 *p = a.run.body + s0 * kSlab + tid;
     const u64 step = stride * kSlab;
@@ -555,20 +576,15 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
         for (unsigned i = 0; i < a.pause; ++i) __builtin_amdgcn_s_sleep(1);
     }
 
-    // vectors past the last whole slab: one block, lanes past the end contribute zeros
-    if (blockIdx.x == (unsigned)(nslab % G)) {
-        const u64 base = nslab * kSlab;
+    if (has_rest) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            u64 idx = base + (u64)u * kBlock + tid;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (idx < a.run.nvec) v = load16<NT>(a.run.body + idx);
-            F::consume(acc, u, v);
+            const u64 idx = nslab * kSlab + (u64)u * kBlock + tid;
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            F::consume(acc, u, idx < a.run.nvec ? rest[u] : zero);
         }
     }
-    // elements before the first and after the last aligned vector: one zero-padded tile
-    if (blockIdx.x == 0 && wave == 0 && (a.run.nhead | a.run.ntail))
-        F::consume(acc, 0, edge_vector<F>(a.run, (int)lane));
+    if (has_edge) F::consume(acc, 0, edge);
 
     wave_total += F::fold(acc);
 
@@ -809,7 +825,11 @@ template <class F, int U, bool NT>
 __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
 {
     typedef typename F::Total Total;
-    const unsigned tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const unsigned tid = threadIdx.x, lane = tid & 63u;
+    // The wavefront's number, read into a scalar register: a branch on it is then a real branch.  As a per-lane value
+    // it would only mask lanes off, and a matrix instruction ignores that mask: a wavefront that was meant to skip an
+    // MMA would execute it on whatever its registers hold.
+    const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
     constexpr u64 kSlab = (u64)kBlock * U;
     const u64 npieces = a.nseg * a.parts;
     __shared__ Total lds[kWaves];
