@@ -46,7 +46,8 @@ def default_params():
                       ("max_grid", 16384), ("blocks_per_cu", DEFAULTS["blocks_per_cu"]),
                       ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
                       ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("seg_tiles", 1), ("seg_short", 1), ("seg_ragged", 1), ("seg_short_pipe", -1), ("seg_block_bytes", 32768), ("lit_unroll", 0),
-                      ("lit_blocks_per_cu", 0), ("lit_m", 16)):
+                      ("lit_blocks_per_cu", 0), ("lit_m", 16), ("seg_runs", 1), ("seg_run_len", 0),
+                      ("seg_runs_max", 7999), ("seg_runs_long", 36863), ("seg_balance", 1)):
         redux.set_param(name, val)
     redux.set_variant("auto")
 
@@ -700,10 +701,10 @@ def test_shutdown_and_reuse_and_host_threads(dev):
 
 
 def test_randomised_shapes_and_settings(dev):
-    """400 random (entry point, dtype, size, base offset, family, launch parameters) cases against the oracle.
+    """700 random (entry point, dtype, size, base offset, family, launch parameters) cases against the oracle.
     Every case stays inside what the host checks allow; the seed is fixed so a failure names its case."""
     rng = np.random.default_rng(20240)
-    for case in range(400):
+    for case in range(700):
         kind = ("flat", "seg", "multipass")[int(rng.integers(0, 3))]
         is_f16 = bool(rng.integers(0, 2))
         variant = ("mfma", "classic", "auto")[int(rng.integers(0, 3))]
@@ -716,8 +717,8 @@ def test_randomised_shapes_and_settings(dev):
         redux.set_param("nontemporal", int(rng.integers(0, 2)))
         off = int(rng.integers(0, 8 if is_f16 else 16))
         if kind == "seg":
-            nseg = int(rng.choice([1, 2, 17, 300, 5000]))
-            seglen = int(rng.choice([1, 7, 8, 24, 64, 100, 333, 512, 520, 1024, 2048, 4099, 30000]))
+            nseg = int(rng.choice([1, 2, 17, 300, 2100, 5000]))
+            seglen = int(rng.choice([1, 7, 8, 24, 64, 100, 333, 512, 520, 700, 1024, 1500, 2048, 2600, 4099, 9000, 17000, 20001, 30000]))
             if nseg * seglen > (1 << 23):
                 nseg = max(1, (1 << 23) // seglen)
             redux.set_param("seg_parts", int(rng.choice([0, 0, 2, 16])))
@@ -727,9 +728,14 @@ def test_randomised_shapes_and_settings(dev):
             redux.set_param("seg_ragged", int(rng.integers(0, 2)))
             redux.set_param("seg_short_pipe", int(rng.integers(-1, 2)))
             redux.set_param("seg_blocks_per_cu", int(rng.choice([0, 0, 1, 5])))
+            redux.set_param("seg_runs", int(rng.choice([1, 1, 0])))
+            redux.set_param("seg_run_len", int(rng.choice([0, 0, 1, 3, 16])))
+            redux.set_param("seg_runs_max", int(rng.choice([7999, 1 << 18])))
+            redux.set_param("seg_runs_long", int(rng.choice([36863, 0, 1 << 18])))
+            redux.set_param("seg_balance", int(rng.integers(0, 2)))
             n = nseg * seglen
         else:
-            n = int(rng.choice([0, 1, 100, 4097, 70001, (1 << 20) + 5, (1 << 22) + 77]))
+            n = int(rng.choice([0, 1, 100, 4097, 70001, 200000, (1 << 19) - 1, (1 << 20) - 9, (1 << 20) + 5, (1 << 22) + 77]))
             redux.set_param("lit_m", int(rng.choice([4, 16, 32])))
         tag = (case, kind, is_f16, variant, n, off)
         if is_f16:
