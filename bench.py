@@ -48,16 +48,16 @@ HBM_PEAK_GBPS = 8000.0
 # FETCH_SIZE + WRITE_SIZE, scaled by what the same counters read for a plain copy of known size, for the HBM bytes).
 # (workload, family actually run): (HBM bytes per launch, kernel, average kernel duration in us, summary).  Absent = not profiled.
 PROFILED = {
-    ('C1', 'classic'): (2218963, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 5.44, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C1', 'mfma'): (2219987, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 4.98, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C2', 'classic'): (134348897, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 19.75, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C2', 'mfma'): (134349292, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 19.16, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C3', 'classic'): (2147631491, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 288.99, 'profiles/redux_sum_f16_C3.md'),
-    ('C3', 'mfma'): (2147632558, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 289.79, 'profiles/redux_sum_f16_C3.md'),
-    ('C4', 'classic'): (1073873164, 'sum_flat_kernel<I8Classic, 8, true>', 147.29, 'profiles/redux_sum_i8_C4.md'),
-    ('C4', 'mfma'): (1073876236, 'sum_flat_kernel<I8MfmaT<4>, 8, true>', 144.86, 'profiles/redux_sum_i8_C4.md'),
-    ('C5', 'classic'): (537428756, 'sum_segments_tiles_kernel<FloatClassic<0>, 8, true, 0>', 74.66, 'profiles/redux_sum_segmented_f16_C5.md'),
-    ('C5', 'mfma'): (537425734, 'sum_segments_tiles_kernel<FloatMfmaT<0, 1>, 8, true, 1>', 74.32, 'profiles/redux_sum_segmented_f16_C5.md'),
+    ('C1', 'classic'): (2217682, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 5.17, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C1', 'mfma'): (2223826, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 4.74, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C2', 'classic'): (134346572, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 19.78, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C2', 'mfma'): (134354380, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 18.97, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C3', 'classic'): (2147629996, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 289.81, 'profiles/redux_sum_f16_C3.md'),
+    ('C3', 'mfma'): (2147636012, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 290.79, 'profiles/redux_sum_f16_C3.md'),
+    ('C4', 'classic'): (1073879110, 'sum_flat_kernel<I8Classic, 8, true>', 146.92, 'profiles/redux_sum_i8_C4.md'),
+    ('C4', 'mfma'): (1073881136, 'sum_flat_kernel<I8MfmaT<4>, 8, true>', 145.39, 'profiles/redux_sum_i8_C4.md'),
+    ('C5', 'classic'): (537427659, 'sum_segments_tiles_kernel<FloatClassic<0>, 8, true, 0>', 74.58, 'profiles/redux_sum_segmented_f16_C5.md'),
+    ('C5', 'mfma'): (537425648, 'sum_segments_tiles_kernel<FloatMfmaT<0, 1>, 8, true, 1>', 74.51, 'profiles/redux_sum_segmented_f16_C5.md'),
 }
 
 

@@ -596,7 +596,7 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
                 // 6.66 and 6.69; 3500-byte segments in runs of 14, 49000 bytes, 6.44, in runs of 13 or 15 6.72 and 6.79).
                 const u64 over = (c * seg_bytes) % 4096;
                 const double in_step = (over <= 768 || over >= 4096 - 768) ? 1.05 : 1.0;
-                const double cost = (double)full * run_cost(c) * in_step + (tail ? run_cost(tail) : 0.0);
+                const double cost = ((double)full * run_cost(c) + (tail ? run_cost(tail) : 0.0)) * in_step;
                 if (c == 1 || cost <= best) { best = cost; len = c; }
             }
         }
