@@ -74,6 +74,12 @@ CASES = [
     ("classic", torch.float16, 12000, 0, redux.KERNEL_WAVE, 6850),
     ("mfma", torch.float16, 131072, 0, redux.KERNEL_BLOCK, 6900),
     ("mfma", torch.float16, 2 << 20, 0, redux.KERNEL_BLOCK, 6800),
+    ("mfma", torch.float16, 2000, 1, redux.KERNEL_RUNS, 6500),        # 87.4 segments per wavefront: the shared-out last run
+    ("mfma", torch.float16, 36000, 1, redux.KERNEL_RUNS, 6650),       # the runs' range just above 32 KiB
+    ("mfma", torch.float16, 32768, 1, redux.KERNEL_BLOCK, 7000),      # misaligned: edge elements loaded ahead of the stream
+    ("classic", torch.float16, 32768, 1, redux.KERNEL_BLOCK, 6800),
+    ("mfma", torch.float16, 100000, 0, redux.KERNEL_BLOCK, 6700),     # three whole passes and a rest, loaded ahead
+    ("mfma", torch.float16, 2000000, 0, redux.KERNEL_BLOCK, 6400),    # 268 segments: cut into pieces so that the rounds fill
 ]
 
 
