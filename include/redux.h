@@ -272,7 +272,8 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               segments of at most this many 16-byte vectors (and 16-byte aligned) take the
  *                               sixteen-segments-per-wavefront kernel; 0 = never (default 64)
  *   "seg_block_bytes"   0..2^40 segmented sum: segments of at least this many bytes take one 256-thread block
- *                               each (or one per piece) and are streamed like the flat sum; 0 = never (default 32768)
+ *                               each (or one per piece) and are streamed like the flat sum; 0 = never (default 28672: measured, from
+ *                               there on a block is ahead of one wavefront per segment)
  *   "seg_short"         0/1     segmented sum: 16-byte aligned segments of a power-of-two size from 16 to 1024 bytes (4096
  *                               with the MMA family, binary32 excepted) take the contiguous-stream kernel (default 1)
  *   "seg_ragged"        0/1     segmented sum: every other segment of up to 1008 bytes takes that kernel's ragged form

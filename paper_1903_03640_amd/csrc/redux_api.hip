@@ -48,7 +48,8 @@ struct Settings {
     long seg_runs_max = 7999;     // largest segment (bytes) that kernel takes
     long seg_balance = 1;         // long segments are cut into more pieces when the last round of pieces would be mostly empty
     long seg_runs_long = 36863;   // it also takes segments of more than 32 KiB up to this size (0 = none)
-    long seg_block_bytes = 32768; // segments of at least this many bytes take one block each (0 = never)
+    long seg_block_bytes = 28672; // segments of at least this many bytes take one block each (0 = never); measured: from
+                                  // 28 KiB on a block is ahead of one wavefront per segment (7.05 against 6.7 TB/s), at 24 KiB behind
     long lit_unroll = 0;          // groups per wavefront iteration of the level-by-level form (0 = per dtype)
     long lit_blocks_per_cu = 0;
     long lit_m = 16;              // linear size m of the MMA matrices of the level-by-level form

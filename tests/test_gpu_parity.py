@@ -45,7 +45,7 @@ def default_params():
     for name, val in (("unroll", 0), ("nontemporal", 1), ("max_chain", 256),
                       ("max_grid", 16384), ("blocks_per_cu", DEFAULTS["blocks_per_cu"]),
                       ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
-                      ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("seg_tiles", 1), ("seg_short", 1), ("seg_ragged", 1), ("seg_short_pipe", -1), ("seg_block_bytes", 32768), ("lit_unroll", 0),
+                      ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("seg_tiles", 1), ("seg_short", 1), ("seg_ragged", 1), ("seg_short_pipe", -1), ("seg_block_bytes", 28672), ("lit_unroll", 0),
                       ("lit_blocks_per_cu", 0), ("lit_m", 16), ("seg_runs", 1), ("seg_run_len", 0),
                       ("seg_runs_max", 7999), ("seg_runs_long", 36863), ("seg_balance", 1)):
         redux.set_param(name, val)

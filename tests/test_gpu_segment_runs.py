@@ -30,11 +30,12 @@ def dev():
 @pytest.fixture(autouse=True)
 def reset():
     redux.set_param("seg_runs_max", 1 << 18)                     # every size here through this kernel, not only what it takes by default
+    redux.set_param("seg_block_bytes", 32768)
     yield
     redux.set_param("seg_runs_max", 7999)
     redux.set_param("seg_runs_long", 36863)
     for name, val in (("max_grid", 16384), ("seg_blocks_per_cu", 0), ("nontemporal", 1), ("seg_runs", 1), ("seg_run_len", 0),
-                      ("seg_block_bytes", 32768), ("seg_parts", 0), ("seg_short", 1), ("seg_tiles", 1)):
+                      ("seg_block_bytes", 28672), ("seg_parts", 0), ("seg_short", 1), ("seg_tiles", 1)):
         redux.set_param(name, val)
     redux.set_variant("auto")
 

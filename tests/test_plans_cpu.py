@@ -290,7 +290,7 @@ def test_segmented_plan_defaults_on_mi355x():
     redux.set_param("seg_block_bytes", 0)
     long_ = redux.plan_sum_segmented(256, 1 << 20, redux.F16, 0, 256)
     assert (long_.kernel, long_.parts, long_.part_len) == (redux.KERNEL_PIECES, 8, 131072)
-    redux.set_param("seg_block_bytes", 32768)
+    redux.set_param("seg_block_bytes", 28672)
     assert redux.plan_sum_segmented(1, 100, redux.I8, 0, 256).kernel == redux.KERNEL_RAGGED
     assert redux.plan_sum_segmented(1, 2000, redux.I8, 0, 256).kernel == redux.KERNEL_RUNS
 
