@@ -46,6 +46,7 @@ struct Settings {
     long seg_runs = 1;            // use the run-of-segments kernel for segments above 1008 bytes that are not cut into pieces
     long seg_run_len = 0;         // segments per run (0 = from the shape)
     long seg_runs_max = 7999;     // largest segment (bytes) that kernel takes
+    long seg_runs_stream = 1;     // run-of-segments kernel, MMA family: 1 = every register reloaded right after its use
     long seg_balance = 1;         // long segments are cut into more pieces when the last round of pieces would be mostly empty
     long seg_runs_long = 36863;   // it also takes segments of more than 32 KiB up to this size (0 = none)
     long seg_block_bytes = 28672; // segments of at least this many bytes take one block each (0 = never); measured: from
@@ -342,6 +343,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "seg_runs_max")) { *lo = 1009; *hi = 1 << 18; return &g_set.seg_runs_max; }
     if (!std::strcmp(name, "seg_runs_long")) { *lo = 0; *hi = 1 << 18; return &g_set.seg_runs_long; }
     if (!std::strcmp(name, "seg_balance")) { *lo = 0; *hi = 1; return &g_set.seg_balance; }
+    if (!std::strcmp(name, "seg_runs_stream")) { *lo = 0; *hi = 1; return &g_set.seg_runs_stream; }
     if (!std::strcmp(name, "seg_run_len")) { *lo = 0; *hi = 16; return &g_set.seg_run_len; }
     if (!std::strcmp(name, "seg_tiles")) { *lo = 0; *hi = 1; return &g_set.seg_tiles; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
@@ -563,12 +565,15 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
     if (p.kernel == REDUX_KERNEL_WAVE && (runs_fit || runs_long)) {
         p.kernel = REDUX_KERNEL_RUNS;
         const bool mfma = effective_variant(S, dtype) == REDUX_VARIANT_MFMA;
-        // measured: the MMA family runs best with four loads per lane in flight and three blocks per compute unit (the
-        // fold and the store at the end of a run leave gaps that other wavefronts fill); the classic family, whose lanes
-        // also convert and add, wants eight loads and more wavefronts the shorter the segments are
+        // measured: the MMA family runs best with four loads per lane in flight; its rolling form, which keeps them in
+        // flight across the end of a run, with two blocks per compute unit (three below 1.5 KB, where the boundaries
+        // take more instructions), its plain form with three (the fold and the store at the end of a run leave gaps that
+        // other wavefronts fill); the classic family, whose lanes also convert and add, wants eight loads and more
+        // wavefronts the shorter the segments are
         p.unroll = S.unroll == 0 ? (mfma ? 4 : 8) : (S.unroll <= 4 ? 4 : 8);
         const u64 step = 64 * (u64)p.unroll;                                    // vectors per iteration of a wavefront
-        const long bpc = S.seg_blocks_per_cu ? S.seg_blocks_per_cu : (mfma ? 3 : seg_bytes < 2560 ? 8 : 4);
+        const long bpc = S.seg_blocks_per_cu ? S.seg_blocks_per_cu
+                       : mfma ? (S.seg_runs_stream && seg_bytes >= 1536 ? 2 : 3) : seg_bytes < 2560 ? 8 : 4;
         u64 gmax = (u64)cus * (u64)bpc;
         if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
         if (gmax < 1) gmax = 1;
@@ -592,11 +597,13 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
                 const u64 waves = (blocks < gmax ? blocks : gmax) * kWaves;
                 const u64 full = nseg / (waves * c);
                 const u64 tail = (nseg - full * waves * c + waves - 1) / waves;
-                // Runs whose length is close to a multiple of 4 KiB make neighbouring wavefronts walk the same memory
-                // channels in step (measured: 2052-byte segments in runs of 8, 16416 bytes, 6.29 TB/s, in runs of 7 or 9
-                // 6.66 and 6.69; 3500-byte segments in runs of 14, 49000 bytes, 6.44, in runs of 13 or 15 6.72 and 6.79).
-                const u64 over = (c * seg_bytes) % 4096;
-                const double in_step = (over <= 768 || over >= 4096 - 768) ? 1.05 : 1.0;
+                // Runs whose length is close to a multiple of 4 KiB, and more so of 32 KiB, make neighbouring wavefronts
+                // walk the same memory channels in step (measured: 2052-byte segments in runs of 8, 16416 bytes, 6.29 TB/s,
+                // in runs of 7 or 9 6.66 and 6.69; 3500-byte segments in runs of 14, 49000 bytes, 6.44, in runs of 13 or
+                // 15 6.72 and 6.79; on 128 MiB, 4000-byte segments in runs of 16, 64000 bytes, 6.1, in runs of 15 6.8).
+                const u64 over = (c * seg_bytes) % 4096, over32 = (c * seg_bytes) % 32768;
+                const double in_step = (over32 <= 2560 || over32 >= 32768 - 2560) ? 1.10
+                                     : (over <= 768 || over >= 4096 - 768) ? 1.05 : 1.0;
                 const double cost = ((double)full * run_cost(c) + (tail ? run_cost(tail) : 0.0)) * in_step;
                 if (c == 1 || cost <= best) { best = cost; len = c; }
             }
@@ -855,7 +862,8 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
             typedef decltype(elem) E;
 #define REDUX_RUNS(KERNEL, UU) do { if (nt) hipLaunchKernelGGL((KERNEL<E, UU, true>), dim3(grid), dim3(kBlock), 0, st, r); \
                                     else    hipLaunchKernelGGL((KERNEL<E, UU, false>), dim3(grid), dim3(kBlock), 0, st, r); } while (0)
-            if (mfma) { if (plan.unroll == 8) REDUX_RUNS(sum_segment_runs_mfma_kernel, 8); else REDUX_RUNS(sum_segment_runs_mfma_kernel, 4); }
+            if (mfma && S.seg_runs_stream) { if (plan.unroll == 8) REDUX_RUNS(sum_segment_runs_mfma_stream_kernel, 8); else REDUX_RUNS(sum_segment_runs_mfma_stream_kernel, 4); }
+            else if (mfma) { if (plan.unroll == 8) REDUX_RUNS(sum_segment_runs_mfma_kernel, 8); else REDUX_RUNS(sum_segment_runs_mfma_kernel, 4); }
             else      { if (plan.unroll == 8) REDUX_RUNS(sum_segment_runs_classic_kernel, 8); else REDUX_RUNS(sum_segment_runs_classic_kernel, 4); }
 #undef REDUX_RUNS
         });

@@ -273,4 +273,123 @@ __global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_kernel(RunArgs a
     }
 }
 
+// The same with the loads rolling: every register is loaded again -- with the vector that the wavefront's next
+// iteration needs in it, which may belong to its next run -- as soon as it has been used, so U loads are in flight
+// all the time, also while a run's second MMA and store are under way, and one block per compute unit is enough.
+// The skeleton is that of the short-segment kernels: a loop whose every pass uses and reloads each register once, in
+// the order the loads were issued in, and a last pass without loads.  Every reload is one load instruction whatever
+// the position (lanes behind the run's last vector read that vector again), and the results are stored by a masked
+// store that is issued in every pass (no lane takes part except at the end of a run), so that the number of memory
+// operations between a load and its use is the same on every path and the waits can be exact.  A run with a
+// non-finite D' is only noted (one bit for each of the wavefront's first 64 runs, one for all later ones together)
+// and summed again by the classic form when the stream has ended, so that no load of the stream sits behind a branch.
+template <class E, int U, bool NT>
+__global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_stream_kernel(RunArgs a)
+{
+    typedef typename E::Out Out;
+    const unsigned lane = threadIdx.x & 63u, n = lane & 15u;
+    const int lane16 = 16 * (int)lane;
+    const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    __shared__ u32x4 low[17];
+    fill_low_masks(low);
+    const RunShare sh = run_share(a.layout, a.nseg, a.per_run, gridDim.x, blockIdx.x, wave);
+    const u64 nruns = sh.full + (sh.tail_count != 0u ? 1u : 0u);      // this wavefront's runs
+    if (nruns == 0) return;
+
+    // where an iteration lies: run k of the wavefront, 64 U vectors from v0 on (scalar registers throughout)
+    struct Iter { u64 k; unsigned v0; RunGeometry g; };
+    const auto geometry = [&](u64 k) {
+        const bool last = k == sh.full;
+        return run_geometry(a, last ? sh.tail_first : sh.first + k * sh.stride, last ? sh.tail_count : a.per_run);
+    };
+    const auto advance = [&](Iter &it) {
+        it.v0 += 64u * U;
+        if (it.v0 >= it.g.nvec) {
+            ++it.k;
+            it.v0 = 0u;
+            if (it.k < nruns) it.g = geometry(it.k);
+        }
+    };
+    const auto fetch = [&](const Iter &it, int u) -> u32x4 {
+        const unsigned idx = it.v0 + 64u * (unsigned)u + lane;
+        return load16<NT>(it.g.base + (idx < it.g.nvec ? idx : it.g.nvec - 1u));
+    };
+
+    typename E::Acc acc = E::zero();
+    RunCursor c;
+    u64 redo = 0;                                  // bit k: run k of this wavefront must be summed again
+    bool redo_later = false;                       // ... and every run from the 64th on
+    // one iteration: its U loads into the accumulator columns, each register reloaded by `refill` right after its use;
+    // at the end of a run the second MMA; the store in every pass
+    const auto work = [&](u32x4 *cur, const Iter &it, auto refill) {
+        const RunGeometry &g = it.g;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned p = (it.v0 + 64u * (unsigned)u) * 16u;    // first byte of this load, from base
+            const u32x4 v = cur[u];
+            if (p < g.total) {                                       // (the same for every lane)
+                if (c.next - p >= 1024u) {                           // no boundary in this load: one MMA, nothing cleared
+                    if (c.col < g.count) acc = E::mma1(v, n == c.col, acc);
+                } else {
+                    u32x4 done = {0u, 0u, 0u, 0u};                   // bytes already handed to a segment
+                    do {
+                        const u32x4 front = low[bytes_in_front(c.next - p, lane16)];
+                        if (c.col < g.count) acc = E::mma1(v & front & ~done, n == c.col, acc);
+                        done = front;
+                        c.pass(g, a.seg_bytes);
+                    } while (c.next - p < 1024u);
+                    if (c.col < g.count) acc = E::mma1(v & ~done, n == c.col, acc);
+                }
+            }
+            refill(u);
+        }
+        const bool run_ends = it.v0 + 64u * U >= g.nvec;
+        Out total = 0;
+        unsigned stores = 0u;                                        // lanes that store: none, except at the end of a run
+        if (run_ends) {
+            bool bad;
+            total = E::fold_out_wide(run_fold(acc, &bad));
+            const bool any = E::kCanBeNonFinite && __builtin_amdgcn_ballot_w64(bad) != 0;
+            if (any) {
+                if (it.k < 64) redo |= 1ull << it.k;
+                else redo_later = true;
+            }
+            stores = any ? 0u : g.count;
+            acc = E::zero();
+        }
+        if (lane < stores) ((Out *)a.out)[g.first + lane] = total;    // lanes 0 .. 15 hold columns 0 .. 15
+    };
+
+    Iter it;
+    it.k = 0;
+    it.v0 = 0u;
+    it.g = geometry(0);
+    c.start(it.g);
+    u32x4 cur[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {                  // issued strictly in the order they are used in: the waits count on it
+        cur[u] = fetch(it, u);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    while (true) {
+        Iter nx = it;
+        advance(nx);
+        if (nx.k >= nruns) break;
+        __builtin_amdgcn_sched_barrier(0);
+        work(cur, it, [&](int u) {
+            cur[u] = fetch(nx, u);
+            __builtin_amdgcn_sched_barrier(0);     // keep the reload right behind the use
+        });
+        if (nx.k != it.k) c.start(nx.g);
+        it = nx;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    work(cur, it, [](int) {});
+    if (redo != 0 || redo_later) {
+        __builtin_amdgcn_s_waitcnt(0);             // the first pass's stores have landed
+        for (u64 k = 0; k < nruns; ++k)
+            if (k < 64 ? ((redo >> k) & 1u) != 0 : redo_later) run_classic<E, U, NT>(a, geometry(k), low, lane);
+    }
+}
+
 } // namespace redux

@@ -92,6 +92,20 @@ def test_run_kernels_wait_for_the_oldest_load_first(kernels):
             assert body.count("s_cbranch_scc") > 2 * body.count("s_cbranch_exec"), name
 
 
+def test_rolling_run_kernel_keeps_its_loads_in_flight(kernels):
+    # the rolling form reloads every register right after its use: inside its main loop every wait in front of a use
+    # leaves the U - 1 younger loads in flight (vmcnt(U - 1), at least once per register), and a reload follows each use
+    for u in (4, 8):
+        for name in pick(kernels, "sum_segment_runs_mfma_stream_kernel", "Li%dELb1E" % u):
+            body = kernels[name][0]
+            loop = body[body.index("Loop Header: Depth=1"):]
+            first_reloads = loop[:loop.index("global_store")]            # the main loop up to the store at the end of a pass
+            assert len(re.findall(r"s_waitcnt vmcnt\(%d\)" % (u - 1), first_reloads)) >= u, name
+            assert len(re.findall(r"global_load_dwordx4", first_reloads)) == u, name
+            assert not re.search(r"s_waitcnt vmcnt\(0\)", first_reloads), name
+            assert body.count("s_cbranch_scc") > 2 * body.count("s_cbranch_exec"), name
+
+
 def test_register_counts(kernels):
     for name in pick(kernels, "sum_segment_runs_"):
         assert kernels[name][1] <= 128, (name, kernels[name][1])       # four blocks per compute unit fit

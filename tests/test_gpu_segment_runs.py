@@ -34,7 +34,7 @@ def reset():
     yield
     redux.set_param("seg_runs_max", 7999)
     redux.set_param("seg_runs_long", 36863)
-    for name, val in (("max_grid", 16384), ("seg_blocks_per_cu", 0), ("nontemporal", 1), ("seg_runs", 1), ("seg_run_len", 0),
+    for name, val in (("max_grid", 16384), ("seg_blocks_per_cu", 0), ("nontemporal", 1), ("seg_runs", 1), ("seg_run_len", 0), ("seg_runs_stream", 1),
                       ("seg_block_bytes", 28672), ("seg_parts", 0), ("seg_short", 1), ("seg_tiles", 1)):
         redux.set_param(name, val)
     redux.set_variant("auto")
@@ -186,6 +186,64 @@ def test_runs_take_segments_just_above_32_kib_by_default(dev, kind, variant):
         pats = patterns(kind, seg_bytes + nseg, nseg * seglen)
         xd = to_dev_at(pats, kind, dev, offset)
         assert redux.plan_sum_segmented(nseg, seglen, CODE[kind], x_address=xd.data_ptr() % 16, compute_units=256).kernel == kernel
+        got = redux.sum_segmented(xd, nseg, seglen)
+        torch.cuda.synchronize()
+        check(got, pats, kind, nseg, seglen, TOL, (kind, seg_bytes, nseg, offset))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_rolling_and_plain_form_give_the_same_bits(dev, kind):
+    """The MMA family has two forms of this kernel: loads rolling across the ends of runs (the default) and run by run.
+    Given the same grid and run length both issue the same MMAs on the same data in the same order, so every result must
+    be the same bit for bit: small and large shapes, every run length, tiny grids.  A run with a non-finite value is summed again by the classic form in
+    both, run by run (the rolling form keeps one bit for each of a wavefront's first 64 runs), so with NaNs in the data
+    and at most 64 runs per wavefront the two still agree bit for bit."""
+    redux.set_variant("mfma")
+    es = ESIZE[kind]
+    redux.set_param("seg_parts", 1)
+    redux.set_param("seg_blocks_per_cu", 3)                      # the same grid, and so the same runs, for both forms
+    for seg_bytes, nseg, offset in ((1012, 1, 0), (1012, 5, 1), (1040, 37, 3), (2000, 1000, 1), (3000, 70001, 0), (4100, 333, 5), (8200, 64, 1),
+                                    (20000, 17, 2), (1016, 30000, 1), (32766, 9, 3)):
+        if seg_bytes % es:
+            continue
+        seglen = seg_bytes // es
+        for with_nan in (False, True):
+            if with_nan and (kind == "i8" or nseg < 5):
+                continue
+            pats = patterns(kind, seg_bytes + nseg, nseg * seglen).copy()
+            if with_nan:
+                bits = pats.view({1: np.uint8, 2: np.uint16, 4: np.uint32}[es])
+                nan = {"f16": 0x7E00, "bf16": 0x7FC0, "f32": 0x7FC00000, "e5m2": 0x7E, "e4m3": 0x7F}[kind]
+                bits[seglen + 3] = nan
+                bits[(nseg - 1) * seglen] = nan
+            xd = to_dev_at(pats, kind, dev, offset)
+            # (with NaNs only shapes of at most 64 runs per wavefront: the default grid, or few segments)
+            for run_len, max_grid in ((0, 16384), (1, 16384), (16, 16384)) + (((3, 2), (16, 1)) if not with_nan or nseg <= 64 else ()):
+                redux.set_param("seg_run_len", run_len)
+                redux.set_param("max_grid", max_grid)
+                assert redux.plan_sum_segmented(nseg, seglen, CODE[kind], x_address=xd.data_ptr() % 16, compute_units=256).kernel == redux.KERNEL_RUNS
+                redux.set_param("seg_runs_stream", 0)
+                plain = redux.sum_segmented(xd, nseg, seglen)
+                redux.set_param("seg_runs_stream", 1)
+                rolling = redux.sum_segmented(xd, nseg, seglen)
+                torch.cuda.synchronize()
+                a, b = plain.cpu().numpy(), rolling.cpu().numpy()
+                assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), (kind, seg_bytes, nseg, offset, with_nan, run_len, max_grid)
+
+
+@pytest.mark.parametrize("kind", ("f16", "i8"))
+def test_plain_form_against_oracle(dev, kind):
+    """The run-by-run form is no longer what runs by default: its own pass against the oracle."""
+    redux.set_variant("mfma")
+    redux.set_param("seg_runs_stream", 0)
+    redux.set_param("seg_parts", 1)
+    es = ESIZE[kind]
+    for seg_bytes, nseg, offset in ((1010, 37, 1), (3000, 5000, 0), (8200, 300, 3), (30000, 40, 1)):
+        if seg_bytes % es:
+            continue
+        seglen = seg_bytes // es
+        pats = patterns(kind, seg_bytes, nseg * seglen)
+        xd = to_dev_at(pats, kind, dev, offset)
         got = redux.sum_segmented(xd, nseg, seglen)
         torch.cuda.synchronize()
         check(got, pats, kind, nseg, seglen, TOL, (kind, seg_bytes, nseg, offset))

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(redux.LIB_PATH), reason="libr
 
 ES = {redux.F16: 2, redux.I8: 1, redux.BF16: 2, redux.F32: 4, redux.F8E4M3: 1, redux.F8E5M2: 1}
 DTYPES = sorted(ES)
-PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short", "seg_ragged", "seg_runs", "seg_run_len", "seg_runs_max", "seg_runs_long", "seg_balance")
+PARAMS = ("blocks_per_cu", "seg_blocks_per_cu", "max_grid", "unroll", "finish", "rows_max_vec", "seg_parts", "seg_tiles", "seg_block_bytes", "layout", "seg_short", "seg_ragged", "seg_runs", "seg_run_len", "seg_runs_max", "seg_runs_long", "seg_balance", "seg_runs_stream")
 
 
 @pytest.fixture(autouse=True)
@@ -223,13 +223,17 @@ def test_segmented_plan_defaults_on_mi355x():
     assert redux.plan_sum_segmented(1023, 4096, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE    # too few segments for the whole-tile kernel
     assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE   # 8208 B: above the run kernel's range
     three = redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256)                           # 3 KiB: not a power of two
-    assert (three.kernel, three.vectors, three.unroll, three.grid) == (redux.KERNEL_RUNS, 13, 4, 768)   # 21.3 segments per wavefront on three blocks per CU: a run of 13 and a last one of 8 or 9
+    assert (three.kernel, three.vectors, three.unroll, three.grid) == (redux.KERNEL_RUNS, 13, 4, 512)   # 32 segments per wavefront on two blocks per CU: two runs of 13 and a last one of 6 (runs of 16 would be 48 KiB: in step with the memory channels)
     few = redux.plan_sum_segmented(40, 2050, redux.F16, 0, 256)
     assert (few.kernel, few.vectors, few.grid) == (redux.KERNEL_RUNS, 1, 10)                      # few segments: one per run
     redux.set_variant("classic")
     three = redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256)
     assert (three.kernel, three.unroll) == (redux.KERNEL_RUNS, 8) and three.grid in (4 * 256, 8 * 256)
     redux.set_variant("auto")
+    redux.set_param("seg_runs_stream", 0)                                                          # the plain form wants three blocks per CU
+    assert redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256).grid == 768
+    redux.set_param("seg_runs_stream", 1)
+    assert redux.plan_sum_segmented(65536, 600, redux.F16, 0, 256).grid == 768                     # 1200 B: three also for the rolling form
     redux.set_param("seg_runs", 0)
     assert redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE
     redux.set_param("seg_runs", 1)
