@@ -214,7 +214,7 @@ typedef enum {
                                 shortened lane butterfly) yield every segment's sum */
     REDUX_KERNEL_RAGGED = 7, /* redux_sum_segmented, any other segment of up to 1008 bytes: the same kernel, each group
                                 of `vectors` lanes reading the aligned vectors that overlap its segment */
-    REDUX_KERNEL_RUNS   = 8  /* redux_sum_segmented, segments from 1009 to 7999 bytes (and from 32769 to 36863 when there
+    REDUX_KERNEL_RUNS   = 8  /* redux_sum_segmented, segments from 1009 to 28671 bytes (classic family: 7999; and from 32769 to 36863 when there
                                 are many) of any length and alignment: one
                                 wavefront streams a run of `vectors` (1 .. 16) consecutive whole segments, every lane of
                                 every load busy; each segment of the run owns one column of the MMA accumulator */
@@ -281,8 +281,9 @@ int redux_resolved_variant(int dtype, int segmented);
  *   "seg_runs"          0/1     segmented sum: segments of more than 1008 and at most "seg_runs_max" bytes (and less than
  *                               "seg_block_bytes") that are not cut into pieces take the run-of-segments kernel; 0 = one
  *                               wavefront per segment instead (default 1)
- *   "seg_runs_max"      1009..2^18  largest segment in bytes that kernel takes (default 7999: measured, from 8000 bytes
- *                               on one wavefront per segment is faster)
+ *   "seg_runs_max"      0, 1009..2^18  largest segment in bytes that kernel takes; 0 = by family (default): 28671 for the
+ *                               MMA family's rolling form (up to where one block per segment takes over), 7999 for the
+ *                               run-by-run forms (measured: from 8000 bytes on one wavefront per segment is ahead of them)
  *   "seg_runs_long"     0..2^18 that kernel also takes segments of more than 32768 bytes up to this size when there are
  *                               at least eight per compute unit (default 36863: measured, one block per segment leaves
  *                               most of its second 32 KiB pass idle there; 0 = none)

@@ -45,7 +45,7 @@ struct Settings {
     long seg_tiles = 1;           // use the pipelined kernel for segments of 1, 2, 4 or 8 whole tiles
     long seg_runs = 1;            // use the run-of-segments kernel for segments above 1008 bytes that are not cut into pieces
     long seg_run_len = 0;         // segments per run (0 = from the shape)
-    long seg_runs_max = 7999;     // largest segment (bytes) that kernel takes
+    long seg_runs_max = 0;        // largest segment (bytes) that kernel takes (0 = by family: 28671 MMA rolling form, else 7999)
     long seg_runs_stream = 1;     // run-of-segments kernel, MMA family: 1 = every register reloaded right after its use
     long seg_balance = 1;         // long segments are cut into more pieces when the last round of pieces would be mostly empty
     long seg_runs_long = 36863;   // it also takes segments of more than 32 KiB up to this size (0 = none)
@@ -340,7 +340,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "seg_ragged")) { *lo = 0; *hi = 1; return &g_set.seg_ragged; }
     if (!std::strcmp(name, "seg_short")) { *lo = 0; *hi = 1; return &g_set.seg_short; }
     if (!std::strcmp(name, "seg_runs")) { *lo = 0; *hi = 1; return &g_set.seg_runs; }
-    if (!std::strcmp(name, "seg_runs_max")) { *lo = 1009; *hi = 1 << 18; return &g_set.seg_runs_max; }
+    if (!std::strcmp(name, "seg_runs_max")) { *lo = 0; *hi = 1 << 18; return &g_set.seg_runs_max; }
     if (!std::strcmp(name, "seg_runs_long")) { *lo = 0; *hi = 1 << 18; return &g_set.seg_runs_long; }
     if (!std::strcmp(name, "seg_balance")) { *lo = 0; *hi = 1; return &g_set.seg_balance; }
     if (!std::strcmp(name, "seg_runs_stream")) { *lo = 0; *hi = 1; return &g_set.seg_runs_stream; }
@@ -448,7 +448,12 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
     // short segments: sixteen per wavefront, one per row of the A operand
     // (only when the ragged form below is switched off: measured, that form is as fast or faster at every size)
     const auto ragged_lanes = [](u64 cover) { u64 l = 1; while (l < cover) l *= 2; return l; };
-    const bool runs_fit = S.seg_runs && seg_bytes > 1008 && seg_bytes <= (u64)S.seg_runs_max;
+    // (measured: the MMA family's rolling form is level with or ahead of one wavefront per segment up to where one block
+    // per segment takes over, and far more even -- 6.7-7.0 against 6.5-7.1 TB/s on 512 MiB, 6.0-6.6 against 5.5-6.6 on
+    // 128 MiB; the run-by-run forms are ahead only below 8000 bytes)
+    const u64 runs_max = S.seg_runs_max ? (u64)S.seg_runs_max
+                       : (effective_variant(S, dtype) == REDUX_VARIANT_MFMA && S.seg_runs_stream) ? 28671 : 7999;
+    const bool runs_fit = S.seg_runs && seg_bytes > 1008 && seg_bytes <= runs_max;
     // Segments a little longer than the 32 KiB that a block reads at a time leave most of its second pass idle
     // (measured, 33000 and 36000 bytes: 6.4 and 6.5 TB/s by one block per segment, 6.7 as runs; from 40000 bytes on the
     // block is ahead, 6.8 against 6.5), so while there are enough of them to give every wavefront its own they go as runs too.
@@ -559,9 +564,9 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
         p.parts = parts;
         p.part_len = ((seglen + parts - 1) / parts + 511) / 512 * 512;
     }
-    // Whole segments of more than 1008 bytes and less than 8000 (measured: from there on one wavefront per segment is
-    // level or ahead, 6.8 against 6.7 TB/s at 8000 B, 6.9 against 6.5 at 12000 B), and those just above 32 KiB: a
-    // wavefront streams a run of up to sixteen of them as one contiguous piece.
+    // Whole segments of more than 1008 bytes up to 28 KiB (the run-by-run forms: less than 8000 bytes, from where on one
+    // wavefront per segment is level or ahead of them), and those just above 32 KiB: a wavefront streams a run of up to
+    // sixteen of them as one contiguous piece.
     if (p.kernel == REDUX_KERNEL_WAVE && (runs_fit || runs_long)) {
         p.kernel = REDUX_KERNEL_RUNS;
         const bool mfma = effective_variant(S, dtype) == REDUX_VARIANT_MFMA;

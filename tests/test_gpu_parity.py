@@ -47,7 +47,7 @@ def default_params():
                       ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
                       ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("seg_tiles", 1), ("seg_short", 1), ("seg_ragged", 1), ("seg_short_pipe", -1), ("seg_block_bytes", 28672), ("lit_unroll", 0),
                       ("lit_blocks_per_cu", 0), ("lit_m", 16), ("seg_runs", 1), ("seg_run_len", 0),
-                      ("seg_runs_max", 7999), ("seg_runs_long", 36863), ("seg_balance", 1)):
+                      ("seg_runs_max", 0), ("seg_runs_long", 36863), ("seg_balance", 1), ("seg_runs_stream", 1)):
         redux.set_param(name, val)
     redux.set_variant("auto")
 
@@ -730,7 +730,8 @@ def test_randomised_shapes_and_settings(dev):
             redux.set_param("seg_blocks_per_cu", int(rng.choice([0, 0, 1, 5])))
             redux.set_param("seg_runs", int(rng.choice([1, 1, 0])))
             redux.set_param("seg_run_len", int(rng.choice([0, 0, 1, 3, 16])))
-            redux.set_param("seg_runs_max", int(rng.choice([7999, 1 << 18])))
+            redux.set_param("seg_runs_max", int(rng.choice([0, 7999, 1 << 18])))
+            redux.set_param("seg_runs_stream", int(rng.integers(0, 2)))
             redux.set_param("seg_runs_long", int(rng.choice([36863, 0, 1 << 18])))
             redux.set_param("seg_balance", int(rng.integers(0, 2)))
             n = nseg * seglen

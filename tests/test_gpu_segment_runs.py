@@ -32,7 +32,7 @@ def reset():
     redux.set_param("seg_runs_max", 1 << 18)                     # every size here through this kernel, not only what it takes by default
     redux.set_param("seg_block_bytes", 32768)
     yield
-    redux.set_param("seg_runs_max", 7999)
+    redux.set_param("seg_runs_max", 0)
     redux.set_param("seg_runs_long", 36863)
     for name, val in (("max_grid", 16384), ("seg_blocks_per_cu", 0), ("nontemporal", 1), ("seg_runs", 1), ("seg_run_len", 0), ("seg_runs_stream", 1),
                       ("seg_block_bytes", 28672), ("seg_parts", 0), ("seg_short", 1), ("seg_tiles", 1)):
@@ -178,7 +178,7 @@ def test_runs_take_segments_just_above_32_kib_by_default(dev, kind, variant):
     """With every setting at its default, many segments of a little more than 32 KiB go through this kernel (few of them, or
     longer ones, through one block per segment); the wavefronts' last, shorter runs are part of what is checked."""
     redux.set_variant(variant)
-    redux.set_param("seg_runs_max", 7999)
+    redux.set_param("seg_runs_max", 0)
     es = ESIZE[kind]
     for seg_bytes, nseg, offset, kernel in ((36002, 2100, 1, redux.KERNEL_RUNS), (33000, 2048, 0, redux.KERNEL_RUNS),
                                             (36002, 2047, 1, redux.KERNEL_BLOCK), (36864, 2100, 0, redux.KERNEL_BLOCK), (40000, 2100, 1, redux.KERNEL_BLOCK)):

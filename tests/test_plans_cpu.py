@@ -132,7 +132,7 @@ def test_run_share_extremes():
        seg_parts=st.sampled_from([0, 0, 0, 2, 8, 64, 4096]), rows_max=st.sampled_from([64, 64, 0, 5]),
        seg_bpc=st.integers(0, 16), unroll=st.sampled_from([0, 1, 2, 4, 8]), block_bytes=st.sampled_from([32768, 32768, 0, 1000]),
        seg_short=st.sampled_from([1, 1, 0]), seg_ragged=st.sampled_from([1, 1, 0]), seg_runs=st.sampled_from([1, 1, 0]),
-       run_len=st.sampled_from([0, 0, 0, 1, 5, 16]), runs_max=st.sampled_from([7999, 7999, 1 << 18]),
+       run_len=st.sampled_from([0, 0, 0, 1, 5, 16]), runs_max=st.sampled_from([0, 0, 7999, 1 << 18]),
        runs_long=st.sampled_from([36863, 36863, 0, 1 << 18]))
 def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts, rows_max, seg_bpc, unroll, block_bytes, seg_short, seg_ragged,
                                    seg_runs, run_len, runs_max, runs_long):
@@ -148,6 +148,7 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
     redux.set_param("seg_runs", seg_runs)
     redux.set_param("seg_run_len", run_len)
     redux.set_param("seg_runs_max", runs_max)
+    runs_max = runs_max or (28671 if redux.resolved_variant(dtype, True) == "mfma" else 7999)   # 0 = by family
     redux.set_param("seg_runs_long", runs_long)
     p = redux.plan_sum_segmented(nseg, seglen, dtype, addr, cus)
     assert 1 <= p.grid <= 16 * cus
@@ -218,10 +219,22 @@ def test_segmented_plan_defaults_on_mi355x():
     assert redux.plan_sum_segmented(65536, 512, redux.F32, 0, 256).grid == 768                  # binary32, 2 KiB: whole-tile kernel, three blocks per CU
     redux.set_param("seg_tiles", 0)
     c5 = redux.plan_sum_segmented(65536, 4096, redux.F16, 0, 256)
+    assert (c5.kernel, c5.unroll, c5.grid, c5.parts) == (redux.KERNEL_RUNS, 4, 512, 1)            # runs of whole segments, rolling loads, two blocks per CU
+    redux.set_param("seg_runs", 0)
+    c5 = redux.plan_sum_segmented(65536, 4096, redux.F16, 0, 256)
     assert (c5.kernel, c5.unroll, c5.grid, c5.parts) == (redux.KERNEL_WAVE, 2, 1024, 1)           # 512 vectors: two loads per lane, four blocks per CU
+    redux.set_param("seg_runs", 1)
     redux.set_param("seg_tiles", 1)
-    assert redux.plan_sum_segmented(1023, 4096, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE    # too few segments for the whole-tile kernel
-    assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE   # 8208 B: above the run kernel's range
+    assert redux.plan_sum_segmented(1023, 4096, redux.F16, 0, 256).kernel == redux.KERNEL_RUNS    # too few segments for the whole-tile kernel
+    assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_RUNS   # 8208 B: the rolling form reaches up to 28 KiB
+    assert redux.plan_sum_segmented(65536, 14000, redux.F16, 0, 256).kernel == redux.KERNEL_RUNS      # 28000 B
+    assert redux.plan_sum_segmented(65536, 14336, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK     # 28 KiB
+    redux.set_variant("classic")
+    assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE   # the run-by-run forms stop below 8000 B
+    redux.set_variant("auto")
+    redux.set_param("seg_runs_stream", 0)
+    assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE
+    redux.set_param("seg_runs_stream", 1)
     three = redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256)                           # 3 KiB: not a power of two
     assert (three.kernel, three.vectors, three.unroll, three.grid) == (redux.KERNEL_RUNS, 13, 4, 512)   # 32 segments per wavefront on two blocks per CU: two runs of 13 and a last one of 6 (runs of 16 would be 48 KiB: in step with the memory channels)
     few = redux.plan_sum_segmented(40, 2050, redux.F16, 0, 256)
@@ -237,9 +250,9 @@ def test_segmented_plan_defaults_on_mi355x():
     redux.set_param("seg_runs", 0)
     assert redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE
     redux.set_param("seg_runs", 1)
-    redux.set_param("seg_runs_max", 1 << 18)
-    assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_RUNS
     redux.set_param("seg_runs_max", 7999)
+    assert redux.plan_sum_segmented(65536, 4096 + 8, redux.F16, 0, 256).kernel == redux.KERNEL_WAVE
+    redux.set_param("seg_runs_max", 0)
     # just above 32 KiB a block's second pass would be mostly idle: runs, while every wavefront can have a segment of its own
     assert redux.plan_sum_segmented(2048, 18000, redux.F16, 0, 256).kernel == redux.KERNEL_RUNS
     assert redux.plan_sum_segmented(2047, 18000, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK

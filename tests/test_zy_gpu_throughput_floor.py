@@ -70,7 +70,8 @@ CASES = [
     ("mfma", torch.float16, 3000, 1, redux.KERNEL_RUNS, 6750),
     ("mfma", torch.int8, 5000, 3, redux.KERNEL_RUNS, 6700),
     ("classic", torch.float16, 3000, 0, redux.KERNEL_RUNS, 6600),
-    ("mfma", torch.float16, 12000, 0, redux.KERNEL_WAVE, 7000),
+    ("mfma", torch.float16, 12000, 0, redux.KERNEL_RUNS, 6900),
+    ("mfma", torch.float16, 24000, 1, redux.KERNEL_RUNS, 6950),
     ("classic", torch.float16, 12000, 0, redux.KERNEL_WAVE, 6850),
     ("mfma", torch.float16, 131072, 0, redux.KERNEL_BLOCK, 6900),
     ("mfma", torch.float16, 2 << 20, 0, redux.KERNEL_BLOCK, 6800),
