@@ -70,8 +70,9 @@ typedef enum {
 /* Which kernel family computes the sum. */
 typedef enum {
     REDUX_VARIANT_AUTO    = 0, /* MFMA (as fast as CLASSIC on the flat sum, with the vector ALU idle; faster on segmented
-                                  sums) -- except CLASSIC for the 8-bit floats, whose MFMAs drop bits, and for the flat
-                                  sum of binary32, whose MMA needs four MFMAs per load and measures 5 % slower */
+                                  sums) -- except CLASSIC for the 8-bit floats, whose MFMAs drop bits, and for binary32,
+                                  whose MMA needs four MFMAs per load and measures 5 % (flat sum) to 25 % (segmented
+                                  sums) slower */
     REDUX_VARIANT_MFMA    = 1, /* MMA encoding: data tile x all-ones, accumulator chained through C   */
     REDUX_VARIANT_CLASSIC = 2  /* per-lane serial accumulation + wavefront tree (Section III)         */
 } redux_variant;

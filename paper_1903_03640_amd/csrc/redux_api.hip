@@ -318,9 +318,12 @@ int effective_variant(const Settings &S, int dtype, bool flat = false)
     // (interleaved runs of 100 calls: 289.8 +- 0.4 against 289.2 +- 0.3 us on 2 GiB of binary16), so the tie goes to the
     // family that keeps the vector ALU idle (2.9 % against 21.5 % busy); after an idle period the MMA family is also
     // 3 % faster for the first forty calls (294 against 304 us).  Segmented sums: as fast (8 KiB segments) or 5-30 %
-    // faster (short and ragged segments).  Binary32 flat sums are the exception: its MMA takes four K-slices, hence four
-    // 8-pass MFMAs, per 16-byte load, and measures 5 % behind the classic family (306 against 290 us on 2 GiB).
-    if (flat && dtype == REDUX_F32) return REDUX_VARIANT_CLASSIC;
+    // faster (short and ragged segments).  Binary32 is the exception: its MMA takes four K-slices, hence four 8-pass
+    // MFMAs, per 16-byte load, and measures 5 % behind the classic family on the flat sum (306 against 290 us on 2 GiB)
+    // and up to 25 % behind on segmented sums (2 KiB segments 5.5 against 7.0 TB/s, 1.5 KB 4.9 against 6.7, 32 KiB 5.7
+    // against 7.1; ahead only on 16-byte aligned power-of-two segments of 64 B - 1 KiB, by 3-6 %).
+    (void)flat;
+    if (dtype == REDUX_F32) return REDUX_VARIANT_CLASSIC;
     return REDUX_VARIANT_MFMA;
 }
 

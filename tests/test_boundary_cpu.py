@@ -75,15 +75,15 @@ def test_settings():
 
 def test_resolved_variant_without_a_gpu():
     """What 'auto' resolves to: the MMA family, except the 8-bit floats (classic everywhere: their MFMAs drop bits) and
-    the flat sum of binary32 (classic: measured faster); an explicit setting wins; unknown dtypes are an error."""
+    binary32 (classic: measured faster); an explicit setting wins; unknown dtypes are an error."""
     redux.set_variant("auto")
     for dt in (redux.F16, redux.I8, redux.BF16):
         assert redux.resolved_variant(dt, segmented=False) == "mfma"
     for dt in (redux.F32, redux.F8E4M3, redux.F8E5M2):
         assert redux.resolved_variant(dt, segmented=False) == "classic"
-    for dt in (redux.F16, redux.I8, redux.BF16, redux.F32):
+    for dt in (redux.F16, redux.I8, redux.BF16):
         assert redux.resolved_variant(dt, segmented=True) == "mfma"
-    for dt in (redux.F8E4M3, redux.F8E5M2):
+    for dt in (redux.F32, redux.F8E4M3, redux.F8E5M2):
         assert redux.resolved_variant(dt, segmented=True) == "classic"
     for v in ("mfma", "classic"):
         redux.set_variant(v)

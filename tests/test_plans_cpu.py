@@ -295,8 +295,9 @@ def test_segmented_plan_defaults_on_mi355x():
     assert redux.plan_sum_segmented(1 << 20, 3, redux.F8E4M3, 0, 256).vectors == 2                    # 3 B can straddle two vectors
     assert redux.plan_sum_segmented(1 << 20, 2, redux.F16, 0, 256).vectors == 1                       # 4 B on a 4-byte boundary cannot
     assert redux.plan_sum_segmented(1 << 20, 2, redux.F16, 2, 256).vectors == 2
-    longest = redux.plan_sum_segmented(1 << 20, 252, redux.F32, 0, 256)                               # 1008 B: the longest
+    longest = redux.plan_sum_segmented(1 << 20, 504, redux.F16, 0, 256)                               # 1008 B: the longest
     assert (longest.vectors, longest.grid) == (64, 256)                                               # 63 of 64 lanes busy: one block per CU
+    assert redux.plan_sum_segmented(1 << 20, 252, redux.F32, 0, 256).grid == 512                      # binary32 runs the classic family: one block more
     assert redux.plan_sum_segmented(1 << 20, 253, redux.F32, 0, 256).kernel == redux.KERNEL_RUNS
     redux.set_param("seg_ragged", 0)
     assert redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256).kernel == redux.KERNEL_WAVE
