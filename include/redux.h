@@ -136,11 +136,11 @@ int redux_sum_static(const void *x, size_t n, int dtype, void *out, void *stream
  * The kernel is chosen from (nseg, seglen, alignment); redux_plan_sum_segmented reports the choice.
  * Segments of up to 1 KiB (aligned powers of two: 4 KiB) are read as one contiguous stream, a group of 2^k lanes
  * per segment, and the constant operands of the two MMAs become 0/1 selection matrices, so that one MMA pair yields
- * many sums; longer segments are taken a run of up to sixteen at a time by one wavefront, which streams the run as
- * one contiguous piece of memory (first MMA with a one-column selector per segment, issued twice for a load that
- * holds a segment boundary; second MMA to fold the rows of all columns at once), with a leaner form for aligned
- * segments of exactly 1, 2, 4 or 8 KiB; segments of 32 KiB and more take a whole block each; a few long segments are cut into pieces whose totals (in the workspace) a second kernel adds
- * per segment.
+ * many sums; longer segments, up to 28 KiB, are taken a run of up to sixteen at a time by one wavefront, which
+ * streams the run as one contiguous piece of memory (first MMA with a one-column selector per segment, issued twice
+ * for a load that holds a segment boundary; second MMA to fold the rows of all columns at once), with a leaner form
+ * for aligned segments of exactly 1, 2, 4 or 8 KiB; segments of 28 KiB and more take a whole block each; a few long
+ * segments are cut into pieces whose totals (in the workspace) a second kernel adds per segment.
  *
  * Reads outside x: segments that do not start or end on a 16-byte boundary are read as the 16-byte aligned vectors
  * that overlap them, so up to 15 bytes before x and after x + nseg*seglen*elemsize may be read (never written).  They
