@@ -288,7 +288,7 @@ int redux_resolved_variant(int dtype, int segmented);
  *   "seg_runs_long"     0..2^18 that kernel also takes segments of more than 32768 bytes up to this size when there are
  *                               at least eight per compute unit (default 36863: measured, one block per segment leaves
  *                               most of its second 32 KiB pass idle there; 0 = none)
- *   "seg_runs_stream"   0/1     that kernel, MMA family: 1 = every register is loaded again, with what the wavefront's next
+ *   "seg_runs_stream"   0/1     that kernel: 1 = every register is loaded again, with what the wavefront's next
  *                               iteration (of this run or of its next one) needs, right after it has been used, so the
  *                               loads stay in flight across the end of a run; 0 = load, work, fold, store, run by run
  *                               (default 1: measured 2-4 % ahead; on the same grid with the same run length the results are the same bit for bit)

@@ -46,7 +46,7 @@ struct Settings {
     long seg_runs = 1;            // use the run-of-segments kernel for segments above 1008 bytes that are not cut into pieces
     long seg_run_len = 0;         // segments per run (0 = from the shape)
     long seg_runs_max = 0;        // largest segment (bytes) that kernel takes (0 = by family: 28671 MMA rolling form, else 7999)
-    long seg_runs_stream = 1;     // run-of-segments kernel, MMA family: 1 = every register reloaded right after its use
+    long seg_runs_stream = 1;     // run-of-segments kernel: 1 = every register reloaded right after its use
     long seg_balance = 1;         // long segments are cut into more pieces when the last round of pieces would be mostly empty
     long seg_runs_long = 36863;   // it also takes segments of more than 32 KiB up to this size (0 = none)
     long seg_block_bytes = 28672; // segments of at least this many bytes take one block each (0 = never); measured: from
@@ -573,15 +573,18 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
     if (p.kernel == REDUX_KERNEL_WAVE && (runs_fit || runs_long)) {
         p.kernel = REDUX_KERNEL_RUNS;
         const bool mfma = effective_variant(S, dtype) == REDUX_VARIANT_MFMA;
-        // measured: the MMA family runs best with four loads per lane in flight; its rolling form, which keeps them in
-        // flight across the end of a run, with two blocks per compute unit (three below 1.5 KB, where the boundaries
-        // take more instructions), its plain form with three (the fold and the store at the end of a run leave gaps that
-        // other wavefronts fill); the classic family, whose lanes also convert and add, wants eight loads and more
+        // measured: the rolling form, which keeps its loads in flight across the end of a run, runs best with four loads
+        // per lane and two blocks per compute unit (three for short segments, where the boundaries take more
+        // instructions: below 1.5 KB in the MMA family, below 3 KB in the classic one); the run-by-run form of the MMA
+        // family with four loads and three blocks (the fold and the store at the end of a run leave gaps that other
+        // wavefronts fill), that of the classic family, whose lanes also convert and add, with eight loads and more
         // wavefronts the shorter the segments are
-        p.unroll = S.unroll == 0 ? (mfma ? 4 : 8) : (S.unroll <= 4 ? 4 : 8);
+        const bool rolling = S.seg_runs_stream != 0;
+        p.unroll = S.unroll == 0 ? (mfma || rolling ? 4 : 8) : (S.unroll <= 4 ? 4 : 8);
         const u64 step = 64 * (u64)p.unroll;                                    // vectors per iteration of a wavefront
         const long bpc = S.seg_blocks_per_cu ? S.seg_blocks_per_cu
-                       : mfma ? (S.seg_runs_stream && seg_bytes >= 1536 ? 2 : 3) : seg_bytes < 2560 ? 8 : 4;
+                       : rolling ? (seg_bytes >= (mfma ? 1536u : 3000u) ? 2 : 3)
+                       : mfma ? 3 : seg_bytes < 2560 ? 8 : 4;
         u64 gmax = (u64)cus * (u64)bpc;
         if (gmax > (u64)S.max_grid) gmax = (u64)S.max_grid;
         if (gmax < 1) gmax = 1;
@@ -872,6 +875,7 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
                                     else    hipLaunchKernelGGL((KERNEL<E, UU, false>), dim3(grid), dim3(kBlock), 0, st, r); } while (0)
             if (mfma && S.seg_runs_stream) { if (plan.unroll == 8) REDUX_RUNS(sum_segment_runs_mfma_stream_kernel, 8); else REDUX_RUNS(sum_segment_runs_mfma_stream_kernel, 4); }
             else if (mfma) { if (plan.unroll == 8) REDUX_RUNS(sum_segment_runs_mfma_kernel, 8); else REDUX_RUNS(sum_segment_runs_mfma_kernel, 4); }
+            else if (S.seg_runs_stream) { if (plan.unroll == 8) REDUX_RUNS(sum_segment_runs_classic_stream_kernel, 8); else REDUX_RUNS(sum_segment_runs_classic_stream_kernel, 4); }
             else      { if (plan.unroll == 8) REDUX_RUNS(sum_segment_runs_classic_kernel, 8); else REDUX_RUNS(sum_segment_runs_classic_kernel, 4); }
 #undef REDUX_RUNS
         });

@@ -283,11 +283,48 @@ __global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_kernel(RunArgs a
 // operations between a load and its use is the same on every path and the waits can be exact.  A run with a
 // non-finite D' is only noted (one bit for each of the wavefront's first 64 runs, one for all later ones together)
 // and summed again by the classic form when the stream has ended, so that no load of the stream sits behind a branch.
-template <class E, int U, bool NT>
-__global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_stream_kernel(RunArgs a)
+// What the two families do with a run's data.  add: the bytes of v (already cleared outside the segment) belong to
+// segment `col` of the run; done: segment `col` is complete; result: lane k's return value is the sum of segment k.
+template <class E>
+struct RunMma {
+    typedef typename E::Acc State;
+    static constexpr bool kCanMix = E::kCanBeNonFinite;   // a non-finite value reaches the other columns through 0 x inf
+    static __device__ __forceinline__ void init(State &st) { st = E::zero(); }
+    static __device__ __forceinline__ void add(State &st, u32x4 v, unsigned col, unsigned lane) { st = E::mma1(v, (lane & 15u) == col, st); }
+    static __device__ __forceinline__ void done(State &, unsigned, unsigned) {}
+    static __device__ __forceinline__ typename E::Out result(State &st, bool *bad)
+    {
+        const typename E::Out total = E::fold_out_wide(run_fold(st, bad));
+        st = E::zero();
+        return total;
+    }
+};
+template <class E>
+struct RunClassic {
+    struct State { typename E::Lane s, res; };            // this lane's share of the open segment; lane k: sum of segment k
+    static constexpr bool kCanMix = false;
+    static __device__ __forceinline__ void init(State &st) { st.s = 0; st.res = 0; }
+    static __device__ __forceinline__ void add(State &st, u32x4 v, unsigned, unsigned) { st.s = st.s + E::lane_sum(v); }
+    static __device__ __forceinline__ void done(State &st, unsigned col, unsigned lane)
+    {
+        const typename E::Lane t = short_butterfly(st.s, 6u);         // the same total in every lane
+        st.res = lane == col ? t : st.res;
+        st.s = 0;
+    }
+    static __device__ __forceinline__ typename E::Out result(State &st, bool *bad)
+    {
+        *bad = false;
+        const typename E::Out total = E::lane_out(st.res);
+        st.res = 0;
+        return total;
+    }
+};
+
+template <class E, class P, int U, bool NT>
+__device__ __forceinline__ void run_stream(const RunArgs &a)
 {
     typedef typename E::Out Out;
-    const unsigned lane = threadIdx.x & 63u, n = lane & 15u;
+    const unsigned lane = threadIdx.x & 63u;
     const int lane16 = 16 * (int)lane;
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     __shared__ u32x4 low[17];
@@ -315,12 +352,13 @@ __global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_stream_kernel(Ru
         return load16<NT>(it.g.base + (idx < it.g.nvec ? idx : it.g.nvec - 1u));
     };
 
-    typename E::Acc acc = E::zero();
+    typename P::State st;
+    P::init(st);
     RunCursor c;
     u64 redo = 0;                                  // bit k: run k of this wavefront must be summed again
     bool redo_later = false;                       // ... and every run from the 64th on
-    // one iteration: its U loads into the accumulator columns, each register reloaded by `refill` right after its use;
-    // at the end of a run the second MMA; the store in every pass
+    // one iteration: its U loads into the run's sums, each register reloaded by `refill` right after its use;
+    // at the end of a run the results; the store in every pass
     const auto work = [&](u32x4 *cur, const Iter &it, auto refill) {
         const RunGeometry &g = it.g;
 #pragma unroll
@@ -328,17 +366,20 @@ __global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_stream_kernel(Ru
             const unsigned p = (it.v0 + 64u * (unsigned)u) * 16u;    // first byte of this load, from base
             const u32x4 v = cur[u];
             if (p < g.total) {                                       // (the same for every lane)
-                if (c.next - p >= 1024u) {                           // no boundary in this load: one MMA, nothing cleared
-                    if (c.col < g.count) acc = E::mma1(v, n == c.col, acc);
+                if (c.next - p >= 1024u) {                           // no boundary in this load: nothing cleared
+                    if (c.col < g.count) P::add(st, v, c.col, lane);
                 } else {
                     u32x4 done = {0u, 0u, 0u, 0u};                   // bytes already handed to a segment
                     do {
                         const u32x4 front = low[bytes_in_front(c.next - p, lane16)];
-                        if (c.col < g.count) acc = E::mma1(v & front & ~done, n == c.col, acc);
+                        if (c.col < g.count) {                       // the segment in front of the boundary is complete
+                            P::add(st, v & front & ~done, c.col, lane);
+                            P::done(st, c.col, lane);
+                        }
                         done = front;
                         c.pass(g, a.seg_bytes);
                     } while (c.next - p < 1024u);
-                    if (c.col < g.count) acc = E::mma1(v & ~done, n == c.col, acc);
+                    if (c.col < g.count) P::add(st, v & ~done, c.col, lane);
                 }
             }
             refill(u);
@@ -347,17 +388,18 @@ __global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_stream_kernel(Ru
         Out total = 0;
         unsigned stores = 0u;                                        // lanes that store: none, except at the end of a run
         if (run_ends) {
+            // (a run that ends exactly where its last load ends never meets its last boundary inside a load)
+            if (c.col < g.count) P::done(st, c.col, lane);
             bool bad;
-            total = E::fold_out_wide(run_fold(acc, &bad));
-            const bool any = E::kCanBeNonFinite && __builtin_amdgcn_ballot_w64(bad) != 0;
+            total = P::result(st, &bad);
+            const bool any = P::kCanMix && __builtin_amdgcn_ballot_w64(bad) != 0;
             if (any) {
                 if (it.k < 64) redo |= 1ull << it.k;
                 else redo_later = true;
             }
             stores = any ? 0u : g.count;
-            acc = E::zero();
         }
-        if (lane < stores) ((Out *)a.out)[g.first + lane] = total;    // lanes 0 .. 15 hold columns 0 .. 15
+        if (lane < stores) ((Out *)a.out)[g.first + lane] = total;    // lanes 0 .. 15 hold the sums of segments 0 .. 15
     };
 
     Iter it;
@@ -385,11 +427,16 @@ __global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_stream_kernel(Ru
     }
     __builtin_amdgcn_sched_barrier(0);
     work(cur, it, [](int) {});
-    if (redo != 0 || redo_later) {
+    if (P::kCanMix && (redo != 0 || redo_later)) {
         __builtin_amdgcn_s_waitcnt(0);             // the first pass's stores have landed
         for (u64 k = 0; k < nruns; ++k)
             if (k < 64 ? ((redo >> k) & 1u) != 0 : redo_later) run_classic<E, U, NT>(a, geometry(k), low, lane);
     }
 }
+
+template <class E, int U, bool NT>
+__global__ void __launch_bounds__(kBlock) sum_segment_runs_mfma_stream_kernel(RunArgs a) { run_stream<E, RunMma<E>, U, NT>(a); }
+template <class E, int U, bool NT>
+__global__ void __launch_bounds__(kBlock) sum_segment_runs_classic_stream_kernel(RunArgs a) { run_stream<E, RunClassic<E>, U, NT>(a); }
 
 } // namespace redux

@@ -96,7 +96,7 @@ def test_rolling_run_kernel_keeps_its_loads_in_flight(kernels):
     # the rolling form reloads every register right after its use: inside its main loop every wait in front of a use
     # leaves the U - 1 younger loads in flight (vmcnt(U - 1), at least once per register), and a reload follows each use
     for u in (4, 8):
-        for name in pick(kernels, "sum_segment_runs_mfma_stream_kernel", "Li%dELb1E" % u):
+        for name in pick(kernels, "sum_segment_runs_mfma_stream_kernel", "Li%dELb1E" % u) + pick(kernels, "sum_segment_runs_classic_stream_kernel", "Li%dELb1E" % u):
             body = kernels[name][0]
             loop = body[body.index("Loop Header: Depth=1"):]
             first_reloads = loop[:loop.index("global_store")]            # the main loop up to the store at the end of a pass

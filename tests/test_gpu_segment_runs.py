@@ -34,7 +34,7 @@ def reset():
     yield
     redux.set_param("seg_runs_max", 0)
     redux.set_param("seg_runs_long", 36863)
-    for name, val in (("max_grid", 16384), ("seg_blocks_per_cu", 0), ("nontemporal", 1), ("seg_runs", 1), ("seg_run_len", 0), ("seg_runs_stream", 1),
+    for name, val in (("max_grid", 16384), ("seg_blocks_per_cu", 0), ("unroll", 0), ("nontemporal", 1), ("seg_runs", 1), ("seg_run_len", 0), ("seg_runs_stream", 1),
                       ("seg_block_bytes", 28672), ("seg_parts", 0), ("seg_short", 1), ("seg_tiles", 1)):
         redux.set_param(name, val)
     redux.set_variant("auto")
@@ -191,17 +191,20 @@ def test_runs_take_segments_just_above_32_kib_by_default(dev, kind, variant):
         check(got, pats, kind, nseg, seglen, TOL, (kind, seg_bytes, nseg, offset))
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("kind", KINDS)
-def test_rolling_and_plain_form_give_the_same_bits(dev, kind):
-    """The MMA family has two forms of this kernel: loads rolling across the ends of runs (the default) and run by run.
+def test_rolling_and_plain_form_give_the_same_bits(dev, kind, variant):
+    """Both families have two forms of this kernel: loads rolling across the ends of runs (the default) and run by run.
     Given the same grid and run length both issue the same MMAs on the same data in the same order, so every result must
     be the same bit for bit: small and large shapes, every run length, tiny grids.  A run with a non-finite value is summed again by the classic form in
     both, run by run (the rolling form keeps one bit for each of a wavefront's first 64 runs), so with NaNs in the data
-    and at most 64 runs per wavefront the two still agree bit for bit."""
-    redux.set_variant("mfma")
+    and at most 64 runs per wavefront the two still agree bit for bit (the classic family never mixes segments and has
+    nothing to sum again)."""
+    redux.set_variant(variant)
     es = ESIZE[kind]
     redux.set_param("seg_parts", 1)
     redux.set_param("seg_blocks_per_cu", 3)                      # the same grid, and so the same runs, for both forms
+    redux.set_param("unroll", 4)                                 # (and the same loads per iteration, which the run length is chosen by)
     for seg_bytes, nseg, offset in ((1012, 1, 0), (1012, 5, 1), (1040, 37, 3), (2000, 1000, 1), (3000, 70001, 0), (4100, 333, 5), (8200, 64, 1),
                                     (20000, 17, 2), (1016, 30000, 1), (32766, 9, 3)):
         if seg_bytes % es:
@@ -228,13 +231,14 @@ def test_rolling_and_plain_form_give_the_same_bits(dev, kind):
                 rolling = redux.sum_segmented(xd, nseg, seglen)
                 torch.cuda.synchronize()
                 a, b = plain.cpu().numpy(), rolling.cpu().numpy()
-                assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), (kind, seg_bytes, nseg, offset, with_nan, run_len, max_grid)
+                assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), (variant, kind, seg_bytes, nseg, offset, with_nan, run_len, max_grid)
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("kind", ("f16", "i8"))
-def test_plain_form_against_oracle(dev, kind):
+def test_plain_form_against_oracle(dev, kind, variant):
     """The run-by-run form is no longer what runs by default: its own pass against the oracle."""
-    redux.set_variant("mfma")
+    redux.set_variant(variant)
     redux.set_param("seg_runs_stream", 0)
     redux.set_param("seg_parts", 1)
     es = ESIZE[kind]

@@ -241,7 +241,12 @@ def test_segmented_plan_defaults_on_mi355x():
     assert (few.kernel, few.vectors, few.grid) == (redux.KERNEL_RUNS, 1, 10)                      # few segments: one per run
     redux.set_variant("classic")
     three = redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256)
-    assert (three.kernel, three.unroll) == (redux.KERNEL_RUNS, 8) and three.grid in (4 * 256, 8 * 256)
+    assert (three.kernel, three.unroll, three.grid) == (redux.KERNEL_RUNS, 4, 2 * 256)               # rolling: four loads, two blocks per CU
+    assert redux.plan_sum_segmented(65536, 1000, redux.F16, 0, 256).grid == 3 * 256                 # 2000 B: three
+    redux.set_param("seg_runs_stream", 0)
+    three = redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256)
+    assert (three.kernel, three.unroll) == (redux.KERNEL_RUNS, 8) and three.grid in (4 * 256, 8 * 256)   # run by run: eight loads, more wavefronts
+    redux.set_param("seg_runs_stream", 1)
     redux.set_variant("auto")
     redux.set_param("seg_runs_stream", 0)                                                          # the plain form wants three blocks per CU
     assert redux.plan_sum_segmented(65536, 3 * 512, redux.F16, 0, 256).grid == 768
