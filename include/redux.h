@@ -321,7 +321,7 @@ int redux_resolved_variant(int dtype, int segmented);
  *   "layout"            0..2    which part of the array a block reads: 0 = blocks interleaved over the
  *                               whole array, 1 = one contiguous share per block, 2 = one contiguous
  *                               eighth per accelerator die, interleaved among that die's blocks (default 2)
- *   "finish"            -1..4   how block partials become the result: 0/1/4 = the block that arrives last
+ *   "finish"            -1..5   how block partials become the result: 0/1/4 = the block that arrives last
  *                               sums them in the same kernel (0: acquire+release on every block's ticket,
  *                               1: release only, acquire in the last block, 4: no release fence at all -- the
  *                               partial is published by a device-scope atomic exchange whose completion the
@@ -329,7 +329,11 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               on the same stream, 3 = every block adds its total to the result atomically
  *                               (the atomic scheme of Section II, for comparison: a fill kernel clears the
  *                               result first, and floating-point results then depend on the order of arrival
- *                               in their last bits), -1 = the measured best for the input size (default -1)
+ *                               in their last bits), 5 = int8 only: every block adds its total to one 64-bit word
+ *                               with a single atomic addition that also counts the blocks (sum above bit 15,
+ *                               count below), and the block that completes the count writes the result: exact,
+ *                               independent of the order, no partials and no clearing kernel (other types: taken
+ *                               as 4), -1 = the measured best for the input: 5 for int8, else by size (default -1)
  *   "max_chain"         1..65536 loop iterations between folds of the MMA accumulators into the wide
  *                               per-wavefront total (bounds binary32 chain length).  For int8 the library lowers
  *                               it where needed so that an int32 accumulator stays below 2^31 for any input

@@ -22,6 +22,7 @@
 // The "classic" family is the tree reduction of Section III with Brent's coarsening: each lane
 // accumulates serially, then a DPP / ds_swizzle butterfly combines the 64 lanes.
 #pragma once
+#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -484,7 +485,8 @@ struct FlatArgs {
     void *out;
     unsigned max_chain; // loop iterations between folds
     int layout;         // which slabs a block takes (see slab_schedule)
-    int finish;         // 0/1/4: the last block to arrive sums the partials; 2: a second kernel does; 3: atomic additions
+    int finish;         // 0/1/4: the last block to arrive sums the partials; 2: a second kernel does; 3: atomic additions;
+                        // 5: atomic additions that count the blocks as well (integers only)
     unsigned stagger;   // start of wavefront w delayed by w x stagger x 64 cycles (long runs only)
     unsigned pause;     // every loop iteration ends with this many 64-cycle sleeps
 };
@@ -603,6 +605,28 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
         if (tid == 0)
             __hip_atomic_fetch_add((typename F::Out *)a.out, F::to_out((lds[0] + lds[1]) + (lds[2] + lds[3])), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    if (a.finish == 5) {
+        // Integer totals only (the host sees to that).  Integer addition does not care about the order, so the blocks may
+        // simply add their totals up with atomic additions, as Section II describes -- and the same addition can count
+        // them: the word holds the running sum above bit 15 and the number of blocks that have added to it below (a grid
+        // has at most 16384 blocks, and a block's total shifted left by 15 leaves the count alone, whatever its sign).
+        // What the addition returns tells the block whether it was the last one, and then old + own is the whole sum:
+        // one round trip instead of three (publish, ticket, read the partials), no partials, no second launch, and the
+        // result cannot depend on who arrived when.  |sum| stays below 2^48 for up to 2^41 int8 elements.
+        if constexpr (std::is_integral<Total>::value) {
+            if (tid == 0) {
+                const i64 block_total = (i64)((lds[0] + lds[1]) + (lds[2] + lds[3]));
+                u64 *word = (u64 *)(a.ticket + 2);                       // the eight bytes behind the ticket, on its line
+                const u64 mine = ((u64)block_total << 15) + 1u;
+                const u64 now = __hip_atomic_fetch_add(word, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+                if ((now & 0x7fffu) == gridDim.x) {
+                    *(typename F::Out *)a.out = (typename F::Out)((i64)now >> 15);
+                    (void)__hip_atomic_exchange(word, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
         return;
     }
     if (tid == 0) {

@@ -180,7 +180,7 @@ def test_flat_chain_folds_and_small_grids(dev, variant, max_chain, max_grid):
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("layout", [0, 1, 2])
-@pytest.mark.parametrize("finish", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("finish", [0, 1, 2, 3, 4, 5])
 def test_flat_layouts_and_finishes(dev, variant, layout, finish):
     redux.set_param("layout", layout)
     redux.set_param("finish", finish)
@@ -284,7 +284,7 @@ def test_every_ordered_finish_gives_the_same_bits(dev, variant):
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
-@pytest.mark.parametrize("finish", [0, 1, 4])
+@pytest.mark.parametrize("finish", [0, 1, 4, 5])
 def test_in_kernel_finish_sees_this_call_not_the_last(dev, variant, finish):
     """Back-to-back calls alternate between two different arrays: a block partial left over from the previous
     call (one that the finishing block read before this call's write had become visible) would give a wrong sum."""
@@ -303,6 +303,23 @@ def test_in_kernel_finish_sees_this_call_not_the_last(dev, variant, finish):
         torch.cuda.synchronize()
         got = outs.cpu().numpy()
         assert np.all(got[0::2] == wa) and np.all(got[1::2] == wb), (n, max_grid)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_counted_atomic_finish_at_the_extremes_of_int8(dev, variant):
+    """The int8 finish that adds block totals and counts blocks in one 64-bit word: totals of either sign, with every
+    grid size class, must leave the count in the low bits alone (and the word at zero for the next call)."""
+    redux.set_variant(variant)
+    redux.set_param("finish", 5)
+    for n, max_grid, bpc in (((1 << 24) + 3, 16384, 16), ((1 << 24) + 3, 16384, 1), ((1 << 22) + 1, 3, 1), (4097, 16384, 1), (1, 16384, 1)):
+        redux.set_param("max_grid", max_grid)
+        redux.set_param("blocks_per_cu", bpc)
+        for value in (-128, 127, -1):
+            x = torch.full((n,), value, dtype=torch.int8, device=dev)
+            outs = torch.zeros(3, dtype=torch.int64, device=dev)
+            for k in range(3):
+                redux.sum(x, out=outs[k:k + 1])
+            assert outs.cpu().tolist() == [value * n] * 3, (n, max_grid, bpc, value)
 
 
 def test_two_streams_do_not_share_a_workspace(dev):
@@ -713,7 +730,7 @@ def test_randomised_shapes_and_settings(dev):
         redux.set_param("max_grid", int(rng.choice([1, 3, 64, 16384])))
         redux.set_param("max_chain", int(rng.choice([1, 7, 256])))
         redux.set_param("layout", int(rng.integers(0, 3)))
-        redux.set_param("finish", int(rng.integers(-1, 5)))
+        redux.set_param("finish", int(rng.integers(-1, 6)))
         redux.set_param("nontemporal", int(rng.integers(0, 2)))
         off = int(rng.integers(0, 8 if is_f16 else 16))
         if kind == "seg":

@@ -44,7 +44,7 @@ def test_flat_plan_invariants(n, dtype, mis, cus, bpc, max_grid, unroll):
     nslab = p.vectors // (256 * p.unroll)
     assert 1 <= p.grid <= min(cus * bpc, max_grid, 16384)
     assert p.grid <= max(nslab, 1)
-    assert p.finish in (2, 4)
+    assert p.finish == 5 if dtype == redux.I8 else p.finish in (2, 4)
     assert 1 <= p.chain <= 256                                       # the default max_chain, possibly lowered for int8
     assert p.kernel == redux.KERNEL_FLAT
 
@@ -57,6 +57,8 @@ def test_flat_plan_defaults_on_mi355x():
     assert (c1.unroll, c1.grid, c1.finish) == (8, 64, 4)            # small: few blocks, finishes in the same kernel
     assert redux.plan_sum(1 << 26, redux.F16, 0, 256).finish == 2   # 128 MiB: all blocks arrive together, a second kernel finishes
     assert redux.plan_sum(0, redux.I8, 0, 256).grid == 1
+    for n in (1 << 20, 1 << 26, 1 << 30):                           # int8: block totals are added and counted by one atomic addition
+        assert redux.plan_sum(n, redux.I8, 0, 256).finish == 5
 
 
 @settings(max_examples=300, deadline=None)
