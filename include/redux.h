@@ -115,8 +115,8 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
  *     returns REDUX_ERR_SCRATCH and launches nothing ("max_grid" = 2048 keeps any setting inside it).  Device
  *     ordinals 0 .. 63.
  *   - The array is shared by every call on a device and keeps what the last call left in it.  Each call clears the
- *     ticket with a small fill kernel ahead of the sum (no memset node, so it can be captured); the partials need no
- *     clearing.  Calls on ONE stream are ordered by the stream and are safe back to back.  Calls that overlap on one
+ *     ticket (and, where the finish reads the partials as they arrive, marks the slots of its blocks empty) with a
+ *     small fill kernel ahead of the sum (no memset node, so it can be captured).  Calls on ONE stream are ordered by the stream and are safe back to back.  Calls that overlap on one
  *     device -- different streams, or different host threads on different streams -- race on the array and give
  *     wrong sums: use redux_sum there, which keeps one workspace per stream.
  */
@@ -321,7 +321,7 @@ int redux_resolved_variant(int dtype, int segmented);
  *   "layout"            0..2    which part of the array a block reads: 0 = blocks interleaved over the
  *                               whole array, 1 = one contiguous share per block, 2 = one contiguous
  *                               eighth per accelerator die, interleaved among that die's blocks (default 2)
- *   "finish"            -1..5   how block partials become the result: 0/1/4 = the block that arrives last
+ *   "finish"            -1..6   how block partials become the result: 0/1/4 = the block that arrives last
  *                               sums them in the same kernel (0: acquire+release on every block's ticket,
  *                               1: release only, acquire in the last block, 4: no release fence at all -- the
  *                               partial is published by a device-scope atomic exchange whose completion the
@@ -333,7 +333,11 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               with a single atomic addition that also counts the blocks (sum above bit 15,
  *                               count below), and the block that completes the count writes the result: exact,
  *                               independent of the order, no partials and no clearing kernel (other types: taken
- *                               as 4), -1 = the measured best for the input: 5 for int8, else by size (default -1)
+ *                               as 4), 6 = floating point only: as 4, but no block waits for its partial to have
+ *                               arrived before it draws its ticket; the partials go to slots that read empty
+ *                               between launches, and the last block reads each slot until it is filled, then
+ *                               empties it again (grids above 2048 blocks and int8: taken as 4),
+ *                               -1 = the measured best for the input: 5 for int8, else 6 or 2 by size (default -1)
  *   "max_chain"         1..65536 loop iterations between folds of the MMA accumulators into the wide
  *                               per-wavefront total (bounds binary32 chain length).  For int8 the library lowers
  *                               it where needed so that an int32 accumulator stays below 2^31 for any input

@@ -84,9 +84,12 @@ int hip_fail(hipError_t e, int status = REDUX_ERR_HIP)
 struct Workspace {
     u64 *partials = nullptr;    // kMaxGrid slots
     unsigned *ticket = nullptr; // behind the partials, on its own 256-byte line
+    u64 *slots = nullptr;       // behind the ticket: kWorkspaceSlots slots that read empty between launches (finish 6)
 };
+constexpr unsigned kWorkspaceSlots = 2048;
 constexpr size_t kTicketOffset = (size_t)kMaxGrid * sizeof(u64);
-constexpr size_t kWorkspaceBytes = kTicketOffset + 256;
+constexpr size_t kSlotsOffset = kTicketOffset + 256;
+constexpr size_t kWorkspaceBytes = kSlotsOffset + (size_t)kWorkspaceSlots * sizeof(u64);
 
 std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
 
@@ -124,7 +127,8 @@ int get_workspace(int dev, hipStream_t st, Workspace *out)
         w.ticket = (unsigned *)((char *)p + kTicketOffset);
         // the ticket must read zero before the first launch; a fill kernel on the caller's
         // stream keeps the ordering without a device-wide synchronisation
-        hipLaunchKernelGGL(fill_zero_words_kernel, dim3(1), dim3(64), 0, st, w.ticket, 64u);
+        w.slots = (u64 *)((char *)p + kSlotsOffset);
+        hipLaunchKernelGGL(empty_slots_kernel, dim3(1), dim3(256), 0, st, w.slots, kWorkspaceSlots, w.ticket, 64u);
         e = hipGetLastError();
         if (e != hipSuccess) { (void)hipFree(p); return hip_fail(e); }
         it = g_ws.emplace(key, w).first;
@@ -357,7 +361,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "lit_blocks_per_cu")) { *lo = 0; *hi = 16; return &g_set.lit_blocks_per_cu; }
     if (!std::strcmp(name, "layout")) { *lo = 0; *hi = 2; return &g_set.layout; }
     if (!std::strcmp(name, "pause")) { *lo = -1; *hi = 64; return &g_set.pause; }
-    if (!std::strcmp(name, "finish")) { *lo = -1; *hi = 5; return &g_set.finish; }
+    if (!std::strcmp(name, "finish")) { *lo = -1; *hi = 6; return &g_set.finish; }
     return nullptr;
 }
 
@@ -410,6 +414,10 @@ FlatPlan plan_flat(const Settings &S, u64 nvec, int cus, int dtype)
     // Not for the other types (their sums depend on the order), nor beyond 2^40 elements (the sum's field has 49 bits).
     if (dtype == REDUX_I8 && nvec <= ((u64)1 << 36) && (S.finish < 0 || S.finish == 5)) p.finish = 5;
     else if (p.finish == 5) p.finish = 4;
+    // The other types: where the same kernel finishes, nobody waits for its partial to arrive but the last block
+    // (finish 6), as long as the grid fits the slots kept empty for that.
+    if (dtype != REDUX_I8 && p.grid <= kWorkspaceSlots && ((S.finish < 0 && p.finish == 4) || S.finish == 6)) p.finish = 6;
+    else if (p.finish == 6) p.finish = 4;
     const bool mfma = effective_variant(S, dtype, true) == REDUX_VARIANT_MFMA;
     p.chain = chain_length(S, dtype, mfma, p.unroll, 4);
     // Measured on 0.5 - 4 GiB of binary16, bfloat16 and int8: a wavefront of the MMA family that sleeps about 500 cycles
@@ -677,6 +685,7 @@ static int launch_sum(const Settings &S, int cus, const Workspace &ws, bool clea
     a.run = es == 4 ? make_run<4>(x, n) : es == 2 ? make_run<2>(x, n) : make_run<1>(x, n);
     a.partials = ws.partials;
     a.ticket = ws.ticket;
+    a.slots = ws.slots;
     a.out = out;
     a.layout = (int)S.layout;
     a.stagger = (unsigned)S.stagger;
@@ -697,7 +706,8 @@ static int launch_sum(const Settings &S, int cus, const Workspace &ws, bool clea
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
     } else if (clear_ticket && a.finish != 2) {
-        hipLaunchKernelGGL(fill_zero_words_kernel, dim3(1), dim3(64), 0, st, a.ticket, 4u);   // the ticket and the counted sum behind it
+        // the ticket and the counted sum behind it; the slots of the blocks to come
+        hipLaunchKernelGGL(empty_slots_kernel, dim3(1), dim3(256), 0, st, a.slots, a.finish == 6 ? grid : 0u, a.ticket, 4u);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
     }
@@ -783,13 +793,15 @@ int redux_sum_static(const void *x, size_t n, int dtype, void *out, void *stream
         }
         ws.partials = (u64 *)g_scratch_ptr[dev];
         ws.ticket = (unsigned *)((char *)g_scratch_ptr[dev] + kScratchTicketOffset);
+        ws.slots = ws.partials;             // marked empty by every call that uses them
     }
     // The launch writes one partial per block.  More blocks than the array has slots can only be asked for through
     // "blocks_per_cu" / "max_grid" on a device with many compute units; such a call is refused, never truncated.
     const Run run = es == 4 ? make_run<4>(x, n) : es == 2 ? make_run<2>(x, n) : make_run<1>(x, n);
     if (plan_flat(S, run.nvec, cus, dtype).grid > (unsigned)kScratchSlots) return REDUX_ERR_SCRATCH;
-    // the array keeps what the last call left in it: the ticket is cleared by a fill kernel ahead of the sum (the
-    // partials need no clearing, every slot that is read has been written by this call's blocks)
+    // the array keeps what the last call left in it: a fill kernel ahead of the sum clears the ticket and, for the finish
+    // that reads partials as they arrive, marks this call's slots empty (the other finishes only read what this call's
+    // blocks have written)
     return launch_sum(S, cus, ws, true, x, n, es, dtype, out, st);
 }
 

@@ -437,10 +437,36 @@ __device__ __forceinline__ T load_partial(const u64 *slot)
     return __builtin_bit_cast(T, __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 }
 
+// A slot that no block has written to since it was last read holds this pattern: a NaN that no sum can produce (a
+// binary64 total comes from binary32 values, whose low 29 bits are zero, or is the default NaN), and which
+// publish_to_slot replaces all the same.
+constexpr u64 kEmptySlot = ~(u64)0;
+constexpr unsigned kSlotSpins = 1u << 22;   // re-reads before a slot is given up (never reached: see take_slot)
+
+template <class T>
+__device__ __forceinline__ void publish_to_slot(u64 *slot, T v)
+{
+    u64 bits = __builtin_bit_cast(u64, v);
+    if (bits == kEmptySlot) bits = 0x7ff8000000000000ull;
+    (void)__hip_atomic_exchange(slot, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // no value comes back: nothing waits
+}
+// The value a block has published to the slot, which is then marked empty again for the next launch.  The caller holds
+// the last ticket, so every block's exchange has been issued, ahead of that block's ticket, and completes without
+// anybody's help; until it has, the slot still reads empty and is read again.
+template <class T>
+__device__ __forceinline__ T take_slot(u64 *slot)
+{
+    u64 bits = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (unsigned spins = 0; bits == kEmptySlot && spins < kSlotSpins; ++spins)
+        bits = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    (void)__hip_atomic_exchange(slot, kEmptySlot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_bit_cast(T, bits);
+}
+
 // Sum of the grid's partials in a fixed order, by all threads of the calling block.
-// Returns the total in thread 0.
-template <class F>
-__device__ __forceinline__ typename F::Total sum_partials(const u64 *partials, unsigned count,
+// Returns the total in thread 0.  kSlots: the partials are slots (publish_to_slot), taken as they arrive.
+template <class F, bool kSlots = false>
+__device__ __forceinline__ typename F::Total sum_partials(u64 *partials, unsigned count,
                                                           typename F::Total *lds /* kBlock entries */)
 {
     typedef typename F::Total Total;
@@ -453,7 +479,8 @@ __device__ __forceinline__ typename F::Total sum_partials(const u64 *partials, u
         if (tid < 64) {
             f64x4 d = {0., 0., 0., 0.};
             for (unsigned i0 = 0; i0 < count; i0 += 64) {
-                double a = (i0 + tid < count) ? load_partial<double>(partials + i0 + tid) : 0.0;
+                double a = 0.0;
+                if (i0 + tid < count) a = kSlots ? take_slot<double>(partials + i0 + tid) : load_partial<double>(partials + i0 + tid);
                 d = __builtin_amdgcn_mfma_f64_16x16x4f64(a, 1.0, d, 0, 0, 0);
             }
             f64x4 dp = {0., 0., 0., 0.};
@@ -464,7 +491,7 @@ __device__ __forceinline__ typename F::Total sum_partials(const u64 *partials, u
         return total;
     } else {
         Total t = 0;
-        for (unsigned i = tid; i < count; i += kBlock) t += load_partial<Total>(partials + i);
+        for (unsigned i = tid; i < count; i += kBlock) t += kSlots ? take_slot<Total>(partials + i) : load_partial<Total>(partials + i);
         lds[tid] = t;
         __syncthreads();
         for (unsigned off = kBlock / 2; off > 0; off >>= 1) {
@@ -482,11 +509,13 @@ struct FlatArgs {
     Run run;
     u64 *partials;      // kMaxGrid slots
     unsigned *ticket;   // zero before the launch; the finishing block resets it
+    u64 *slots;         // finish 6: one per block, all empty (kEmptySlot) before the launch; the finishing block empties them
     void *out;
     unsigned max_chain; // loop iterations between folds
     int layout;         // which slabs a block takes (see slab_schedule)
     int finish;         // 0/1/4: the last block to arrive sums the partials; 2: a second kernel does; 3: atomic additions;
-                        // 5: atomic additions that count the blocks as well (integers only)
+                        // 5: atomic additions that count the blocks as well (integers only); 6: as 4, but nobody waits
+                        // for its partial to arrive: the last block does, slot by slot (floating point only)
     unsigned stagger;   // start of wavefront w delayed by w x stagger x 64 cycles (long runs only)
     unsigned pause;     // every loop iteration ends with this many 64-cycle sleeps
 };
@@ -629,6 +658,27 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
         }
         return;
     }
+    if (a.finish == 6) {
+        // As finish 4 below, one round trip shorter: the block sends its partial off (an atomic exchange whose old value
+        // nobody needs) and draws its ticket at once.  The last ticket then says that every partial is on its way, not
+        // that it has arrived, so the slots start out empty and the finishing block reads each until it is not.
+        if constexpr (!std::is_integral<Total>::value) {
+            if (tid == 0) {
+                publish_to_slot(a.slots + blockIdx.x, (lds[0] + lds[1]) + (lds[2] + lds[3]));
+                const unsigned t = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                is_last = (t == gridDim.x - 1) ? 1u : 0u;
+            }
+            __syncthreads();
+            if (is_last) {
+                Total total = sum_partials<F, true>(a.slots, gridDim.x, lds);
+                if (tid == 0) {
+                    *(typename F::Out *)a.out = F::to_out(total);
+                    (void)__hip_atomic_exchange(a.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+        return;
+    }
     if (tid == 0) {
         Total block_total = ((lds[0] + lds[1]) + (lds[2] + lds[3]));
         // The partial must be visible device-wide before the ticket moves.  The block that draws the
@@ -668,7 +718,7 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
 
 // Second kernel of the two-kernel finish: one block sums the partials in the same fixed order.
 template <class F>
-__global__ void __launch_bounds__(kBlock) finish_kernel(const u64 *partials, unsigned count, void *out)
+__global__ void __launch_bounds__(kBlock) finish_kernel(u64 *partials, unsigned count, void *out)
 {
     typedef typename F::Total Total;
     __shared__ Total lds[kBlock];
@@ -917,7 +967,7 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
 
 // One block per segment adds that segment's piece totals in a fixed order.
 template <class F>
-__global__ void __launch_bounds__(kBlock) finish_segments_kernel(const u64 *partials, unsigned parts, void *out)
+__global__ void __launch_bounds__(kBlock) finish_segments_kernel(u64 *partials, unsigned parts, void *out)
 {
     typedef typename F::Total Total;
     __shared__ Total lds[kBlock];
@@ -1094,6 +1144,13 @@ __global__ void fill_zero_words_kernel(unsigned *p, unsigned count)
 {
     unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) p[i] = 0u;
+}
+
+// `count` slots marked empty, and the first `words` words at `zero` cleared, by one block
+__global__ void empty_slots_kernel(u64 *slots, unsigned count, unsigned *zero, unsigned words)
+{
+    for (unsigned i = threadIdx.x; i < count; i += blockDim.x) slots[i] = kEmptySlot;
+    if (threadIdx.x < words) zero[threadIdx.x] = 0u;
 }
 
 // Plain 16-byte-per-lane copy of `nvec` vectors: a kernel of exactly known traffic, used to

@@ -180,7 +180,7 @@ def test_flat_chain_folds_and_small_grids(dev, variant, max_chain, max_grid):
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("layout", [0, 1, 2])
-@pytest.mark.parametrize("finish", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("finish", [0, 1, 2, 3, 4, 5, 6])
 def test_flat_layouts_and_finishes(dev, variant, layout, finish):
     redux.set_param("layout", layout)
     redux.set_param("finish", finish)
@@ -271,7 +271,7 @@ def test_every_ordered_finish_gives_the_same_bits(dev, variant):
     n = (1 << 24) + 12345
     x = to_dev(workloads.normal_f16(5, n), dev)
     bits = {}
-    for finish in (2, 1, 4):
+    for finish in (2, 1, 4, 6):
         redux.set_param("finish", finish)
         outs = torch.empty(100, dtype=torch.float32, device=dev)
         for k in range(100):
@@ -280,7 +280,7 @@ def test_every_ordered_finish_gives_the_same_bits(dev, variant):
         got = outs.cpu().numpy().view(np.uint32)
         assert np.all(got == got[0]), finish
         bits[finish] = int(got[0])
-    assert bits[1] == bits[2] == bits[4], bits
+    assert bits[1] == bits[2] == bits[4] == bits[6], bits
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -303,6 +303,36 @@ def test_in_kernel_finish_sees_this_call_not_the_last(dev, variant, finish):
         torch.cuda.synchronize()
         got = outs.cpu().numpy()
         assert np.all(got[0::2] == wa) and np.all(got[1::2] == wb), (n, max_grid)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_slots_finish_sees_this_call_not_the_last(dev, variant):
+    """The finish whose last block takes the partials from slots as they arrive (floating point): calls alternating
+    between two arrays, and between grids of different sizes, must give the bits of the two-kernel finish every time --
+    a slot left filled by the call before, or one read before it was filled, would show."""
+    redux.set_variant(variant)
+    for n, max_grid, bpc in (((1 << 23) + 77, 16384, 1), ((1 << 23) + 77, 2048, 16), ((1 << 20) + 3, 33, 1), (5000, 16384, 1)):
+        redux.set_param("max_grid", max_grid)
+        redux.set_param("blocks_per_cu", bpc)
+        a, b = workloads.normal_f16(73, n), workloads.normal_f16(74, n // 3)
+        xa, xb = to_dev(a, dev), to_dev(b, dev)
+        redux.set_param("finish", 2)
+        fa, fb = gpu_sum(xa, variant), gpu_sum(xb, variant)
+        check_f16(fa, a)
+        check_f16(fb, b)
+        want = [np.float32(fa).view(np.uint32), np.float32(fb).view(np.uint32)]
+        redux.set_param("finish", 6)
+        assert redux.plan_sum(n, redux.F16, xa.data_ptr(), 256).finish == 6
+        outs = torch.zeros(200, dtype=torch.float32, device=dev)
+        for k in range(200):
+            redux.sum(xa if k % 2 == 0 else xb, out=outs[k:k + 1])
+        torch.cuda.synchronize()
+        got = outs.cpu().numpy().view(np.uint32)
+        assert np.all(got[0::2] == want[0]) and np.all(got[1::2] == want[1]), (n, max_grid)
+    # a grid beyond the slots falls back to the finish that waits
+    redux.set_param("max_grid", 16384)
+    redux.set_param("blocks_per_cu", 16)
+    assert redux.plan_sum(1 << 26, redux.F16, 0, 256).finish == 4
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -730,7 +760,7 @@ def test_randomised_shapes_and_settings(dev):
         redux.set_param("max_grid", int(rng.choice([1, 3, 64, 16384])))
         redux.set_param("max_chain", int(rng.choice([1, 7, 256])))
         redux.set_param("layout", int(rng.integers(0, 3)))
-        redux.set_param("finish", int(rng.integers(-1, 6)))
+        redux.set_param("finish", int(rng.integers(-1, 7)))
         redux.set_param("nontemporal", int(rng.integers(0, 2)))
         off = int(rng.integers(0, 8 if is_f16 else 16))
         if kind == "seg":
