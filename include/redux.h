@@ -21,7 +21,7 @@
  *   - All argument checks happen before the first HIP call, so the error
  *     returns for bad arguments can be exercised on a machine without a GPU.
  *   - The library owns one small workspace (block partials + a ticket
- *     counter, < 128 KiB) per (device, stream); it is created by the first
+ *     counter, 144 KiB) per (device, stream); it is created by the first
  *     call on that stream (one hipMalloc, so not during stream capture) and
  *     released by redux_shutdown().  Two calls on the same stream are ordered
  *     by the stream; calls on different streams use different workspaces, and host threads
