@@ -400,14 +400,14 @@ FlatPlan plan_flat(const Settings &S, u64 nvec, int cus, int dtype)
     }
     const u64 nslab = nvec / ((u64)kBlock * p.unroll);
     p.grid = (unsigned)(nslab < 1 ? 1 : (nslab < gmax ? nslab : gmax));
-    // Measured (us per whole call; 64 / 128 / 256 blocks at 2 / 4 / 8 MiB): finishing inside the kernel, every block
-    // publishing its partial with an atomic exchange and drawing a ticket (finish 4), takes 4.7 / 5.9 / 8.2 and a second
-    // one-block kernel (finish 2) 6.3 / 6.7 / 6.7: up to 4 MiB the same kernel finishes.  From 8 to 128 MiB all 256
-    // blocks arrive within a microsecond and their 512 read-modify-writes queue up (9.5 against 7.1 at 16 MiB, 24.5
-    // against 22.7 at 128 MiB), so the second kernel finishes.  From 256 MiB on the arrivals are spread out and both
-    // cost the same (40.3, 76.3, 148.0, 291.5 at 256 MiB ... 2 GiB): one kernel per call it is.
+    // Measured (us per whole call, back to back; 64 / 128 / 256 blocks at 2 / 4 / 8 MiB): finishing inside the kernel, every
+    // block sending its partial off and drawing a ticket (finish 6), takes 4.4 / 5.3 / 6.8 and a second one-block kernel
+    // (finish 2) 7.1 / 7.1 / 7.1: up to 8 MiB the same kernel finishes.  From 16 to 128 MiB all 256 blocks arrive within
+    // a microsecond and their read-modify-writes queue up (7.8 against 7.0 at 16 MiB, 22.9 against 22.5 at 128 MiB), so
+    // the second kernel finishes.  From 256 MiB on the arrivals are spread out and the one kernel is ahead again
+    // (39.1 / 74.2 / 144.5 / 288.3 against 40.0 / 74.8 / 145.2 / 288.9 at 256 MiB ... 2 GiB): one kernel per call it is.
     p.finish = (int)S.finish;
-    if (p.finish < 0) p.finish = (nvec <= ((u64)4 << 20) / 16 || nvec >= ((u64)256 << 20) / 16) ? 4 : 2;
+    if (p.finish < 0) p.finish = (nvec <= ((u64)8 << 20) / 16 || nvec >= ((u64)256 << 20) / 16) ? 4 : 2;
     // int8: the totals are integers, so one atomic addition per block can both add them up and count the blocks (finish
     // 5): one round trip at the end of the kernel instead of three.  Measured, us per call, against the better of
     // finish 2 and 4: 3.96 / 5.5 at 1 MiB, 6.45 / 6.6 at 8 MiB, 22.6 / 23.0 at 128 MiB, 144.0 / 145.7 at 1 GiB.

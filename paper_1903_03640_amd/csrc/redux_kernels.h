@@ -475,14 +475,24 @@ __device__ __forceinline__ typename F::Total sum_partials(u64 *partials, unsigne
         // The next level of the paper's hierarchy, in binary64, by one wavefront:
         // first MMA  D <- A x 1 + D with A = 64 partials (16 x 4), chained over all partials;
         // second MMA D' <- 1 x D.
+        // Every thread of the block fetches one partial, so 256 of them cost one round trip to where they live, not
+        // four in a row; the first wavefront takes them from shared memory in the same order as it would have loaded them.
         Total total = 0;
-        if (tid < 64) {
-            f64x4 d = {0., 0., 0., 0.};
-            for (unsigned i0 = 0; i0 < count; i0 += 64) {
-                double a = 0.0;
-                if (i0 + tid < count) a = kSlots ? take_slot<double>(partials + i0 + tid) : load_partial<double>(partials + i0 + tid);
-                d = __builtin_amdgcn_mfma_f64_16x16x4f64(a, 1.0, d, 0, 0, 0);
+        const bool first_wave = __builtin_amdgcn_readfirstlane(tid >> 6) == 0;   // scalar: matrix instructions ignore the lane mask
+        f64x4 d = {0., 0., 0., 0.};
+        for (unsigned base = 0; base < count; base += kBlock) {
+            double a = 0.0;
+            if (base + tid < count) a = kSlots ? take_slot<double>(partials + base + tid) : load_partial<double>(partials + base + tid);
+            if (base) __syncthreads();          // the round before has been read
+            lds[tid] = a;
+            __syncthreads();
+            if (first_wave) {
+                const unsigned left = count - base;
+                const unsigned chunks = left >= kBlock ? kBlock / 64 : (left + 63) / 64;
+                for (unsigned j = 0; j < chunks; ++j) d = __builtin_amdgcn_mfma_f64_16x16x4f64(lds[j * 64 + tid], 1.0, d, 0, 0, 0);
             }
+        }
+        if (first_wave) {
             f64x4 dp = {0., 0., 0., 0.};
 #pragma unroll
             for (int r = 0; r < 4; ++r) dp = __builtin_amdgcn_mfma_f64_16x16x4f64(1.0, d[r], dp, 0, 0, 0);
