@@ -48,16 +48,16 @@ HBM_PEAK_GBPS = 8000.0
 # FETCH_SIZE + WRITE_SIZE, scaled by what the same counters read for a plain copy of known size, for the HBM bytes).
 # (workload, family actually run): (HBM bytes per launch, kernel, average kernel duration in us, summary).  Absent = not profiled.
 PROFILED = {
-    ('C1', 'classic'): (2250927, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 4.62, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C1', 'mfma'): (2240687, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 4.20, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C2', 'classic'): (134375986, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 19.90, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C2', 'mfma'): (134366642, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 19.09, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C3', 'classic'): (2147631219, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 289.90, 'profiles/redux_sum_f16_C3.md'),
-    ('C3', 'mfma'): (2147620968, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 290.45, 'profiles/redux_sum_f16_C3.md'),
-    ('C4', 'classic'): (1073845961, 'sum_flat_kernel<I8Classic, 8, true>', 145.55, 'profiles/redux_sum_i8_C4.md'),
-    ('C4', 'mfma'): (1073855208, 'sum_flat_kernel<I8MfmaT<4>, 8, true>', 144.12, 'profiles/redux_sum_i8_C4.md'),
-    ('C5', 'classic'): (537420434, 'sum_segments_tiles_kernel<FloatClassic<0>, 8, true, 0>', 74.61, 'profiles/redux_sum_segmented_f16_C5.md'),
-    ('C5', 'mfma'): (537417266, 'sum_segments_tiles_kernel<FloatMfmaT<0, 1>, 8, true, 1>', 74.56, 'profiles/redux_sum_segmented_f16_C5.md'),
+    ('C1', 'classic'): (2245808, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 4.73, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C1', 'mfma'): (2227376, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 4.41, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C2', 'classic'): (134372136, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 19.85, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C2', 'mfma'): (134353576, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 19.42, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C3', 'classic'): (2147626971, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 289.54, 'profiles/redux_sum_f16_C3.md'),
+    ('C3', 'mfma'): (2147611953, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 289.68, 'profiles/redux_sum_f16_C3.md'),
+    ('C4', 'classic'): (1073855287, 'sum_flat_kernel<I8Classic, 8, true>', 145.61, 'profiles/redux_sum_i8_C4.md'),
+    ('C4', 'mfma'): (1073861442, 'sum_flat_kernel<I8MfmaT<4>, 8, true>', 144.19, 'profiles/redux_sum_i8_C4.md'),
+    ('C5', 'classic'): (537420431, 'sum_segments_tiles_kernel<FloatClassic<0>, 8, true, 0>', 74.77, 'profiles/redux_sum_segmented_f16_C5.md'),
+    ('C5', 'mfma'): (537411143, 'sum_segments_tiles_kernel<FloatMfmaT<0, 1>, 8, true, 1>', 74.50, 'profiles/redux_sum_segmented_f16_C5.md'),
 }
 
 
