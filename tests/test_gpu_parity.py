@@ -268,19 +268,19 @@ def test_every_ordered_finish_gives_the_same_bits(dev, variant):
     """The block partials are the same whoever adds them up, and every finish but the atomic additions adds them in
     block order: the second kernel and the last block to arrive must agree bit for bit, call after call."""
     redux.set_variant(variant)
-    n = (1 << 24) + 12345
-    x = to_dev(workloads.normal_f16(5, n), dev)
-    bits = {}
-    for finish in (2, 1, 4, 6):
-        redux.set_param("finish", finish)
-        outs = torch.empty(100, dtype=torch.float32, device=dev)
-        for k in range(100):
-            redux.sum(x, out=outs[k:k + 1])
-        torch.cuda.synchronize()
-        got = outs.cpu().numpy().view(np.uint32)
-        assert np.all(got == got[0]), finish
-        bits[finish] = int(got[0])
-    assert bits[1] == bits[2] == bits[4] == bits[6], bits
+    for n in ((1 << 24) + 12345, 1000):                      # 256 blocks; a single block, which writes its total itself
+        x = to_dev(workloads.normal_f16(5, n), dev)
+        bits = {}
+        for finish in (2, 1, 4, 6):
+            redux.set_param("finish", finish)
+            outs = torch.empty(100, dtype=torch.float32, device=dev)
+            for k in range(100):
+                redux.sum(x, out=outs[k:k + 1])
+            torch.cuda.synchronize()
+            got = outs.cpu().numpy().view(np.uint32)
+            assert np.all(got == got[0]), finish
+            bits[finish] = int(got[0])
+        assert bits[1] == bits[2] == bits[4] == bits[6], (n, bits)
 
 
 @pytest.mark.parametrize("variant", VARIANTS)

@@ -59,6 +59,9 @@ def test_flat_plan_defaults_on_mi355x():
     assert redux.plan_sum(0, redux.I8, 0, 256).grid == 1
     for n in (1 << 20, 1 << 26, 1 << 30):                           # int8: block totals are added and counted by one atomic addition
         assert redux.plan_sum(n, redux.I8, 0, 256).finish == 5
+    assert redux.plan_sum((1 << 40) + 4096, redux.I8, 0, 256).finish == 4   # beyond the 49 bits the counted word gives the sum
+    assert redux.plan_sum(1 << 23, redux.F16, 0, 256).finish == 2             # 16 MiB: the smallest size that takes the second kernel
+    assert redux.plan_sum(1 << 22, redux.F16, 0, 256).finish == 6
 
 
 @settings(max_examples=300, deadline=None)
