@@ -441,7 +441,7 @@ __device__ __forceinline__ T load_partial(const u64 *slot)
 // binary64 total comes from binary32 values, whose low 29 bits are zero, or is the default NaN), and which
 // publish_to_slot replaces all the same.
 constexpr u64 kEmptySlot = ~(u64)0;
-constexpr unsigned kSlotSpins = 1u << 22;   // re-reads before a slot is given up (never reached: see take_slot)
+constexpr unsigned kSlotSpins = 1u << 22;   // re-reads before a slot is given up (never reached: see fetch_partials)
 
 template <class T>
 __device__ __forceinline__ void publish_to_slot(u64 *slot, T v)
@@ -450,17 +450,29 @@ __device__ __forceinline__ void publish_to_slot(u64 *slot, T v)
     if (bits == kEmptySlot) bits = 0x7ff8000000000000ull;
     (void)__hip_atomic_exchange(slot, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // no value comes back: nothing waits
 }
-// The value a block has published to the slot, which is then marked empty again for the next launch.  The caller holds
-// the last ticket, so every block's exchange has been issued, ahead of that block's ticket, and completes without
-// anybody's help; until it has, the slot still reads empty and is read again.
-template <class T>
-__device__ __forceinline__ T take_slot(u64 *slot)
+// The values that blocks have published to slots base + r x 256 + thread (r = 0 .. R-1; zeros past `count`), fetched in
+// one go.  kSlots: the slots are then marked empty again for the next launch.  The caller holds the last ticket, so
+// every exchange that fills a slot has been issued, ahead of its block's ticket, and completes without anybody's help;
+// until it has, the slot still reads empty and is read again.
+template <class T, bool kSlots, unsigned R>
+__device__ __forceinline__ void fetch_partials(u64 *partials, unsigned base, unsigned count, T (&v)[R])
 {
-    u64 bits = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (unsigned spins = 0; bits == kEmptySlot && spins < kSlotSpins; ++spins)
-        bits = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    (void)__hip_atomic_exchange(slot, kEmptySlot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return __builtin_bit_cast(T, bits);
+    u64 bits[R];
+#pragma unroll
+    for (unsigned r = 0; r < R; ++r) {
+        const unsigned i = base + r * kBlock + threadIdx.x;
+        bits[r] = i < count ? __hip_atomic_load(partials + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : (u64)0;
+    }
+#pragma unroll
+    for (unsigned r = 0; r < R; ++r) {
+        const unsigned i = base + r * kBlock + threadIdx.x;
+        if (kSlots && i < count) {
+            for (unsigned spins = 0; bits[r] == kEmptySlot && spins < kSlotSpins; ++spins)
+                bits[r] = __hip_atomic_load(partials + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            (void)__hip_atomic_exchange(partials + i, kEmptySlot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        v[r] = __builtin_bit_cast(T, bits[r]);
+    }
 }
 
 // Sum of the grid's partials in a fixed order, by all threads of the calling block.
@@ -471,25 +483,31 @@ __device__ __forceinline__ typename F::Total sum_partials(u64 *partials, unsigne
 {
     typedef typename F::Total Total;
     const unsigned tid = threadIdx.x;
+    constexpr unsigned R = 8;                   // partials per thread and trip to where they live
     if (F::kMfmaFinish) {
         // The next level of the paper's hierarchy, in binary64, by one wavefront:
         // first MMA  D <- A x 1 + D with A = 64 partials (16 x 4), chained over all partials;
         // second MMA D' <- 1 x D.
-        // Every thread of the block fetches one partial, so 256 of them cost one round trip to where they live, not
-        // four in a row; the first wavefront takes them from shared memory in the same order as it would have loaded them.
+        // Every thread of the block fetches partials, so 2048 of them cost one round trip to where they live; the first
+        // wavefront takes them from shared memory, 256 at a time, in index order.
         Total total = 0;
         const bool first_wave = __builtin_amdgcn_readfirstlane(tid >> 6) == 0;   // scalar: matrix instructions ignore the lane mask
         f64x4 d = {0., 0., 0., 0.};
-        for (unsigned base = 0; base < count; base += kBlock) {
-            double a = 0.0;
-            if (base + tid < count) a = kSlots ? take_slot<double>(partials + base + tid) : load_partial<double>(partials + base + tid);
-            if (base) __syncthreads();          // the round before has been read
-            lds[tid] = a;
-            __syncthreads();
-            if (first_wave) {
-                const unsigned left = count - base;
-                const unsigned chunks = left >= kBlock ? kBlock / 64 : (left + 63) / 64;
-                for (unsigned j = 0; j < chunks; ++j) d = __builtin_amdgcn_mfma_f64_16x16x4f64(lds[j * 64 + tid], 1.0, d, 0, 0, 0);
+        for (unsigned base = 0; base < count; base += kBlock * R) {
+            double a[R];
+            fetch_partials<double, kSlots, R>(partials, base, count, a);
+#pragma unroll
+            for (unsigned r = 0; r < R; ++r) {
+                const unsigned from = base + r * kBlock;
+                if (from >= count) break;
+                if (from) __syncthreads();          // the 256 before have been read
+                lds[tid] = a[r];
+                __syncthreads();
+                if (first_wave) {
+                    const unsigned left = count - from;
+                    const unsigned chunks = left >= kBlock ? kBlock / 64 : (left + 63) / 64;
+                    for (unsigned j = 0; j < chunks; ++j) d = __builtin_amdgcn_mfma_f64_16x16x4f64(lds[j * 64 + tid], 1.0, d, 0, 0, 0);
+                }
             }
         }
         if (first_wave) {
@@ -501,7 +519,12 @@ __device__ __forceinline__ typename F::Total sum_partials(u64 *partials, unsigne
         return total;
     } else {
         Total t = 0;
-        for (unsigned i = tid; i < count; i += kBlock) t += kSlots ? take_slot<Total>(partials + i) : load_partial<Total>(partials + i);
+        for (unsigned base = 0; base < count; base += kBlock * R) {
+            Total a[R];
+            fetch_partials<Total, kSlots, R>(partials, base, count, a);
+#pragma unroll
+            for (unsigned r = 0; r < R; ++r) t += a[r];
+        }
         lds[tid] = t;
         __syncthreads();
         for (unsigned off = kBlock / 2; off > 0; off >>= 1) {
