@@ -20,8 +20,8 @@
  *     library does not).  Outputs are written only by kernels.
  *   - All argument checks happen before the first HIP call, so the error
  *     returns for bad arguments can be exercised on a machine without a GPU.
- *   - The library owns one small workspace (block partials + a ticket
- *     counter, 144 KiB) per (device, stream); it is created by the first
+ *   - The library owns one small workspace (block partials, slots, ticket
+ *     counters: 320 KiB) per (device, stream); it is created by the first
  *     call on that stream (one hipMalloc, so not during stream capture) and
  *     released by redux_shutdown().  Two calls on the same stream are ordered
  *     by the stream; calls on different streams use different workspaces, and host threads
@@ -208,7 +208,7 @@ typedef enum {
     REDUX_KERNEL_TILES  = 4, /* redux_sum_segmented, segments of exactly 1, 2, 4 or 8 KiB: one wavefront per
                                 segment with the next segment's loads issued ahead */
     REDUX_KERNEL_BLOCK  = 5, /* redux_sum_segmented, long segments: one block per segment or per piece of one
-                                (parts > 1: a per-segment finish kernel follows) */
+                                (parts > 1: the piece totals are added per segment, see "seg_finish") */
     REDUX_KERNEL_SHORT  = 6, /* redux_sum_segmented, 16-byte aligned segments of 16, 32, ... 1024 bytes (MMA family, except
                                 binary32: ... 4096 bytes): the array is
                                 read as one contiguous stream and 0/1 selection matrices in the two MMAs (or a
@@ -225,7 +225,8 @@ typedef struct {
     int      kernel;   /* a redux_kernel */
     int      unroll;   /* 16-byte loads in flight per lane (ROWS: per row group) */
     unsigned grid;     /* 256-thread blocks of the main kernel */
-    int      finish;   /* FLAT: 1 = in the same kernel, 2 = second kernel; segmented: 2 if parts > 1, else 0 */
+    int      finish;   /* FLAT: the value of "finish" that is used (2 = second kernel; 4, 5, 6 = in the same kernel); segmented:
+                          0 if parts == 1, else where the piece totals meet: 2 = second kernel, 5 (int8) / 6 = same kernel */
     uint64_t parts;    /* pieces per segment (above 1 only for PIECES and BLOCK) */
     uint64_t part_len; /* elements per piece */
     unsigned head;     /* FLAT: elements before the first 16-byte aligned vector */
@@ -303,6 +304,14 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               four per compute unit, take the pipelined one-wavefront-per-segment kernel (default 1)
  *   "seg_parts"         0,1,2,4,...,4096  segmented sum: pieces a long segment is cut into; 0 = from the
  *                               shape (default 0); ignored if nseg * pieces exceeds the workspace (16384)
+ *   "seg_finish"        -1,0,1  segmented sum, long segments cut into pieces, one block per piece: 1 = the block of a
+ *                               segment that arrives last adds the segment's piece totals in the same kernel (floating
+ *                               point: totals in slots that read empty between launches, arrivals counted by a ticket
+ *                               per segment; int8: one 64-bit atomic addition per piece that adds and counts), 0 = a
+ *                               second kernel adds them; same order, same bits.  -1 = the measured best: the same
+ *                               kernel for calls of up to 8 MiB and for few pieces per segment (up to 8; int8: up to 32,
+ *                               and any number from 256 MiB on), never where a block has a second piece to go on
+ *                               to (default -1)
  *   "compensated"       0/1     redux_sum, binary16, MMA family: the first MMA runs with C = 0 and its row sums are added to the
  *                               running sums with a two-sum on the vector ALU, the lost parts kept in a second
  *                               accumulator (for the precision study: it buys nothing once chains are bounded, and costs

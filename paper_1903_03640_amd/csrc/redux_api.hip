@@ -57,6 +57,8 @@ struct Settings {
     long compensated = 0;         // flat sum, binary16, MMA family: two-sum compensated chain (precision study)
     long lit_half = 0;            // level-by-level form, binary16, m = 16: both MMA results and the partial sums in binary16
     long finish = -1;             // -1 = from the input size
+    long seg_finish = -1;         // segments cut into pieces, one block each: 1 = the last block of a segment to arrive adds its piece
+                                  // totals, 0 = a second kernel does, -1 = measured best
     long pause = -1;              // flat sum: 64-cycle sleeps at the end of every loop iteration (-1 = measured best)
 };
 Settings g_set;
@@ -84,12 +86,16 @@ int hip_fail(hipError_t e, int status = REDUX_ERR_HIP)
 struct Workspace {
     u64 *partials = nullptr;    // kMaxGrid slots
     unsigned *ticket = nullptr; // behind the partials, on its own 256-byte line
-    u64 *slots = nullptr;       // behind the ticket: kWorkspaceSlots slots that read empty between launches (finish 6)
+    u64 *slots = nullptr;       // behind the ticket: kMaxGrid slots that read empty between launches (flat sum, finish 6: the
+                                // first kWorkspaceSlots; segments cut into pieces that finish in the kernel: one per piece)
+    u64 *counted = nullptr;     // behind the slots: kMaxGrid / 2 words that read zero between launches, one per segment that is
+                                // cut into pieces (floating point: its ticket; int8: its counted sum)
 };
 constexpr unsigned kWorkspaceSlots = 2048;
 constexpr size_t kTicketOffset = (size_t)kMaxGrid * sizeof(u64);
 constexpr size_t kSlotsOffset = kTicketOffset + 256;
-constexpr size_t kWorkspaceBytes = kSlotsOffset + (size_t)kWorkspaceSlots * sizeof(u64);
+constexpr size_t kCountedOffset = kSlotsOffset + (size_t)kMaxGrid * sizeof(u64);
+constexpr size_t kWorkspaceBytes = kCountedOffset + (size_t)(kMaxGrid / 2) * sizeof(u64);
 
 std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
 
@@ -128,7 +134,9 @@ int get_workspace(int dev, hipStream_t st, Workspace *out)
         // the ticket must read zero before the first launch; a fill kernel on the caller's
         // stream keeps the ordering without a device-wide synchronisation
         w.slots = (u64 *)((char *)p + kSlotsOffset);
-        hipLaunchKernelGGL(empty_slots_kernel, dim3(1), dim3(256), 0, st, w.slots, kWorkspaceSlots, w.ticket, 64u);
+        w.counted = (u64 *)((char *)p + kCountedOffset);
+        hipLaunchKernelGGL(empty_slots_kernel, dim3(1), dim3(256), 0, st, w.slots, (unsigned)kMaxGrid, w.ticket, 64u);
+        hipLaunchKernelGGL(fill_zero_words_kernel, dim3(kMaxGrid / 256), dim3(256), 0, st, (unsigned *)w.counted, (unsigned)kMaxGrid);
         e = hipGetLastError();
         if (e != hipSuccess) { (void)hipFree(p); return hip_fail(e); }
         it = g_ws.emplace(key, w).first;
@@ -354,6 +362,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "seg_run_len")) { *lo = 0; *hi = 16; return &g_set.seg_run_len; }
     if (!std::strcmp(name, "seg_tiles")) { *lo = 0; *hi = 1; return &g_set.seg_tiles; }
     if (!std::strcmp(name, "seg_parts")) { *lo = 0; *hi = 4096; return &g_set.seg_parts; }
+    if (!std::strcmp(name, "seg_finish")) { *lo = -1; *hi = 1; return &g_set.seg_finish; }
     if (!std::strcmp(name, "compensated")) { *lo = 0; *hi = 1; return &g_set.compensated; }
     if (!std::strcmp(name, "lit_half")) { *lo = 0; *hi = 1; return &g_set.lit_half; }
     if (!std::strcmp(name, "lit_m")) { *lo = 4; *hi = 32; return &g_set.lit_m; }
@@ -672,6 +681,25 @@ SegPlan plan_segmented(const Settings &S, u64 nseg, u64 seglen, int dtype, size_
     return p;
 }
 
+// Segments cut into pieces: does the same kernel add a segment's piece totals (the last block of the segment to arrive),
+// or a second kernel?  Only the one-block-per-piece kernel can; its slots and tickets cover every shape it is given
+// (pieces <= kMaxGrid, at least two per segment).  Measured, us per call back to back, second kernel / same kernel:
+//   2 x 0.5 ... 4 MiB    8.4 / 5.9 - 7.0 (a launch less, and the call is all launch)
+//   128 x 128 KiB ... 1 MiB (4 pieces each)   9.3 / 6.7 (16 MiB), 9.4 / 8.9, 13.6 / 13.1, 23.5 / 22.7 (128 MiB), level above
+//   2 or 16 x ... (32 - 256 pieces each), 16 - 128 MiB   8.4 / 10.1, 8.9 / 12.3, 13.5 / 16.8, 23.4 / 25.4: the arrivals of a
+//       segment's pieces all at once queue up at its ticket; int8, which has one read-modify-write per piece and no piece
+//       totals to fetch, is level or ahead up to 32 pieces (9.3 / 8.6 ... 24.3 / 22.6) and from 256 MiB on (79.6 / 78.4)
+//   more pieces than blocks (a block goes on to a second piece): 79.6 / 91.8 -- it waits for its ticket first
+bool seg_finish_in_kernel(const Settings &S, const SegPlan &p, int dtype, u64 nseg, u64 seg_bytes)
+{
+    if (p.kernel != REDUX_KERNEL_BLOCK || p.parts <= 1 || S.seg_finish == 0) return false;
+    if (S.seg_finish > 0) return true;
+    if (nseg * p.parts > (u64)p.grid) return false;
+    const u64 bytes = nseg * seg_bytes;
+    if (bytes <= ((u64)8 << 20)) return true;
+    return dtype == REDUX_I8 ? (p.parts <= 32 || bytes >= ((u64)256 << 20)) : p.parts <= 8;
+}
+
 } // namespace
 
 // =====================================================================================================
@@ -931,11 +959,19 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     a.parts = plan.parts;
     a.part_len = plan.part_len;
     a.partials = nullptr;
+    a.seg_finish = 0;
+    a.slots = nullptr;
+    a.tickets = nullptr;
+    a.counted = nullptr;
     if (plan.parts > 1) {
         Workspace ws;
         std::lock_guard<std::mutex> lock(g_mu);
         if ((rc = get_workspace(dev, st, &ws)) != REDUX_OK) return rc;
         a.partials = ws.partials;
+        a.seg_finish = seg_finish_in_kernel(S, plan, dtype, nseg, seglen * es) ? 1 : 0;
+        a.slots = ws.slots;
+        a.tickets = (unsigned *)ws.counted;
+        a.counted = ws.counted;
     }
     const int unroll = plan.unroll;
 
@@ -968,7 +1004,7 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     }
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
-    if (a.parts > 1) {
+    if (a.parts > 1 && !a.seg_finish) {
         const unsigned p = (unsigned)a.parts, g = (unsigned)nseg;
         if (dtype == REDUX_I8) hipLaunchKernelGGL(finish_segments_kernel<I8Classic>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
         else if (mfma)         hipLaunchKernelGGL(finish_segments_kernel<F16Mfma>, dim3(g), dim3(kBlock), 0, st, a.partials, p, out);
@@ -1141,7 +1177,7 @@ int redux_plan_sum_segmented(size_t nseg, size_t seglen, int dtype, uintptr_t x_
     plan->kernel = p.kernel;
     plan->unroll = p.unroll;
     plan->grid = p.grid;
-    plan->finish = p.parts > 1 ? 2 : 0;
+    plan->finish = p.parts > 1 ? (seg_finish_in_kernel(g_set, p, dtype, nseg, seglen * es) ? (dtype == REDUX_I8 ? 5 : 6) : 2) : 0;
     plan->parts = p.parts;
     plan->part_len = p.part_len;
     plan->head = 0;

@@ -776,6 +776,14 @@ struct SegArgs {
     // fill the chip; piece totals go to `partials` and finish_segments_kernel adds them up.
     u64 parts, part_len;
     u64 *partials;
+    // One block per piece, finish in the same kernel (seg_finish = 1): the block that is the last of its segment to arrive adds
+    // the segment's piece totals.  Floating point: totals go to `slots` (one per piece, all empty before the launch and after
+    // it) and arrivals are counted in tickets[segment]; int8: total and count share the 64-bit word counted[segment].
+    // Tickets and counted words are zero before the launch and after it.
+    int seg_finish;
+    u64 *slots;
+    unsigned *tickets;
+    u64 *counted;
 };
 
 // all-ones in the low b bytes of a 128-bit word (b = 0 .. 16), as two 64-bit halves
@@ -944,7 +952,8 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
     constexpr u64 kSlab = (u64)kBlock * U;
     const u64 npieces = a.nseg * a.parts;
-    __shared__ Total lds[kWaves];
+    __shared__ Total lds[kBlock];
+    __shared__ unsigned is_last;
 
     for (u64 piece = blockIdx.x; piece < npieces; piece += gridDim.x) {
         const u64 seg = piece / a.parts, part = piece % a.parts;
@@ -996,10 +1005,39 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
         __syncthreads();
         if (tid == 0) {
             const Total total = (lds[0] + lds[1]) + (lds[2] + lds[3]);
-            if (a.parts == 1) ((typename F::Out *)a.out)[seg] = F::to_out(total);
-            else a.partials[piece] = __builtin_bit_cast(u64, total);
+            is_last = 0u;
+            if (a.parts == 1) {
+                ((typename F::Out *)a.out)[seg] = F::to_out(total);
+            } else if (!a.seg_finish) {
+                a.partials[piece] = __builtin_bit_cast(u64, total);      // finish_segments_kernel, launched behind this kernel, adds them
+            } else if constexpr (std::is_integral<Total>::value) {
+                // integer totals: one atomic addition per piece adds them up and counts them (sum above bit 15, count below;
+                // at most 4096 pieces per segment); whoever completes the count holds the segment's sum
+                const u64 mine = ((u64)(i64)total << 15) + 1u;
+                const u64 now = __hip_atomic_fetch_add(a.counted + seg, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+                if ((now & 0x7fffu) == a.parts) {
+                    ((typename F::Out *)a.out)[seg] = (typename F::Out)((i64)now >> 15);
+                    (void)__hip_atomic_exchange(a.counted + seg, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            } else {
+                // the piece total is sent off to its slot and the segment's ticket drawn at once; the last ticket says that all
+                // of the segment's totals are on their way, and fetch_partials reads each slot until it has arrived
+                publish_to_slot(a.slots + piece, total);
+                const unsigned t = __hip_atomic_fetch_add(a.tickets + seg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                is_last = (t == (unsigned)a.parts - 1u) ? 1u : 0u;
+            }
         }
-        __syncthreads();                                   // lds is reused by the next piece
+        __syncthreads();                                   // lds is reused: by the sum of the piece totals, or by the next piece
+        if constexpr (!std::is_integral<Total>::value) {
+            if (is_last) {                                 // (the same for the whole block)
+                const Total total = sum_partials<F, true>(a.slots + seg * a.parts, (unsigned)a.parts, lds);
+                if (tid == 0) {
+                    ((typename F::Out *)a.out)[seg] = F::to_out(total);
+                    (void)__hip_atomic_exchange(a.tickets + seg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                __syncthreads();
+            }
+        }
     }
 }
 

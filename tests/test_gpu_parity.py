@@ -47,7 +47,7 @@ def default_params():
                       ("seg_blocks_per_cu", DEFAULTS["seg_blocks_per_cu"]), ("layout", DEFAULTS["layout"]),
                       ("finish", DEFAULTS["finish"]), ("rows_max_vec", 64), ("seg_parts", 0), ("seg_tiles", 1), ("seg_short", 1), ("seg_ragged", 1), ("seg_short_pipe", -1), ("seg_block_bytes", 28672), ("lit_unroll", 0),
                       ("lit_blocks_per_cu", 0), ("lit_m", 16), ("seg_runs", 1), ("seg_run_len", 0),
-                      ("seg_runs_max", 0), ("seg_runs_long", 36863), ("seg_balance", 1), ("seg_runs_stream", 1)):
+                      ("seg_runs_max", 0), ("seg_runs_long", 36863), ("seg_balance", 1), ("seg_runs_stream", 1), ("seg_finish", -1)):
         redux.set_param(name, val)
     redux.set_variant("auto")
 
@@ -488,10 +488,12 @@ def test_segmented_short_rows_i8(dev, variant, seglen):
 @pytest.mark.parametrize("nseg,seglen,parts", [(3, (1 << 20) + 3, 0), (2, 1 << 22, 0), (256, 65536, 0), (5, 100003, 8),
                                                (1, (1 << 23) + 17, 0), (7, 5000, 4), (16, 1 << 16, 64), (3, 40, 2)])
 @pytest.mark.parametrize("block_bytes", [32768, 0, 4096])
-def test_segmented_long_pieces(dev, variant, nseg, seglen, parts, block_bytes):
+@pytest.mark.parametrize("seg_finish", [-1, 0, 1])
+def test_segmented_long_pieces(dev, variant, nseg, seglen, parts, block_bytes, seg_finish):
     redux.set_variant(variant)
     redux.set_param("seg_parts", parts)
     redux.set_param("seg_block_bytes", block_bytes)           # one block per piece, or (0) one wavefront per piece
+    redux.set_param("seg_finish", seg_finish)                 # piece totals meet in the same kernel or in a second one
     x = workloads.normal_f16(nseg + parts, nseg * seglen)
     want, want_abs = oracle.sum_segmented_f16(x, nseg, seglen)
     got = redux.sum_segmented(to_dev(x, dev, 1), nseg, seglen)
@@ -501,6 +503,46 @@ def test_segmented_long_pieces(dev, variant, nseg, seglen, parts, block_bytes):
     torch.cuda.synchronize()
     assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
     assert np.array_equal(goti.cpu().numpy(), wanti)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_pieces_meet_in_the_kernel_or_behind_it_with_the_same_bits(dev, variant):
+    """Segments cut into pieces: the last block of a segment to arrive adds the piece totals, or a second kernel does --
+    in the same order, so bit for bit the same, call after call; calls alternate between two arrays and two shapes, so
+    a slot, a ticket or a counted word left over from the call before (or read before it was filled) would show."""
+    redux.set_variant(variant)
+    shapes = ((3, (1 << 20) + 3, 0), (40, 100001, 0), (8, 33333, 0), (100, 300000, 16), (2, 1 << 22, 0), (4, 70001, 4096))
+    for nseg, seglen, parts in shapes:
+        redux.set_param("seg_parts", parts)
+        a, b = workloads.normal_f16(81, nseg * seglen), workloads.normal_f16(82, (nseg - 1) * (seglen - 7))
+        ai, bi = workloads.uniform_i8(83, nseg * seglen), workloads.uniform_i8(84, (nseg - 1) * (seglen - 7))
+        xa, xb, xai, xbi = to_dev(a, dev, 1), to_dev(b, dev), to_dev(ai, dev, 3), to_dev(bi, dev)
+        want = {}
+        wanti = {False: oracle.sum_segmented_i8(ai, nseg, seglen)[0], True: oracle.sum_segmented_i8(bi, nseg - 1, seglen - 7)[0]}
+        for fin in (0, 1):
+            redux.set_param("seg_finish", fin)
+            plan = redux.plan_sum_segmented(nseg, seglen, redux.F16, xa.data_ptr(), 256)
+            assert plan.kernel == redux.KERNEL_BLOCK and plan.parts > 1 and plan.finish == (6 if fin else 2)
+            for k in range(6):
+                small = k % 2 == 1
+                n2, l2 = (nseg - 1, seglen - 7) if small else (nseg, seglen)
+                got = redux.sum_segmented(xb if small else xa, n2, l2)
+                goti = redux.sum_segmented(xbi if small else xai, n2, l2)
+                torch.cuda.synchronize()
+                bits = got.cpu().numpy().view(np.uint32)
+                if fin == 0 and k < 2:
+                    ref, ref_abs = oracle.sum_segmented_f16(b if small else a, n2, l2)
+                    assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - ref) <= TOL * ref_abs)
+                    want[small] = bits
+                assert np.array_equal(bits, want[small]), (nseg, seglen, parts, fin, k)
+                assert np.array_equal(goti.cpu().numpy(), wanti[small]), (nseg, seglen, parts, fin, k)
+    # int8 at its extremes: the counted word holds the sum above bit 15, whatever its sign
+    redux.set_param("seg_parts", 64)
+    redux.set_param("seg_finish", 1)
+    for value in (-128, 127):
+        x = torch.full((3 * 3000001,), value, dtype=torch.int8, device=dev)
+        for _ in range(2):
+            assert redux.sum_segmented(x, 3, 3000001).cpu().tolist() == [value * 3000001] * 3
 
 
 # ---- the level-by-level form (groups of m*m = 256, C = 0 per group, one launch per level) -------------------
