@@ -204,7 +204,8 @@ typedef enum {
     REDUX_KERNEL_FLAT   = 0, /* redux_sum */
     REDUX_KERNEL_ROWS   = 1, /* redux_sum_segmented, sixteen short segments per wavefront */
     REDUX_KERNEL_WAVE   = 2, /* redux_sum_segmented, one wavefront per segment */
-    REDUX_KERNEL_PIECES = 3, /* redux_sum_segmented, long segments cut into pieces + per-segment finish */
+    REDUX_KERNEL_PIECES = 3, /* redux_sum_segmented, long segments cut into pieces, one wavefront per piece, + a per-segment finish
+                                kernel: only with "seg_block_bytes" = 0 (from 32 KiB on) or "seg_parts" above 1 */
     REDUX_KERNEL_TILES  = 4, /* redux_sum_segmented, segments of exactly 1, 2, 4 or 8 KiB: one wavefront per
                                 segment with the next segment's loads issued ahead */
     REDUX_KERNEL_BLOCK  = 5, /* redux_sum_segmented, long segments: one block per segment or per piece of one
