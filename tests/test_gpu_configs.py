@@ -76,6 +76,40 @@ def test_segmented_config(variant):
     print("C5 %s: worst err/sum|x| %.3g" % (variant, np.max(np.abs(got - want) / want_abs)))
 
 
+@pytest.mark.parametrize("variant", ["auto", "mfma", "classic"])
+def test_full_size_arrays_as_a_few_long_segments(variant):
+    """The arrays of C5 and C4 at full size, read as a handful of long segments: every segment is cut into pieces, one
+    block each, whose totals meet in a second kernel (the library's choice at this size: there are more pieces than
+    blocks) or, when asked for, in the same kernel."""
+    redux.set_variant(variant)
+    try:
+        cfg, host, x, _ = config_data("C5")
+        n = cfg.nseg * cfg.seglen
+        for nseg in (16, 128, 1):
+            seglen = n // nseg
+            want, want_abs = oracle.sum_segmented_f16(host, nseg, seglen)
+            for seg_finish, finish in ((-1, 2), (1, 6)):
+                redux.set_param("seg_finish", seg_finish)
+                plan = redux.plan_sum_segmented(nseg, seglen, redux.F16, x.data_ptr(), 256)
+                assert plan.kernel == redux.KERNEL_BLOCK and plan.parts > 1 and plan.finish == finish, (nseg, plan.parts, plan.finish)
+                got = redux.sum_segmented(x, nseg, seglen)
+                torch.cuda.synchronize()
+                assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - want) <= TOL * want_abs), (nseg, seg_finish)
+        cfg, host, x, _ = config_data("C4")
+        for nseg in (64, 4):
+            seglen = cfg.n // nseg
+            want = oracle.sum_segmented_i8(host, nseg, seglen)[0]
+            for seg_finish, finish in ((-1, 2), (1, 5)):
+                redux.set_param("seg_finish", seg_finish)
+                plan = redux.plan_sum_segmented(nseg, seglen, redux.I8, x.data_ptr(), 256)
+                assert plan.kernel == redux.KERNEL_BLOCK and plan.parts > 1 and plan.finish == finish, (nseg, plan.parts, plan.finish)
+                got = redux.sum_segmented(x, nseg, seglen)
+                torch.cuda.synchronize()
+                assert np.array_equal(got.cpu().numpy(), want), (nseg, seg_finish)
+    finally:
+        redux.set_param("seg_finish", -1)
+
+
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4"])
 def test_multipass_configs(name):
     """The level-by-level form at full size: result and number of launches."""
