@@ -294,8 +294,10 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               iteration (of this run or of its next one) needs, right after it has been used, so the
  *                               loads stay in flight across the end of a run; 0 = load, work, fold, store, run by run
  *                               (default 1: measured 2-4 % ahead; on the same grid with the same run length the results are the same bit for bit)
- *   "seg_balance"       0/1     segmented sum, one block per segment: segments are cut into (more) pieces of at least 64 KiB
- *                               while the last round of pieces over the grid would leave more than 15 % of it idle (default 1)
+ *   "seg_balance"       0..99   segmented sum, one block per segment: segments are cut into (more) pieces of at least 64 KiB
+ *                               while the rounds of pieces over the grid would leave too much of it idle: 1 = whole segments
+ *                               are cut below 85 % use, segments that are cut anyway on to 92 %; 2 .. 99 = that
+ *                               percentage for both; 0 = never (default 1)
  *   "seg_run_len"       0..16   that kernel: segments per run; 0 = the length with the lowest cost per wavefront
  *                               (iterations, of which a run's last is partly idle, plus a fixed cost per run; every
  *                               wavefront takes the same number of whole runs and a share of what is left) (default 0)

@@ -281,7 +281,7 @@ def test_segmented_plan_defaults_on_mi355x():
     # where the pieces of a segment meet: in the same kernel for small calls and for few pieces per segment (int8: up to 32),
     # in a second kernel where many would arrive at one ticket together or a block has a second piece to go on to
     for shape, want in (((2, 1 << 20, redux.F16), (64, 128, 6)), ((128, 1 << 19, redux.F16), (4, 512, 6)), ((16, 1 << 22, redux.F16), (32, 512, 2)),
-                        ((16, 1 << 23, redux.I8), (32, 512, 5)), ((2, 1 << 26, redux.I8), (256, 512, 2)), ((100, 2621440, redux.F16), (32, 512, 2))):
+                        ((16, 1 << 23, redux.I8), (32, 512, 5)), ((2, 1 << 26, redux.I8), (256, 512, 2)), ((100, 2621440, redux.F16), (64, 512, 2))):
         q = redux.plan_sum_segmented(shape[0], shape[1], shape[2], 0, 256)
         assert (q.kernel, q.parts, q.grid, q.finish) == (redux.KERNEL_BLOCK,) + want, (shape, q.parts, q.grid, q.finish)
     redux.set_param("seg_finish", 0)
