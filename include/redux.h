@@ -105,7 +105,7 @@ int redux_sum(const void *x, size_t n, int dtype, void *out, void *stream);
  * redux_sum_static -- redux_sum for callers that must not allocate: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same result bit for bit as redux_sum with
  * the same settings; the only difference is where the block partials and the ticket live: not in the per-stream
- * workspace that redux_sum allocates on first use, but in a static array in device memory (16 640 bytes per device,
+ * workspace that redux_sum allocates on first use, but in a static array in device memory (18 688 bytes per device,
  * held from the moment the library's code is loaded on a device until the process ends).
  *
  *   - Calls no hipMalloc, hipFree or any other allocating routine, on any call.  The first call on a device asks the
@@ -333,7 +333,7 @@ int redux_resolved_variant(int dtype, int segmented);
  *   "layout"            0..2    which part of the array a block reads: 0 = blocks interleaved over the
  *                               whole array, 1 = one contiguous share per block, 2 = one contiguous
  *                               eighth per accelerator die, interleaved among that die's blocks (default 2)
- *   "finish"            -1..6   how block partials become the result: 0/1/4 = the block that arrives last
+ *   "finish"            -1..8   how block partials become the result: 0/1/4 = the block that arrives last
  *                               sums them in the same kernel (0: acquire+release on every block's ticket,
  *                               1: release only, acquire in the last block, 4: no release fence at all -- the
  *                               partial is published by a device-scope atomic exchange whose completion the
@@ -349,7 +349,13 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               arrived before it draws its ticket; the partials go to slots that read empty
  *                               between launches, and the last block reads each slot until it is filled, then
  *                               empties it again (grids above 2048 blocks and int8: taken as 4),
- *                               -1 = the measured best for the input: 5 for int8, else 6 or 2 by size (default -1)
+ *                               7 = as 6 and 8 = as 5, with the arrivals counted in two levels: the blocks of an
+ *                               accelerator die (block b runs on die b mod 8) meet at a word of the die's own, the
+ *                               last of each die at the common one, so that no word has more than gridDim / 8
+ *                               read-modify-writes queueing at it,
+ *                               -1 = the measured best for the input: 5 or 8 for int8, else 6 or 7; the two-level
+ *                               forms for inputs above 2 MiB and below 256 MiB, whose blocks all arrive within a
+ *                               microsecond (default -1)
  *   "max_chain"         1..65536 loop iterations between folds of the MMA accumulators into the wide
  *                               per-wavefront total (bounds binary32 chain length).  For int8 the library lowers
  *                               it where needed so that an int32 accumulator stays below 2^31 for any input

@@ -21,7 +21,8 @@ using namespace redux;
 // holds its own copy of this array from the moment the code object is loaded until the process ends.
 constexpr int kScratchSlots = 2048;                              // block partials a launch may write
 constexpr size_t kScratchTicketOffset = (size_t)kScratchSlots * sizeof(u64);
-constexpr size_t kScratchBytes = kScratchTicketOffset + 256;    // 16 640 bytes
+constexpr size_t kScratchLeavesOffset = kScratchTicketOffset + 256;   // eight second-level tickets, 256 bytes apart
+constexpr size_t kScratchBytes = kScratchLeavesOffset + 8 * 256;      // 18 688 bytes
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
@@ -135,7 +136,7 @@ int get_workspace(int dev, hipStream_t st, Workspace *out)
         // stream keeps the ordering without a device-wide synchronisation
         w.slots = (u64 *)((char *)p + kSlotsOffset);
         w.counted = (u64 *)((char *)p + kCountedOffset);
-        hipLaunchKernelGGL(empty_slots_kernel, dim3(1), dim3(256), 0, st, w.slots, (unsigned)kMaxGrid, w.ticket, 64u);
+        hipLaunchKernelGGL(empty_slots_kernel, dim3(1), dim3(256), 0, st, w.slots, (unsigned)kMaxGrid, w.ticket, 64u, (unsigned *)nullptr);
         hipLaunchKernelGGL(fill_zero_words_kernel, dim3(kMaxGrid / 256), dim3(256), 0, st, (unsigned *)w.counted, (unsigned)kMaxGrid);
         e = hipGetLastError();
         if (e != hipSuccess) { (void)hipFree(p); return hip_fail(e); }
@@ -370,7 +371,7 @@ long *param_slot(const char *name, long *lo, long *hi)
     if (!std::strcmp(name, "lit_blocks_per_cu")) { *lo = 0; *hi = 16; return &g_set.lit_blocks_per_cu; }
     if (!std::strcmp(name, "layout")) { *lo = 0; *hi = 2; return &g_set.layout; }
     if (!std::strcmp(name, "pause")) { *lo = -1; *hi = 64; return &g_set.pause; }
-    if (!std::strcmp(name, "finish")) { *lo = -1; *hi = 6; return &g_set.finish; }
+    if (!std::strcmp(name, "finish")) { *lo = -1; *hi = 8; return &g_set.finish; }
     return nullptr;
 }
 
@@ -409,24 +410,24 @@ FlatPlan plan_flat(const Settings &S, u64 nvec, int cus, int dtype)
     }
     const u64 nslab = nvec / ((u64)kBlock * p.unroll);
     p.grid = (unsigned)(nslab < 1 ? 1 : (nslab < gmax ? nslab : gmax));
-    // Measured (us per whole call, back to back; 64 / 128 / 256 blocks at 2 / 4 / 8 MiB): finishing inside the kernel, every
-    // block sending its partial off and drawing a ticket (finish 6), takes 4.4 / 5.3 / 6.8 and a second one-block kernel
-    // (finish 2) 7.1 / 7.1 / 7.1: up to 8 MiB the same kernel finishes.  From 16 to 128 MiB all 256 blocks arrive within
-    // a microsecond and their read-modify-writes queue up (7.8 against 7.0 at 16 MiB, 22.9 against 22.5 at 128 MiB), so
-    // the second kernel finishes.  From 256 MiB on the arrivals are spread out and the one kernel is ahead again
-    // (39.1 / 74.2 / 144.5 / 288.3 against 40.0 / 74.8 / 145.2 / 288.9 at 256 MiB ... 2 GiB): one kernel per call it is.
-    p.finish = (int)S.finish;
-    if (p.finish < 0) p.finish = (nvec <= ((u64)8 << 20) / 16 || nvec >= ((u64)256 << 20) / 16) ? 4 : 2;
-    // int8: the totals are integers, so one atomic addition per block can both add them up and count the blocks (finish
-    // 5): one round trip at the end of the kernel instead of three.  Measured, us per call, against the better of
-    // finish 2 and 4: 3.96 / 5.5 at 1 MiB, 6.45 / 6.6 at 8 MiB, 22.6 / 23.0 at 128 MiB, 144.0 / 145.7 at 1 GiB.
-    // Not for the other types (their sums depend on the order), nor beyond 2^40 elements (the sum's field has 49 bits).
-    if (dtype == REDUX_I8 && nvec <= ((u64)1 << 36) && (S.finish < 0 || S.finish == 5)) p.finish = 5;
-    else if (p.finish == 5) p.finish = 4;
-    // The other types: where the same kernel finishes, nobody waits for its partial to arrive but the last block
-    // (finish 6), as long as the grid fits the slots kept empty for that.
-    if (dtype != REDUX_I8 && p.grid <= kWorkspaceSlots && ((S.finish < 0 && p.finish == 4) || S.finish == 6)) p.finish = 6;
-    else if (p.finish == 6) p.finish = 4;
+    // How the block totals meet (all in the same kernel; us per whole call, back to back, binary16 / int8):
+    //   floating point: every block sends its partial to a slot and draws a ticket, the last one adds the slots (finish 6);
+    //   int8: one atomic addition per block adds its total to a word and counts it (finish 5).
+    //   Read-modify-writes of one word are served one after the other, about 8 ns each.  From 4 to 128 MiB all blocks arrive
+    //   within a microsecond and the last waits for a queue of 256, so there the blocks of a die meet at the die's own word
+    //   first and the eight dies at the common one (finish 7 / 8): 8 MiB 5.2 / 4.5 against 7.1 / 6.6 in one level (and
+    //   6.4 - 7.0 with a second one-block kernel, finish 2), 32 MiB 8.5 / 7.6 against 10.2 / 9.5 (8.8), 128 MiB 22.4 / 21.5
+    //   against 23.6 / 22.8 (22.4).  Up to 2 MiB (64 blocks) and from 256 MiB on (arrivals spread out) one level is level
+    //   or ahead by the second level's round trip: 2 GiB 289.0 / 288.9 against 289.4 / 289.1 (second kernel 289.1 / 290.4).
+    // What an input cannot take falls back to the plain ticket finish (4): int8 beyond 2^40 elements (the counted
+    // word's sum has 49 bits), floating point on more blocks than there are slots.
+    const bool together = nvec > ((u64)2 << 20) / 16 && nvec < ((u64)256 << 20) / 16;
+    const bool is_int = dtype == REDUX_I8;
+    int finish = (int)S.finish;
+    if (finish < 0) finish = is_int ? (together ? 8 : 5) : (together ? 7 : 6);
+    if ((finish == 5 || finish == 8) && !(is_int && nvec <= ((u64)1 << 36))) finish = 4;
+    if ((finish == 6 || finish == 7) && (is_int || p.grid > kWorkspaceSlots)) finish = 4;
+    p.finish = finish;
     const bool mfma = effective_variant(S, dtype, true) == REDUX_VARIANT_MFMA;
     p.chain = chain_length(S, dtype, mfma, p.unroll, 4);
     // Measured on 0.5 - 4 GiB of binary16, bfloat16 and int8: a wavefront of the MMA family that sleeps about 500 cycles
@@ -721,6 +722,7 @@ static int launch_sum(const Settings &S, int cus, const Workspace &ws, bool clea
     a.partials = ws.partials;
     a.ticket = ws.ticket;
     a.slots = ws.slots;
+    a.leaves = (unsigned *)ws.counted;
     a.out = out;
     a.layout = (int)S.layout;
     a.stagger = (unsigned)S.stagger;
@@ -742,7 +744,7 @@ static int launch_sum(const Settings &S, int cus, const Workspace &ws, bool clea
         if (e != hipSuccess) return hip_fail(e);
     } else if (clear_ticket && a.finish != 2) {
         // the ticket and the counted sum behind it; the slots of the blocks to come
-        hipLaunchKernelGGL(empty_slots_kernel, dim3(1), dim3(256), 0, st, a.slots, a.finish == 6 ? grid : 0u, a.ticket, 4u);
+        hipLaunchKernelGGL(empty_slots_kernel, dim3(1), dim3(256), 0, st, a.slots, a.finish == 6 || a.finish == 7 ? grid : 0u, a.ticket, 4u, a.leaves);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
     }
@@ -829,6 +831,7 @@ int redux_sum_static(const void *x, size_t n, int dtype, void *out, void *stream
         ws.partials = (u64 *)g_scratch_ptr[dev];
         ws.ticket = (unsigned *)((char *)g_scratch_ptr[dev] + kScratchTicketOffset);
         ws.slots = ws.partials;             // marked empty by every call that uses them
+        ws.counted = (u64 *)((char *)g_scratch_ptr[dev] + kScratchLeavesOffset);   // (only its use as second-level tickets)
     }
     // The launch writes one partial per block.  More blocks than the array has slots can only be asked for through
     // "blocks_per_cu" / "max_grid" on a device with many compute units; such a call is refused, never truncated.

@@ -542,7 +542,8 @@ struct FlatArgs {
     Run run;
     u64 *partials;      // kMaxGrid slots
     unsigned *ticket;   // zero before the launch; the finishing block resets it
-    u64 *slots;         // finish 6: one per block, all empty (kEmptySlot) before the launch; the finishing block empties them
+    u64 *slots;         // finish 6, 7: one per block, all empty (kEmptySlot) before the launch; the finishing block empties them
+    unsigned *leaves;   // finish 7, 8: eight tickets (8: counted sums), 256 bytes apart, zero before the launch and after it
     void *out;
     unsigned max_chain; // loop iterations between folds
     int layout;         // which slabs a block takes (see slab_schedule)
@@ -674,7 +675,7 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
                                    __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
-    if (a.finish == 5) {
+    if (a.finish == 5 || a.finish == 8) {
         // Integer totals only (the host sees to that).  Integer addition does not care about the order, so the blocks may
         // simply add their totals up with atomic additions, as Section II describes -- and the same addition can count
         // them: the word holds the running sum above bit 15 and the number of blocks that have added to it below (a grid
@@ -686,25 +687,62 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
             if (tid == 0) {
                 const i64 block_total = (i64)((lds[0] + lds[1]) + (lds[2] + lds[3]));
                 u64 *word = (u64 *)(a.ticket + 2);                       // the eight bytes behind the ticket, on its line
-                const u64 mine = ((u64)block_total << 15) + 1u;
-                const u64 now = __hip_atomic_fetch_add(word, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
-                if ((now & 0x7fffu) == gridDim.x) {
-                    *(typename F::Out *)a.out = (typename F::Out)((i64)now >> 15);
-                    (void)__hip_atomic_exchange(word, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                u64 mine = ((u64)block_total << 15) + 1u;
+                unsigned arrivals = gridDim.x;
+                bool up = true;
+                if (a.finish == 8) {
+                    // in two levels (see finish 7 below for why): the blocks of a die add to the die's own word, and the
+                    // one that completes its count adds the die's sum to the common word, which counts dies
+                    const unsigned die = blockIdx.x % kXcds;
+                    const unsigned on_die = (gridDim.x - die + kXcds - 1) / kXcds;
+                    u64 *leaf = (u64 *)(a.leaves + die * 64u);
+                    const u64 now = __hip_atomic_fetch_add(leaf, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+                    up = (now & 0x7fffu) == on_die;
+                    if (up) {
+                        (void)__hip_atomic_exchange(leaf, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        mine = (now & ~(u64)0x7fffu) + 1u;               // the die's sum, counted as one arrival
+                        arrivals = gridDim.x < (unsigned)kXcds ? gridDim.x : (unsigned)kXcds;
+                    }
+                }
+                if (up) {
+                    const u64 now = __hip_atomic_fetch_add(word, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+                    if ((now & 0x7fffu) == arrivals) {
+                        *(typename F::Out *)a.out = (typename F::Out)((i64)now >> 15);
+                        (void)__hip_atomic_exchange(word, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
             }
         }
         return;
     }
-    if (a.finish == 6) {
+    if (a.finish == 6 || a.finish == 7) {
         // As finish 4 below, one round trip shorter: the block sends its partial off (an atomic exchange whose old value
         // nobody needs) and draws its ticket at once.  The last ticket then says that every partial is on its way, not
         // that it has arrived, so the slots start out empty and the finishing block reads each until it is not.
         if constexpr (!std::is_integral<Total>::value) {
             if (tid == 0) {
                 publish_to_slot(a.slots + blockIdx.x, (lds[0] + lds[1]) + (lds[2] + lds[3]));
-                const unsigned t = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                is_last = (t == gridDim.x - 1) ? 1u : 0u;
+                unsigned last = 0u;
+                if (a.finish == 7) {
+                    // Tickets in two levels.  Read-modify-writes of one word are served one after the other, about 8 ns
+                    // each, so when all blocks arrive together the last waits for a queue of them.  Each die's blocks
+                    // (block b runs on die b mod 8) draw from a ticket of their own, on a line of its own, and the last of
+                    // a die draws from the common one: eight short queues side by side and one of eight.
+                    const unsigned die = blockIdx.x % kXcds;
+                    const unsigned on_die = (gridDim.x - die + kXcds - 1) / kXcds;
+                    unsigned *leaf = a.leaves + die * 64u;
+                    const unsigned t = __hip_atomic_fetch_add(leaf, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (t == on_die - 1) {
+                        (void)__hip_atomic_exchange(leaf, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const unsigned dies = gridDim.x < (unsigned)kXcds ? gridDim.x : (unsigned)kXcds;
+                        const unsigned r = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        last = (r == dies - 1) ? 1u : 0u;
+                    }
+                } else {
+                    const unsigned t = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    last = (t == gridDim.x - 1) ? 1u : 0u;
+                }
+                is_last = last;
             }
             __syncthreads();
             if (is_last) {
@@ -1222,11 +1260,13 @@ __global__ void fill_zero_words_kernel(unsigned *p, unsigned count)
     if (i < count) p[i] = 0u;
 }
 
-// `count` slots marked empty, and the first `words` words at `zero` cleared, by one block
-__global__ void empty_slots_kernel(u64 *slots, unsigned count, unsigned *zero, unsigned words)
+// `count` slots marked empty, the first `words` words at `zero` cleared, and (if given) the eight tickets of the second
+// level, 256 bytes apart and eight bytes each, by one block
+__global__ void empty_slots_kernel(u64 *slots, unsigned count, unsigned *zero, unsigned words, unsigned *leaves)
 {
     for (unsigned i = threadIdx.x; i < count; i += blockDim.x) slots[i] = kEmptySlot;
     if (threadIdx.x < words) zero[threadIdx.x] = 0u;
+    if (leaves && threadIdx.x < 16u) leaves[(threadIdx.x >> 1) * 64u + (threadIdx.x & 1u)] = 0u;
 }
 
 // Plain 16-byte-per-lane copy of `nvec` vectors: a kernel of exactly known traffic, used to

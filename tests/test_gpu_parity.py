@@ -180,7 +180,7 @@ def test_flat_chain_folds_and_small_grids(dev, variant, max_chain, max_grid):
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("layout", [0, 1, 2])
-@pytest.mark.parametrize("finish", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("finish", [0, 1, 2, 3, 4, 5, 6, 7, 8])
 def test_flat_layouts_and_finishes(dev, variant, layout, finish):
     redux.set_param("layout", layout)
     redux.set_param("finish", finish)
@@ -271,7 +271,7 @@ def test_every_ordered_finish_gives_the_same_bits(dev, variant):
     for n in ((1 << 24) + 12345, 1000):                      # 256 blocks; a single block, which writes its total itself
         x = to_dev(workloads.normal_f16(5, n), dev)
         bits = {}
-        for finish in (2, 1, 4, 6):
+        for finish in (2, 1, 4, 6, 7):
             redux.set_param("finish", finish)
             outs = torch.empty(100, dtype=torch.float32, device=dev)
             for k in range(100):
@@ -280,11 +280,11 @@ def test_every_ordered_finish_gives_the_same_bits(dev, variant):
             got = outs.cpu().numpy().view(np.uint32)
             assert np.all(got == got[0]), finish
             bits[finish] = int(got[0])
-        assert bits[1] == bits[2] == bits[4] == bits[6], (n, bits)
+        assert bits[1] == bits[2] == bits[4] == bits[6] == bits[7], (n, bits)
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
-@pytest.mark.parametrize("finish", [0, 1, 4, 5])
+@pytest.mark.parametrize("finish", [0, 1, 4, 5, 8])
 def test_in_kernel_finish_sees_this_call_not_the_last(dev, variant, finish):
     """Back-to-back calls alternate between two different arrays: a block partial left over from the previous
     call (one that the finishing block read before this call's write had become visible) would give a wrong sum."""
@@ -306,7 +306,8 @@ def test_in_kernel_finish_sees_this_call_not_the_last(dev, variant, finish):
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
-def test_slots_finish_sees_this_call_not_the_last(dev, variant):
+@pytest.mark.parametrize("slots_finish", [6, 7])
+def test_slots_finish_sees_this_call_not_the_last(dev, variant, slots_finish):
     """The finish whose last block takes the partials from slots as they arrive (floating point): calls alternating
     between two arrays, and between grids of different sizes, must give the bits of the two-kernel finish every time --
     a slot left filled by the call before, or one read before it was filled, would show."""
@@ -321,8 +322,8 @@ def test_slots_finish_sees_this_call_not_the_last(dev, variant):
         check_f16(fa, a)
         check_f16(fb, b)
         want = [np.float32(fa).view(np.uint32), np.float32(fb).view(np.uint32)]
-        redux.set_param("finish", 6)
-        assert redux.plan_sum(n, redux.F16, xa.data_ptr(), 256).finish == 6
+        redux.set_param("finish", slots_finish)            # 7: tickets in two levels, the blocks of a die first
+        assert redux.plan_sum(n, redux.F16, xa.data_ptr(), 256).finish == slots_finish
         outs = torch.zeros(200, dtype=torch.float32, device=dev)
         for k in range(200):
             redux.sum(xa if k % 2 == 0 else xb, out=outs[k:k + 1])
@@ -340,16 +341,17 @@ def test_counted_atomic_finish_at_the_extremes_of_int8(dev, variant):
     """The int8 finish that adds block totals and counts blocks in one 64-bit word: totals of either sign, with every
     grid size class, must leave the count in the low bits alone (and the word at zero for the next call)."""
     redux.set_variant(variant)
-    redux.set_param("finish", 5)
-    for n, max_grid, bpc in (((1 << 24) + 3, 16384, 16), ((1 << 24) + 3, 16384, 1), ((1 << 22) + 1, 3, 1), (4097, 16384, 1), (1, 16384, 1)):
-        redux.set_param("max_grid", max_grid)
-        redux.set_param("blocks_per_cu", bpc)
-        for value in (-128, 127, -1):
-            x = torch.full((n,), value, dtype=torch.int8, device=dev)
-            outs = torch.zeros(3, dtype=torch.int64, device=dev)
-            for k in range(3):
-                redux.sum(x, out=outs[k:k + 1])
-            assert outs.cpu().tolist() == [value * n] * 3, (n, max_grid, bpc, value)
+    for finish in (5, 8):                                    # one level; two levels (a word per die, then the common one)
+        redux.set_param("finish", finish)
+        for n, max_grid, bpc in (((1 << 24) + 3, 16384, 16), ((1 << 24) + 3, 16384, 1), ((1 << 22) + 1, 3, 1), ((1 << 22) + 1, 13, 1), (4097, 16384, 1), (1, 16384, 1)):
+            redux.set_param("max_grid", max_grid)
+            redux.set_param("blocks_per_cu", bpc)
+            for value in (-128, 127, -1):
+                x = torch.full((n,), value, dtype=torch.int8, device=dev)
+                outs = torch.zeros(3, dtype=torch.int64, device=dev)
+                for k in range(3):
+                    redux.sum(x, out=outs[k:k + 1])
+                assert outs.cpu().tolist() == [value * n] * 3, (finish, n, max_grid, bpc, value)
 
 
 def test_two_streams_do_not_share_a_workspace(dev):
@@ -802,7 +804,7 @@ def test_randomised_shapes_and_settings(dev):
         redux.set_param("max_grid", int(rng.choice([1, 3, 64, 16384])))
         redux.set_param("max_chain", int(rng.choice([1, 7, 256])))
         redux.set_param("layout", int(rng.integers(0, 3)))
-        redux.set_param("finish", int(rng.integers(-1, 7)))
+        redux.set_param("finish", int(rng.integers(-1, 9)))
         redux.set_param("nontemporal", int(rng.integers(0, 2)))
         off = int(rng.integers(0, 8 if is_f16 else 16))
         if kind == "seg":

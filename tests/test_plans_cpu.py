@@ -44,7 +44,8 @@ def test_flat_plan_invariants(n, dtype, mis, cus, bpc, max_grid, unroll):
     nslab = p.vectors // (256 * p.unroll)
     assert 1 <= p.grid <= min(cus * bpc, max_grid, 16384)
     assert p.grid <= max(nslab, 1)
-    assert p.finish == 5 if dtype == redux.I8 else p.finish in (2, 4, 6) and (p.finish != 6 or p.grid <= 2048)
+    assert p.finish in (5, 8) if dtype == redux.I8 else p.finish in (4, 6, 7) and (p.finish == 4) == (p.grid > 2048)
+    assert (p.finish in (7, 8)) == (2 << 20 < p.vectors * 16 < 256 << 20) or p.finish == 4
     assert 1 <= p.chain <= 256                                       # the default max_chain, possibly lowered for int8
     assert p.kernel == redux.KERNEL_FLAT
 
@@ -55,13 +56,14 @@ def test_flat_plan_defaults_on_mi355x():
     assert (c3.head, c3.tail, c3.vectors) == (0, 1, 134219271)      # the last 16-byte vector holds one element
     c1 = redux.plan_sum(1 << 20, redux.F16, 0, 256)
     assert (c1.unroll, c1.grid, c1.finish) == (8, 64, 6)            # small: few blocks, finishes in the same kernel
-    assert redux.plan_sum(1 << 26, redux.F16, 0, 256).finish == 2   # 128 MiB: all blocks arrive together, a second kernel finishes
+    assert redux.plan_sum(1 << 26, redux.F16, 0, 256).finish == 7   # 128 MiB: all blocks arrive together, so by die first
     assert redux.plan_sum(0, redux.I8, 0, 256).grid == 1
-    for n in (1 << 20, 1 << 26, 1 << 30):                           # int8: block totals are added and counted by one atomic addition
-        assert redux.plan_sum(n, redux.I8, 0, 256).finish == 5
+    for n, f in ((1 << 20, 5), (1 << 26, 8), (1 << 30, 5)):          # int8: block totals are added and counted by one atomic addition (mid sizes: by die first)
+        assert redux.plan_sum(n, redux.I8, 0, 256).finish == f
     assert redux.plan_sum((1 << 40) + 4096, redux.I8, 0, 256).finish == 4   # beyond the 49 bits the counted word gives the sum
-    assert redux.plan_sum(1 << 23, redux.F16, 0, 256).finish == 2             # 16 MiB: the smallest size that takes the second kernel
-    assert redux.plan_sum(1 << 22, redux.F16, 0, 256).finish == 6
+    assert redux.plan_sum(1 << 21, redux.F16, 0, 256).finish == 7             # 4 MiB: 128 blocks arrive together
+    assert redux.plan_sum(1 << 20, redux.F16, 0, 256).finish == 6
+    assert redux.plan_sum(1 << 27, redux.F16, 0, 256).finish == 6             # 256 MiB: they no longer do
 
 
 @settings(max_examples=300, deadline=None)

@@ -47,7 +47,7 @@ def both(x, dtype_code, out_dtype, dev):
 
 
 @pytest.mark.parametrize("variant", ("auto", "mfma", "classic"))
-@pytest.mark.parametrize("finish", (-1, 1, 2, 3, 4, 5, 6))
+@pytest.mark.parametrize("finish", (-1, 1, 2, 3, 4, 5, 6, 7, 8))
 def test_static_matches_redux_sum_two_calls_in_a_row(dev, variant, finish):
     redux.set_variant(variant)
     redux.set_param("finish", finish)
