@@ -23,7 +23,7 @@ Order of events
 `value`            whole-job throughput in GB/s: algorithmic bytes (2 B per binary16 element, 1 B per
                    int8 element) x K / wall time of the K timed calls.
 `roofline`         the reduction kernel against the 8 TB/s HBM3E peak: `achieved` is the same algorithmic bytes over
-                   the average duration of a call in the timed region, by HIP events.  For C3, C4 and C5 a call is
+                   the average duration of a call in the timed region, by HIP events.  For every workload a call is
                    one kernel launch (the block that finishes last adds up the block partials), so this is that
                    kernel's average launch duration plus the gap to the next launch.
 `cpu_baseline`     the CPU oracle (untuned) timed on the same array on this host: all host cores (`value`, `cores`) and
@@ -48,16 +48,16 @@ HBM_PEAK_GBPS = 8000.0
 # FETCH_SIZE + WRITE_SIZE, scaled by what the same counters read for a plain copy of known size, for the HBM bytes).
 # (workload, family actually run): (HBM bytes per launch, kernel, average kernel duration in us, summary).  Absent = not profiled.
 PROFILED = {
-    ('C1', 'classic'): (2245808, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 4.73, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C1', 'mfma'): (2227376, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 4.41, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C2', 'classic'): (134372136, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 19.85, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C2', 'mfma'): (134353576, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 19.42, 'profiles/redux_sum_f16_C1_C2.md'),
-    ('C3', 'classic'): (2147626971, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 289.54, 'profiles/redux_sum_f16_C3.md'),
-    ('C3', 'mfma'): (2147611953, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 289.68, 'profiles/redux_sum_f16_C3.md'),
-    ('C4', 'classic'): (1073855287, 'sum_flat_kernel<I8Classic, 8, true>', 145.61, 'profiles/redux_sum_i8_C4.md'),
-    ('C4', 'mfma'): (1073861442, 'sum_flat_kernel<I8MfmaT<4>, 8, true>', 144.19, 'profiles/redux_sum_i8_C4.md'),
-    ('C5', 'classic'): (537420431, 'sum_segments_tiles_kernel<FloatClassic<0>, 8, true, 0>', 74.77, 'profiles/redux_sum_segmented_f16_C5.md'),
-    ('C5', 'mfma'): (537411143, 'sum_segments_tiles_kernel<FloatMfmaT<0, 1>, 8, true, 1>', 74.50, 'profiles/redux_sum_segmented_f16_C5.md'),
+    ('C1', 'classic'): (2246885, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 4.74, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C1', 'mfma'): (2252389, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 4.59, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C2', 'classic'): (134380556, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 22.28, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C2', 'mfma'): (134386050, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 21.44, 'profiles/redux_sum_f16_C1_C2.md'),
+    ('C3', 'classic'): (2147627295, 'sum_flat_kernel<FloatClassic<0>, 8, true>', 289.42, 'profiles/redux_sum_f16_C3.md'),
+    ('C3', 'mfma'): (2147632757, 'sum_flat_kernel<FloatMfmaT<0, 4>, 8, true>', 288.99, 'profiles/redux_sum_f16_C3.md'),
+    ('C4', 'classic'): (1073852100, 'sum_flat_kernel<I8Classic, 8, true>', 145.72, 'profiles/redux_sum_i8_C4.md'),
+    ('C4', 'mfma'): (1073872601, 'sum_flat_kernel<I8MfmaT<4>, 8, true>', 144.00, 'profiles/redux_sum_i8_C4.md'),
+    ('C5', 'classic'): (537420392, 'sum_segments_tiles_kernel<FloatClassic<0>, 8, true, 0>', 74.63, 'profiles/redux_sum_segmented_f16_C5.md'),
+    ('C5', 'mfma'): (537417381, 'sum_segments_tiles_kernel<FloatMfmaT<0, 1>, 8, true, 1>', 74.48, 'profiles/redux_sum_segmented_f16_C5.md'),
 }
 
 
