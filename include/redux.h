@@ -312,9 +312,9 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               point: totals in slots that read empty between launches, arrivals counted by a ticket
  *                               per segment; int8: one 64-bit atomic addition per piece that adds and counts), 0 = a
  *                               second kernel adds them; same order, same bits.  -1 = the measured best: the same
- *                               kernel for calls of up to 8 MiB and for few pieces per segment (up to 8; int8: up to 32,
- *                               and any number from 256 MiB on), never where a block has a second piece to go on
- *                               to (default -1)
+ *                               kernel wherever there is a block for every piece (a block that goes on to another
+ *                               piece would wait for its ticket first).  Up to 28 segments of 32 or more pieces
+ *                               count their arrivals in two levels, as "finish" 7 and 8 do (default -1)
  *   "compensated"       0/1     redux_sum, binary16, MMA family: the first MMA runs with C = 0 and its row sums are added to the
  *                               running sums with a two-sum on the vector ALU, the lost parts kept in a second
  *                               accumulator (for the precision study: it buys nothing once chains are bounded, and costs

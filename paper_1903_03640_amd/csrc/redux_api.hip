@@ -692,20 +692,26 @@ SegPlan plan_segmented(const Settings &S, u64 nseg, u64 seglen, int dtype, size_
 // Segments cut into pieces: does the same kernel add a segment's piece totals (the last block of the segment to arrive),
 // or a second kernel?  Only the one-block-per-piece kernel can; its slots and tickets cover every shape it is given
 // (pieces <= kMaxGrid, at least two per segment).  Measured, us per call back to back, second kernel / same kernel:
-//   2 x 0.5 ... 4 MiB    8.4 / 5.9 - 7.0 (a launch less, and the call is all launch)
-//   128 x 128 KiB ... 1 MiB (4 pieces each)   9.3 / 6.7 (16 MiB), 9.4 / 8.9, 13.6 / 13.1, 23.5 / 22.7 (128 MiB), level above
-//   2 or 16 x ... (32 - 256 pieces each), 16 - 128 MiB   8.4 / 10.1, 8.9 / 12.3, 13.5 / 16.8, 23.4 / 25.4: the arrivals of a
-//       segment's pieces all at once queue up at its ticket; int8, which has one read-modify-write per piece and no piece
-//       totals to fetch, is level or ahead up to 32 pieces (9.3 / 8.6 ... 24.3 / 22.6) and from 256 MiB on (79.6 / 78.4)
-//   more pieces than blocks (a block goes on to a second piece): 79.6 / 91.8 -- it waits for its ticket first
-bool seg_finish_in_kernel(const Settings &S, const SegPlan &p, int dtype, u64 nseg, u64 seg_bytes)
+//   2 x 0.5 ... 8 MiB (16 - 256 pieces each)       9.2 / 6.3 (a launch less, and the call is all launch)
+//   2 x 16 ... 64 MiB (256 pieces each)            9.2 / 8.9, 13.4 / 13.2, 23.2 / 23.0 with the arrivals counted in two
+//       levels (one level: 8.4 / 10.1 ... 23.4 / 25.4, the 256 arrivals queue up at the segment's ticket)
+//   16 x 0.5 ... 8 MiB                              9.2 / 6.3 - 7.1, 9.2 / 8.8, 13.4 / 13.2, 23.2 / 22.9
+//   128 x 64 KiB ... 1 MiB (2 - 4 pieces each)      9.3 / 6.4 - 6.7, 9.4 / 8.9, 13.5 / 13.0, 23.3 / 22.6
+//   int8: the same or better (one read-modify-write per piece, no piece totals to fetch): 9.7 / 8.0, 14.2 / 12.5, 24.0 / 22.5
+//   more pieces than blocks (a block goes on to another piece, and would wait for its ticket first): 79.6 / 91.8,
+//       256 MiB in 2 x 256 pieces on 256 blocks 41.5 / 42.5
+// Arrivals counted in two levels: nine words per segment on a 256-byte line each fit the 64 KiB of per-segment words for
+// up to 28 segments; worth it from 32 pieces per segment.
+bool seg_two_levels(const SegPlan &p, u64 nseg)
+{
+    return p.kernel == REDUX_KERNEL_BLOCK && p.parts >= 32 && nseg * 9 <= (u64)(kMaxGrid / 2) * sizeof(u64) / 256;
+}
+
+bool seg_finish_in_kernel(const Settings &S, const SegPlan &p, u64 nseg)
 {
     if (p.kernel != REDUX_KERNEL_BLOCK || p.parts <= 1 || S.seg_finish == 0) return false;
     if (S.seg_finish > 0) return true;
-    if (nseg * p.parts > (u64)p.grid) return false;
-    const u64 bytes = nseg * seg_bytes;
-    if (bytes <= ((u64)8 << 20)) return true;
-    return dtype == REDUX_I8 ? (p.parts <= 32 || bytes >= ((u64)256 << 20)) : p.parts <= 8;
+    return nseg * p.parts <= (u64)p.grid;
 }
 
 } // namespace
@@ -970,6 +976,7 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     a.part_len = plan.part_len;
     a.partials = nullptr;
     a.seg_finish = 0;
+    a.seg_two_levels = 0;
     a.slots = nullptr;
     a.tickets = nullptr;
     a.counted = nullptr;
@@ -978,7 +985,8 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
         std::lock_guard<std::mutex> lock(g_mu);
         if ((rc = get_workspace(dev, st, &ws)) != REDUX_OK) return rc;
         a.partials = ws.partials;
-        a.seg_finish = seg_finish_in_kernel(S, plan, dtype, nseg, seglen * es) ? 1 : 0;
+        a.seg_finish = seg_finish_in_kernel(S, plan, nseg) ? 1 : 0;
+        a.seg_two_levels = seg_two_levels(plan, nseg) ? 1 : 0;
         a.slots = ws.slots;
         a.tickets = (unsigned *)ws.counted;
         a.counted = ws.counted;
@@ -1187,7 +1195,7 @@ int redux_plan_sum_segmented(size_t nseg, size_t seglen, int dtype, uintptr_t x_
     plan->kernel = p.kernel;
     plan->unroll = p.unroll;
     plan->grid = p.grid;
-    plan->finish = p.parts > 1 ? (seg_finish_in_kernel(g_set, p, dtype, nseg, seglen * es) ? (dtype == REDUX_I8 ? 5 : 6) : 2) : 0;
+    plan->finish = p.parts > 1 ? (seg_finish_in_kernel(g_set, p, nseg) ? (dtype == REDUX_I8 ? 5 : 6) : 2) : 0;
     plan->parts = p.parts;
     plan->part_len = p.part_len;
     plan->head = 0;

@@ -819,6 +819,10 @@ struct SegArgs {
     // it) and arrivals are counted in tickets[segment]; int8: total and count share the 64-bit word counted[segment].
     // Tickets and counted words are zero before the launch and after it.
     int seg_finish;
+    // 1 = arrivals counted in two levels (a few segments of many pieces): piece p of a segment meets the pieces with the same p mod 8 at
+    // word 1 + p mod 8 of the segment's nine words, the last of each of the eight groups at word 0; every word on a 256-byte
+    // line of its own (read-modify-writes of one line are served one after the other)
+    int seg_two_levels;
     u64 *slots;
     unsigned *tickets;
     u64 *counted;
@@ -1051,18 +1055,48 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
             } else if constexpr (std::is_integral<Total>::value) {
                 // integer totals: one atomic addition per piece adds them up and counts them (sum above bit 15, count below;
                 // at most 4096 pieces per segment); whoever completes the count holds the segment's sum
-                const u64 mine = ((u64)(i64)total << 15) + 1u;
-                const u64 now = __hip_atomic_fetch_add(a.counted + seg, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
-                if ((now & 0x7fffu) == a.parts) {
-                    ((typename F::Out *)a.out)[seg] = (typename F::Out)((i64)now >> 15);
-                    (void)__hip_atomic_exchange(a.counted + seg, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                u64 mine = ((u64)(i64)total << 15) + 1u;
+                u64 *word = a.counted + seg;
+                u64 arrivals = a.parts;
+                bool up = true;
+                if (a.seg_two_levels) {
+                    const u64 group = part % 8u, in_group = (a.parts - group + 7u) / 8u;
+                    u64 *leaf = a.counted + (seg * 9u + 1u + group) * 32u;
+                    const u64 now = __hip_atomic_fetch_add(leaf, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+                    up = (now & 0x7fffu) == in_group;
+                    if (up) {
+                        (void)__hip_atomic_exchange(leaf, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        mine = (now & ~(u64)0x7fffu) + 1u;               // the group's sum, counted as one arrival
+                    }
+                    word = a.counted + seg * 9u * 32u;
+                    arrivals = a.parts < 8u ? a.parts : 8u;
+                }
+                if (up) {
+                    const u64 now = __hip_atomic_fetch_add(word, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+                    if ((now & 0x7fffu) == arrivals) {
+                        ((typename F::Out *)a.out)[seg] = (typename F::Out)((i64)now >> 15);
+                        (void)__hip_atomic_exchange(word, (u64)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
             } else {
                 // the piece total is sent off to its slot and the segment's ticket drawn at once; the last ticket says that all
                 // of the segment's totals are on their way, and fetch_partials reads each slot until it has arrived
                 publish_to_slot(a.slots + piece, total);
-                const unsigned t = __hip_atomic_fetch_add(a.tickets + seg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                is_last = (t == (unsigned)a.parts - 1u) ? 1u : 0u;
+                unsigned last = 0u;
+                if (a.seg_two_levels) {
+                    const unsigned group = (unsigned)(part % 8u), in_group = ((unsigned)a.parts - group + 7u) / 8u;
+                    unsigned *leaf = a.tickets + (seg * 9u + 1u + group) * 64u;
+                    const unsigned t = __hip_atomic_fetch_add(leaf, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (t == in_group - 1u) {
+                        (void)__hip_atomic_exchange(leaf, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const unsigned r = __hip_atomic_fetch_add(a.tickets + seg * 9u * 64u, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        last = (r == ((unsigned)a.parts < 8u ? (unsigned)a.parts : 8u) - 1u) ? 1u : 0u;
+                    }
+                } else {
+                    const unsigned t = __hip_atomic_fetch_add(a.tickets + seg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    last = (t == (unsigned)a.parts - 1u) ? 1u : 0u;
+                }
+                is_last = last;
             }
         }
         __syncthreads();                                   // lds is reused: by the sum of the piece totals, or by the next piece
@@ -1071,7 +1105,7 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
                 const Total total = sum_partials<F, true>(a.slots + seg * a.parts, (unsigned)a.parts, lds);
                 if (tid == 0) {
                     ((typename F::Out *)a.out)[seg] = F::to_out(total);
-                    (void)__hip_atomic_exchange(a.tickets + seg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    (void)__hip_atomic_exchange(a.tickets + (a.seg_two_levels ? seg * 9u * 64u : seg), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
                 __syncthreads();
             }

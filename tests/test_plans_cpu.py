@@ -193,7 +193,7 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
             # piece totals meet in a second kernel (2) or in the same one (5: int8, counted; 6: floating point, slots), and
             # in the same one only if no block has a second piece to go on to
             assert p.finish in ((2, 5) if dtype == redux.I8 else (2, 6))
-            assert p.finish == 2 or nseg * p.parts <= p.grid
+            assert (p.finish != 2) == (nseg * p.parts <= p.grid)
         else:
             assert p.part_len == seglen and p.finish == 0
         assert p.grid <= nseg * p.parts
@@ -280,10 +280,11 @@ def test_segmented_plan_defaults_on_mi355x():
     # 1072 segments of 500000 bytes on 512 blocks would be 2.1 rounds: four pieces each make it 8.4
     cut = redux.plan_sum_segmented(1072, 250000, redux.F16, 0, 256)
     assert (cut.kernel, cut.parts, cut.grid, cut.finish) == (redux.KERNEL_BLOCK, 4, 512, 2) and cut.part_len * 2 >= 65536
-    # where the pieces of a segment meet: in the same kernel for small calls and for few pieces per segment (int8: up to 32),
-    # in a second kernel where many would arrive at one ticket together or a block has a second piece to go on to
-    for shape, want in (((2, 1 << 20, redux.F16), (64, 128, 6)), ((128, 1 << 19, redux.F16), (4, 512, 6)), ((16, 1 << 22, redux.F16), (32, 512, 2)),
-                        ((16, 1 << 23, redux.I8), (32, 512, 5)), ((2, 1 << 26, redux.I8), (256, 512, 2)), ((100, 2621440, redux.F16), (64, 512, 2))):
+    # where the pieces of a segment meet: in the same kernel wherever there is a block for every piece, in a second
+    # kernel where a block has a second piece to go on to
+    for shape, want in (((2, 1 << 20, redux.F16), (64, 128, 6)), ((128, 1 << 19, redux.F16), (4, 512, 6)), ((16, 1 << 22, redux.F16), (32, 512, 6)),
+                        ((16, 1 << 23, redux.I8), (32, 512, 5)), ((2, 1 << 26, redux.I8), (256, 512, 5)), ((100, 2621440, redux.F16), (64, 512, 2)),
+                        ((2, 1 << 27, redux.F16), (256, 256, 2))):
         q = redux.plan_sum_segmented(shape[0], shape[1], shape[2], 0, 256)
         assert (q.kernel, q.parts, q.grid, q.finish) == (redux.KERNEL_BLOCK,) + want, (shape, q.parts, q.grid, q.finish)
     redux.set_param("seg_finish", 0)
