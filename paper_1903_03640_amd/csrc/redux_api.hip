@@ -413,7 +413,7 @@ FlatPlan plan_flat(const Settings &S, u64 nvec, int cus, int dtype)
     // How the block totals meet (all in the same kernel; us per whole call, back to back, binary16 / int8):
     //   floating point: every block sends its partial to a slot and draws a ticket, the last one adds the slots (finish 6);
     //   int8: one atomic addition per block adds its total to a word and counts it (finish 5).
-    //   Read-modify-writes of one word are served one after the other, about 8 ns each.  From 4 to 128 MiB all blocks arrive
+    //   Read-modify-writes of one line of memory are served one after the other, about 8 ns each.  From 4 to 128 MiB all blocks arrive
     //   within a microsecond and the last waits for a queue of 256, so there the blocks of a die meet at the die's own word
     //   first and the eight dies at the common one (finish 7 / 8): 8 MiB 5.2 / 4.5 against 7.1 / 6.6 in one level (and
     //   6.4 - 7.0 with a second one-block kernel, finish 2), 32 MiB 8.5 / 7.6 against 10.2 / 9.5 (8.8), 128 MiB 22.4 / 21.5

@@ -724,10 +724,11 @@ __global__ void __launch_bounds__(kBlock) sum_flat_kernel(FlatArgs a)
                 publish_to_slot(a.slots + blockIdx.x, (lds[0] + lds[1]) + (lds[2] + lds[3]));
                 unsigned last = 0u;
                 if (a.finish == 7) {
-                    // Tickets in two levels.  Read-modify-writes of one word are served one after the other, about 8 ns
-                    // each, so when all blocks arrive together the last waits for a queue of them.  Each die's blocks
-                    // (block b runs on die b mod 8) draw from a ticket of their own, on a line of its own, and the last of
-                    // a die draws from the common one: eight short queues side by side and one of eight.
+                    // Tickets in two levels.  Read-modify-writes of one line of memory are served one after the other,
+                    // about 8 ns each, so when all blocks arrive together the last waits for a queue of them.  Each die's
+                    // blocks (block b runs on die b mod 8) draw from a ticket of their own, on a line of its own (eight
+                    // tickets next to each other gain nothing), and the last of a die draws from the common one: eight
+                    // short queues side by side and one of eight.
                     const unsigned die = blockIdx.x % kXcds;
                     const unsigned on_die = (gridDim.x - die + kXcds - 1) / kXcds;
                     unsigned *leaf = a.leaves + die * 64u;
@@ -821,7 +822,7 @@ struct SegArgs {
     int seg_finish;
     // 1 = arrivals counted in two levels (a few segments of many pieces): piece p of a segment meets the pieces with the same p mod 8 at
     // word 1 + p mod 8 of the segment's nine words, the last of each of the eight groups at word 0; every word on a 256-byte
-    // line of its own (read-modify-writes of one line are served one after the other)
+    // line of its own (read-modify-writes of one line of memory are served one after the other)
     int seg_two_levels;
     u64 *slots;
     unsigned *tickets;
