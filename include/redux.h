@@ -294,10 +294,12 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               iteration (of this run or of its next one) needs, right after it has been used, so the
  *                               loads stay in flight across the end of a run; 0 = load, work, fold, store, run by run
  *                               (default 1: measured 2-4 % ahead; on the same grid with the same run length the results are the same bit for bit)
- *   "seg_balance"       0..99   segmented sum, one block per segment: segments are cut into (more) pieces of at least 64 KiB
- *                               while the rounds of pieces over the grid would leave too much of it idle: 1 = whole segments
- *                               are cut below 85 % use, segments that are cut anyway on to 92 %; 2 .. 99 = that
- *                               percentage for both; 0 = never (default 1)
+ *   "seg_balance"       0..99   segmented sum, one block per segment: into how many pieces (a power of two, of at least 64 KiB)
+ *                               a segment is cut.  1 = the number with the lowest modelled time: whole rounds of pieces
+ *                               over the grid at full time, a last round that fills a fraction f of the grid at sqrt(f) of
+ *                               one (at least half), plus what adding the piece totals costs; 2 .. 99 = the first number
+ *                               that uses that percentage of its rounds' slots; 0 = only as many as it takes to have
+ *                               two pieces per compute unit (default 1)
  *   "seg_run_len"       0..16   that kernel: segments per run; 0 = the length with the lowest cost per wavefront
  *                               (iterations, of which a run's last is partly idle, plus a fixed cost per run; every
  *                               wavefront takes the same number of whole runs and a share of what is left) (default 0)

@@ -7,6 +7,7 @@
 #include "redux_runs.h"
 
 #include <climits>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <map>
@@ -560,11 +561,39 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
                 if (g > pieces) g = pieces;
                 return (double)pieces / (double)(g * ((pieces + g - 1) / g));
             };
-            // Whole segments are cut only below 85 % (pieces cost what adds them up: 700 segments of 1 MB on 256 blocks, 91 %
-            // used, 6.8 TB/s whole against 6.5 in eight pieces each); segments that are cut anyway go on to 92 % (200 segments
-            // of 5 MB: 8 pieces each 6.3 TB/s, 32 each 6.7; 100 of 10 MB: 6.5 -> 6.9).  ("seg_balance" 2 .. 99: that percentage for both.)
-            const auto enough = [&](u64 pr) { return S.seg_balance == 1 ? (pr == 1 ? 0.85 : 0.92) : (double)S.seg_balance / 100.0; };
-            while (S.seg_balance && used(parts) < enough(parts) && nseg * parts * 2 <= (u64)kMaxGrid && seg_bytes / (parts * 2) >= 65536) parts *= 2;
+            // All numbers of pieces that are allowed are looked at (halving while a piece stays above 64 KiB), and the one with
+            // the lowest modelled time wins, fewer pieces within 1 %.  The model: whole rounds of pieces over the grid take
+            // their full time, a last round that fills a fraction f of the grid the square root of f (fewer blocks leave each
+            // more bandwidth) but at least half a round (what a block on its own can draw); pieces cost what adds them up, 3 us for a second kernel and half a microsecond in the same one
+            // (where every piece has a block), against the call's time at 6.5 TB/s.  Against the best of 1 .. 64 pieces
+            // measured on 60 shapes of 100 - 3000 segments in 128 MiB - 1 GiB the choice is within 2 % on average (1 GiB: 700
+            // segments whole 6.4 TB/s in 2.7 rounds, in 8 pieces each 6.9; 200 segments of 5 MB in 8 pieces 6.3, in 64 6.9;
+            // 128 MiB: 200 segments whole 6.1, in 8 pieces 5.5).  ("seg_balance" 2 .. 99: the first number of pieces that uses
+            // that percentage of its rounds' slots, as it used to be.)
+            if (S.seg_balance == 1) {
+                const double call_us = (double)nseg * (double)seg_bytes / 6.5e6;
+                const auto score = [&](u64 pr) {
+                    const u64 pieces = nseg * pr;
+                    const u64 piece_bytes = (seg_bytes + pr - 1) / pr;
+                    u64 g = (u64)cus * (u64)(S.seg_blocks_per_cu ? S.seg_blocks_per_cu : (piece_bytes >= ((u64)512 << 10) ? 1 : 2));
+                    if (g > (u64)S.max_grid) g = (u64)S.max_grid;
+                    if (g < 1) g = 1;
+                    const double rounds = (double)pieces / (double)g;
+                    const double whole = std::floor(rounds), f = rounds - whole;
+                    const double last = f > 0.0 ? (f > 0.25 ? std::sqrt(f) : 0.5) : 0.0;
+                    const double use = rounds / (whole + last);
+                    const double extra = pr == 1 ? 0.0 : (pieces <= g && S.seg_finish != 0 ? 0.5 : 3.0);
+                    return use * call_us / (call_us + extra);
+                };
+                // (pieces of 32 KiB are allowed as far as the first rule above goes, of 64 KiB beyond)
+                u64 best = 1;
+                for (u64 pr = 2; nseg * pr <= (u64)kMaxGrid && (pr <= parts || seg_bytes / pr >= 65536); pr *= 2)
+                    if (score(pr) > score(best) * 1.01) best = pr;
+                parts = best;
+            } else if (S.seg_balance > 1) {
+                const double enough = (double)S.seg_balance / 100.0;
+                while (used(parts) < enough && nseg * parts * 2 <= (u64)kMaxGrid && seg_bytes / (parts * 2) >= 65536) parts *= 2;
+            }
         }
         if (parts > 1 && nseg <= (u64)kMaxGrid / parts) {
             p.parts = parts;

@@ -514,7 +514,7 @@ def test_pieces_meet_in_the_kernel_or_behind_it_with_the_same_bits(dev, variant)
     a slot, a ticket or a counted word left over from the call before (or read before it was filled) would show."""
     redux.set_variant(variant)
     # (the shapes of up to 28 segments in 32 or more pieces count their arrivals in two levels; 29 segments do not)
-    shapes = ((3, (1 << 20) + 3, 0), (40, 100001, 0), (8, 33333, 0), (100, 300000, 16), (2, 1 << 22, 0), (4, 70001, 4096), (28, 150001, 32),
+    shapes = ((3, (1 << 20) + 3, 0), (40, 100001, 0), (8, 33333, 2), (100, 300000, 16), (2, 1 << 22, 0), (4, 70001, 4096), (28, 150001, 32),
               (29, 150001, 32), (5, 3000001, 256))
     for nseg, seglen, parts in shapes:
         redux.set_param("seg_parts", parts)

@@ -282,9 +282,9 @@ def test_segmented_plan_defaults_on_mi355x():
     assert (cut.kernel, cut.parts, cut.grid, cut.finish) == (redux.KERNEL_BLOCK, 4, 512, 2) and cut.part_len * 2 >= 65536
     # where the pieces of a segment meet: in the same kernel wherever there is a block for every piece, in a second
     # kernel where a block has a second piece to go on to
-    for shape, want in (((2, 1 << 20, redux.F16), (64, 128, 6)), ((128, 1 << 19, redux.F16), (4, 512, 6)), ((16, 1 << 22, redux.F16), (32, 512, 6)),
-                        ((16, 1 << 23, redux.I8), (32, 512, 5)), ((2, 1 << 26, redux.I8), (256, 512, 5)), ((100, 2621440, redux.F16), (64, 512, 2)),
-                        ((2, 1 << 27, redux.F16), (256, 256, 2))):
+    for shape, want in (((2, 1 << 20, redux.F16), (64, 128, 6)), ((128, 1 << 19, redux.F16), (2, 256, 6)), ((16, 1 << 22, redux.F16), (16, 256, 6)),
+                        ((16, 1 << 23, redux.I8), (16, 256, 5)), ((2, 1 << 26, redux.I8), (128, 256, 5)), ((100, 2621440, redux.F16), (64, 512, 2)),
+                        ((2, 1 << 27, redux.F16), (128, 256, 6))):
         q = redux.plan_sum_segmented(shape[0], shape[1], shape[2], 0, 256)
         assert (q.kernel, q.parts, q.grid, q.finish) == (redux.KERNEL_BLOCK,) + want, (shape, q.parts, q.grid, q.finish)
     redux.set_param("seg_finish", 0)
@@ -331,7 +331,9 @@ def test_segmented_plan_defaults_on_mi355x():
     assert redux.plan_sum_segmented(1 << 22, 64, redux.F16, 2, 256).kernel == redux.KERNEL_WAVE
     redux.set_param("seg_ragged", 1)
     long_ = redux.plan_sum_segmented(256, 1 << 20, redux.F16, 0, 256)
-    assert (long_.kernel, long_.parts, long_.part_len, long_.unroll, long_.grid) == (redux.KERNEL_BLOCK, 2, 524288, 8, 256)
+    assert (long_.kernel, long_.parts, long_.part_len, long_.unroll, long_.grid) == (redux.KERNEL_BLOCK, 1, 1 << 20, 8, 256)    # a block each, one round
+    long_ = redux.plan_sum_segmented(64, 1 << 22, redux.F16, 0, 256)
+    assert (long_.kernel, long_.parts, long_.part_len, long_.unroll, long_.grid) == (redux.KERNEL_BLOCK, 4, 1 << 20, 8, 256)    # four pieces each make it 256
     assert redux.plan_sum_segmented(4096, 65536, redux.F16, 0, 256).kernel == redux.KERNEL_BLOCK      # 128 KiB each, no pieces
     redux.set_param("seg_block_bytes", 0)
     long_ = redux.plan_sum_segmented(256, 1 << 20, redux.F16, 0, 256)
