@@ -307,7 +307,7 @@ int redux_resolved_variant(int dtype, int segmented);
  *                               been consumed, 0 = plain load-then-work loop, -1 = the measured best for the shape (default -1)
  *   "seg_tiles"         0/1     segmented sum: 16-byte aligned segments of exactly 1, 2, 4 or 8 KiB, at least
  *                               four per compute unit, take the pipelined one-wavefront-per-segment kernel (default 1)
- *   "seg_parts"         0,1,2,4,...,4096  segmented sum: pieces a long segment is cut into; 0 = from the
+ *   "seg_parts"         0..4096 segmented sum: pieces a long segment is cut into; 0 = from the
  *                               shape (default 0); ignored if nseg * pieces exceeds the workspace (16384)
  *   "seg_finish"        -1,0,1  segmented sum, long segments cut into pieces, one block per piece: 1 = the block of a
  *                               segment that arrives last adds the segment's piece totals in the same kernel (floating

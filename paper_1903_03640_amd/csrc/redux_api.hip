@@ -589,6 +589,11 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
                 u64 best = 1;
                 for (u64 pr = 2; nseg * pr <= (u64)kMaxGrid && (pr <= parts || seg_bytes / pr >= 65536); pr *= 2)
                     if (score(pr) > score(best) * 1.01) best = pr;
+                // ... and the numbers that make exactly one round of it (a handful of segments need not be a power of two)
+                for (u64 per_cu = 1; per_cu <= 2; ++per_cu) {
+                    const u64 pr = (u64)cus * per_cu / nseg;
+                    if (pr >= 2 && nseg * pr <= (u64)kMaxGrid && seg_bytes / pr >= 65536 && score(pr) > score(best) * 1.01) best = pr;
+                }
                 parts = best;
             } else if (S.seg_balance > 1) {
                 const double enough = (double)S.seg_balance / 100.0;
@@ -1006,6 +1011,7 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
     a.partials = nullptr;
     a.seg_finish = 0;
     a.seg_two_levels = 0;
+    a.seg_word_stride = 1;
     a.slots = nullptr;
     a.tickets = nullptr;
     a.counted = nullptr;
@@ -1016,6 +1022,7 @@ int redux_sum_segmented(const void *x, size_t nseg, size_t seglen, int dtype, vo
         a.partials = ws.partials;
         a.seg_finish = seg_finish_in_kernel(S, plan, nseg) ? 1 : 0;
         a.seg_two_levels = seg_two_levels(plan, nseg) ? 1 : 0;
+        a.seg_word_stride = nseg <= (u64)(kMaxGrid / 2) * sizeof(u64) / 256 ? 32u : 1u;      // a line per segment while they fit (256 segments)
         a.slots = ws.slots;
         a.tickets = (unsigned *)ws.counted;
         a.counted = ws.counted;
@@ -1291,7 +1298,7 @@ int redux_set_param(const char *name, long value)
     long lo = 0, hi = 0;
     long *slot = param_slot(name, &lo, &hi);
     if (!slot || value < lo || value > hi) return REDUX_ERR_PARAM;
-    if ((slot == &g_set.unroll || slot == &g_set.seg_parts || slot == &g_set.lit_unroll) && (value & (value - 1)) != 0)
+    if ((slot == &g_set.unroll || slot == &g_set.lit_unroll) && (value & (value - 1)) != 0)
         return REDUX_ERR_PARAM;   // 0 or a power of two
     if (slot == &g_set.lit_m && value != 4 && value != 16 && value != 32) return REDUX_ERR_PARAM;
     *slot = value;

@@ -824,6 +824,8 @@ struct SegArgs {
     // word 1 + p mod 8 of the segment's nine words, the last of each of the eight groups at word 0; every word on a 256-byte
     // line of its own (read-modify-writes of one line of memory are served one after the other)
     int seg_two_levels;
+    unsigned seg_word_stride;   // one level: the words of two segments are this many 8-byte words apart (32 = a 256-byte line each, so
+                                // that the arrivals of different segments do not queue up behind each other; 1 where there are too many)
     u64 *slots;
     unsigned *tickets;
     u64 *counted;
@@ -1057,7 +1059,7 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
                 // integer totals: one atomic addition per piece adds them up and counts them (sum above bit 15, count below;
                 // at most 4096 pieces per segment); whoever completes the count holds the segment's sum
                 u64 mine = ((u64)(i64)total << 15) + 1u;
-                u64 *word = a.counted + seg;
+                u64 *word = a.counted + seg * a.seg_word_stride;
                 u64 arrivals = a.parts;
                 bool up = true;
                 if (a.seg_two_levels) {
@@ -1094,7 +1096,7 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
                         last = (r == ((unsigned)a.parts < 8u ? (unsigned)a.parts : 8u) - 1u) ? 1u : 0u;
                     }
                 } else {
-                    const unsigned t = __hip_atomic_fetch_add(a.tickets + seg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const unsigned t = __hip_atomic_fetch_add(a.tickets + seg * a.seg_word_stride * 2u, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     last = (t == (unsigned)a.parts - 1u) ? 1u : 0u;
                 }
                 is_last = last;
@@ -1106,7 +1108,7 @@ __global__ void __launch_bounds__(kBlock) sum_segments_block_kernel(SegArgs a)
                 const Total total = sum_partials<F, true>(a.slots + seg * a.parts, (unsigned)a.parts, lds);
                 if (tid == 0) {
                     ((typename F::Out *)a.out)[seg] = F::to_out(total);
-                    (void)__hip_atomic_exchange(a.tickets + (a.seg_two_levels ? seg * 9u * 64u : seg), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    (void)__hip_atomic_exchange(a.tickets + (a.seg_two_levels ? seg * 9u * 64u : seg * a.seg_word_stride * 2u), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
                 __syncthreads();
             }

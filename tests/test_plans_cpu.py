@@ -187,7 +187,9 @@ def test_segmented_plan_invariants(nseg, seglen, dtype, aligned, cus, seg_parts,
         assert p.parts == 1 and p.grid <= -(-nseg // 4)
     elif p.kernel == redux.KERNEL_BLOCK:
         assert block_bytes and seglen * es >= block_bytes and p.unroll in (1, 2, 4, 8)
-        assert p.parts & (p.parts - 1) == 0 and p.parts * p.part_len >= seglen
+        # pieces per segment: a power of two, or what makes exactly one round over one or two blocks per compute unit
+        assert p.parts & (p.parts - 1) == 0 or (seg_parts == 0 and p.parts in (cus // nseg, 2 * cus // nseg))
+        assert p.parts * p.part_len >= seglen
         if p.parts > 1:
             assert nseg * p.parts <= 16384 and p.part_len % 512 == 0
             # piece totals meet in a second kernel (2) or in the same one (5: int8, counted; 6: floating point, slots), and
