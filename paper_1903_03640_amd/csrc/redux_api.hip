@@ -591,7 +591,9 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
                     if (score(pr) > score(best) * 1.01) best = pr;
                 // ... and the numbers that make exactly one round of it (a handful of segments need not be a power of two)
                 for (u64 per_cu = 1; per_cu <= 2; ++per_cu) {
-                    const u64 pr = (u64)cus * per_cu / nseg;
+                    u64 pr = (u64)cus * per_cu / nseg;
+                    // (measured: 234, 238, 242, 246 or 250 blocks -- twice an odd number -- run 5 % behind 240, 243, 245, 247, 252, 253 or 255)
+                    while (pr >= 2 && (nseg * pr) % 4 == 2) --pr;
                     if (pr >= 2 && nseg * pr <= (u64)kMaxGrid && seg_bytes / pr >= 65536 && score(pr) > score(best) * 1.01) best = pr;
                 }
                 parts = best;
