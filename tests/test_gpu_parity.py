@@ -661,7 +661,9 @@ def test_graph_replay_matches_eager(dev):
     nshort = 20000                                            # the same array as short aligned (128 B) and ragged (200 B) segments
     outs = [torch.zeros(1, dtype=torch.float32, device=dev), torch.zeros(nseg, dtype=torch.float32, device=dev),
             torch.zeros(1, dtype=torch.int64, device=dev), torch.zeros(1, dtype=torch.float32, device=dev),
-            torch.zeros(nshort, dtype=torch.float32, device=dev), torch.zeros(nshort, dtype=torch.float32, device=dev)]
+            torch.zeros(nshort, dtype=torch.float32, device=dev), torch.zeros(nshort, dtype=torch.float32, device=dev),
+            torch.zeros(3, dtype=torch.float32, device=dev), torch.zeros(1, dtype=torch.int64, device=dev)]
+    xi8 = to_dev(workloads.uniform_i8(64, (1 << 23) + 5), dev)      # all blocks arrive together: counted in two levels
 
     def run_all():
         redux.sum(x, out=outs[0])
@@ -670,6 +672,8 @@ def test_graph_replay_matches_eager(dev):
         redux.sum_multipass(x, out=outs[3])
         redux.sum_segmented(x[:nshort * 64], nshort, 64, out=outs[4])
         redux.sum_segmented(x[:nshort * 100], nshort, 100, out=outs[5])
+        redux.sum_segmented(x[:3 * 700001], 3, 700001, out=outs[6])      # pieces that meet in the same kernel (slots, tickets)
+        redux.sum(xi8, out=outs[7])
 
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
@@ -690,6 +694,9 @@ def test_graph_replay_matches_eager(dev):
             assert torch.equal(got, want), rep
     check_f16(eager[0].item(), x.cpu().numpy())
     assert eager[2].item() == oracle.sum_i8(xi.cpu().numpy())[0]
+    assert eager[7].item() == oracle.sum_i8(xi8.cpu().numpy())[0]
+    want, want_abs = oracle.sum_segmented_f16(x[:3 * 700001].cpu().numpy(), 3, 700001)
+    assert np.all(np.abs(eager[6].cpu().numpy().astype(np.float64) - want) <= TOL * want_abs)
 
 
 def test_graph_survives_growth_of_the_level_buffers(dev):
