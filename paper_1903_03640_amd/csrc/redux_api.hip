@@ -88,10 +88,12 @@ int hip_fail(hipError_t e, int status = REDUX_ERR_HIP)
 struct Workspace {
     u64 *partials = nullptr;    // kMaxGrid slots
     unsigned *ticket = nullptr; // behind the partials, on its own 256-byte line
-    u64 *slots = nullptr;       // behind the ticket: kMaxGrid slots that read empty between launches (flat sum, finish 6: the
+    u64 *slots = nullptr;       // behind the ticket: kMaxGrid slots that read empty between launches (flat sum, finish 6 and 7: the
                                 // first kWorkspaceSlots; segments cut into pieces that finish in the kernel: one per piece)
-    u64 *counted = nullptr;     // behind the slots: kMaxGrid / 2 words that read zero between launches, one per segment that is
-                                // cut into pieces (floating point: its ticket; int8: its counted sum)
+    u64 *counted = nullptr;     // behind the slots: 64 KiB of words that read zero between launches.  Flat sum, finish 7 and 8: the
+                                // eight second-level tickets, a 256-byte line each.  Segments cut into pieces: a word per segment
+                                // (floating point: its ticket; int8: its counted sum), a line apart while they fit; nine lines per
+                                // segment where the arrivals are counted in two levels
 };
 constexpr unsigned kWorkspaceSlots = 2048;
 constexpr size_t kTicketOffset = (size_t)kMaxGrid * sizeof(u64);

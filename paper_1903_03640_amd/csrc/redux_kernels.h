@@ -549,7 +549,8 @@ struct FlatArgs {
     int layout;         // which slabs a block takes (see slab_schedule)
     int finish;         // 0/1/4: the last block to arrive sums the partials; 2: a second kernel does; 3: atomic additions;
                         // 5: atomic additions that count the blocks as well (integers only); 6: as 4, but nobody waits
-                        // for its partial to arrive: the last block does, slot by slot (floating point only)
+                        // for its partial to arrive: the last block does, slot by slot (floating point only); 7, 8: as 6
+                        // and 5, the arrivals counted in two levels (by accelerator die, then device-wide)
     unsigned stagger;   // start of wavefront w delayed by w x stagger x 64 cycles (long runs only)
     unsigned pause;     // every loop iteration ends with this many 64-cycle sleeps
 };
