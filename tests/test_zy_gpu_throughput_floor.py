@@ -81,6 +81,9 @@ CASES = [
     ("classic", torch.float16, 32768, 1, redux.KERNEL_BLOCK, 6800),
     ("mfma", torch.float16, 100000, 0, redux.KERNEL_BLOCK, 6700),     # three whole passes and a rest, loaded ahead
     ("mfma", torch.float16, 2000000, 0, redux.KERNEL_BLOCK, 6400),    # 268 segments: cut into pieces so that the rounds fill
+    ("mfma", torch.float16, 1 << 20, 0, redux.KERNEL_BLOCK, 7050),    # 511 segments, whole, one block each
+    ("mfma", torch.float16, 8 << 20, 0, redux.KERNEL_BLOCK, 6950),    # 63 segments in four pieces each, one round, added up in the same kernel
+    ("classic", torch.float16, 64 << 20, 1, redux.KERNEL_BLOCK, 6600),  # 7 segments in 36 pieces each, arrivals counted in two levels
 ]
 
 
