@@ -551,9 +551,9 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
         if (S.seg_parts > 0) parts = (u64)S.seg_parts;
         else {
             while (nseg * parts < want_blocks && nseg * parts * 2 <= (u64)kMaxGrid && seg_bytes / (parts * 2) >= 32768) parts *= 2;
-            // Blocks take pieces in rounds, and a last round that is only partly filled leaves the rest of the chip idle
-            // (measured: 1073 segments of 500000 bytes on 512 blocks, 2.1 rounds, 6.1 TB/s against 6.9 for a whole number
-            // of rounds): pieces are halved while too few of the rounds' slots are used and a piece stays above 64 KiB.
+            // (that is the number "seg_balance" = 0 keeps.)  Blocks take pieces in rounds, and a last round that is only partly
+            // filled leaves the rest of the chip idle (measured: 1073 segments of 500000 bytes on 512 blocks, 2.1 rounds,
+            // 6.1 TB/s against 6.9 for a whole number of rounds).  `used`: the share of the rounds' slots that hold a piece.
             const auto used = [&](u64 pr) {
                 const u64 pieces = nseg * pr;
                 const u64 piece_bytes = (seg_bytes + pr - 1) / pr;
@@ -566,9 +566,10 @@ SegPlan plan_segmented_shape(const Settings &S, u64 nseg, u64 seglen, int dtype,
             // All numbers of pieces that are allowed are looked at (halving while a piece stays above 64 KiB), and the one with
             // the lowest modelled time wins, fewer pieces within 1 %.  The model: whole rounds of pieces over the grid take
             // their full time, a last round that fills a fraction f of the grid the square root of f (fewer blocks leave each
-            // more bandwidth) but at least half a round (what a block on its own can draw); pieces cost what adds them up, 3 us for a second kernel and half a microsecond in the same one
-            // (where every piece has a block), against the call's time at 6.5 TB/s.  Against the best of 1 .. 64 pieces
-            // measured on 60 shapes of 100 - 3000 segments in 128 MiB - 1 GiB the choice is within 2 % on average (1 GiB: 700
+            // more bandwidth) but at least half a round (what a block on its own can draw); pieces cost what adds them up,
+            // 3 us for a second kernel and half a microsecond in the same one (where every piece has a block), against the
+            // call's time at 6.5 TB/s.  Against the best of 1 .. 128 pieces measured on 60 shapes of 100 - 3000 segments
+            // in 128 MiB - 1 GiB the choice is within 1 % on average and 7 % at worst (1 GiB: 700
             // segments whole 6.4 TB/s in 2.7 rounds, in 8 pieces each 6.9; 200 segments of 5 MB in 8 pieces 6.3, in 64 6.9;
             // 128 MiB: 200 segments whole 6.1, in 8 pieces 5.5).  ("seg_balance" 2 .. 99: the first number of pieces that uses
             // that percentage of its rounds' slots, as it used to be.)
